@@ -1,0 +1,189 @@
+/*
+ * cwl.h -- C ABI of the ChunkWise LoRA hot path for AMD MI355X (gfx950).
+ *
+ * The four calls follow the pipeline of arxiv 2601.21109, Sec. III (A: token complexity
+ * estimator, B: adaptive chunker, C: per-chunk rank & scale selector, D: boundary-safe composer
+ * on the LoRA projection):
+ *
+ *      cwl_score_tokens  ->  cwl_partition_chunks  ->  cwl_select_ranks  ->  cwl_chunkwise_lora_linear
+ *
+ * General rules
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - The caller owns every buffer.  The library never allocates, frees or synchronises; every
+ *     call only enqueues kernels on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  Scratch memory comes in through the `workspace` arguments, sized by the matching
+ *     *_workspace_bytes() query; workspaces must be 256-byte aligned.
+ *   - All matrices are row-major.  Leading dimensions are in elements.
+ *   - Argument errors are detected on the host before anything is launched and returned
+ *     synchronously.  Data-dependent conditions are reported through a device status word.
+ *   - Token rows, chunk indices and sequence offsets are 32-bit: n_rows < 2^31.
+ *   - Results are deterministic: the same inputs give bitwise identical outputs.
+ */
+#ifndef CWL_H
+#define CWL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CWL_OK = 0,
+    CWL_ERR_NULL = 1,          /* a required pointer is NULL                                  */
+    CWL_ERR_INVALID_ARG = 2,   /* a size, stride, ladder or threshold is out of range         */
+    CWL_ERR_INFEASIBLE = 3,    /* l_max < 2*l_min - 1: the length bounds cannot always be met */
+    CWL_ERR_CAPACITY = 4,      /* a caller-provided buffer or workspace is too small          */
+    CWL_ERR_UNSUPPORTED = 5,   /* shape / dtype combination the kernels do not cover          */
+    CWL_ERR_DEVICE = 6         /* the HIP runtime refused a launch                            */
+} cwl_status;
+
+typedef enum { CWL_F32 = 0, CWL_BF16 = 1 } cwl_dtype;
+
+/* Bits of the device status word written by cwl_partition_chunks. */
+#define CWL_STATUS_CAPACITY 1u     /* more chunks than `cap`; only the first cap were written  */
+#define CWL_STATUS_NAN_SCORE 2u    /* a NaN score was met and scored as 0                      */
+#define CWL_STATUS_BAD_OFFSETS 4u  /* seq_offsets not non-decreasing within [0, n_rows]        */
+
+#define CWL_MAX_LADDER 16          /* largest K (rungs of the rank ladder)                     */
+#define CWL_MAX_RANK 256           /* largest r_max                                            */
+
+const char* cwl_status_string(cwl_status s);   /* static string, never NULL */
+int32_t cwl_abi_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_score_tokens -- per-token difficulty score (Sec. III-A, signal (i); Sec. IV-A):
+ * the entropy, in nats, of the next-token distribution softmax(logits[t, :]).
+ *
+ *   logits      [n_rows, vocab], element type `dt`, row t starts at logits + t*row_stride
+ *   row_stride  in elements, >= vocab
+ *   entropy     [n_rows] fp32, written
+ *
+ * Accumulation is fp32.  A logit of -inf has probability 0; a row holding NaN or +inf, or made
+ * of -inf only, scores NaN.  n_rows == 0 is a no-op.  vocab must be >= 1.
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_score_tokens(const void* logits, cwl_dtype dt, int64_t n_rows, int64_t vocab,
+                            int64_t row_stride, float* entropy, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_partition_chunks -- adaptive chunker (Sec. III-B, Sec. IV-B).
+ *
+ * Scores are first turned into Q10 fixed-point integers q = floor(h*1024 + 0.5) (fp32; NaN and
+ * negatives -> 0, clamped to 2^20) so that every later decision is an integer one.  Each
+ * sequence is then cut greedily, left to right: a chunk opened at p closes at the first end e
+ * (chunk = [p, e)), p+l_min <= e <= p+l_max, that leaves either no tail or a tail of at least
+ * l_min tokens, and at which, with S = sum of q over the chunk and n = e-p,
+ *      S >= theta_q*n          (the chunk's mean reached the average-complexity threshold), or
+ *      q[e] >= theta_q         (the next token is itself hard and opens a new chunk), or
+ *      |q[e]*n - S| > delta_q*n (the next token leaves the chunk's regime);
+ * if none fires, at the last such end.  A sequence shorter than l_min becomes one chunk.  So
+ * hard spans are cut every l_min tokens and easy spans grow to l_max.
+ *
+ *   entropy        [n_rows] fp32 scores
+ *   seq_offsets    [n_seqs+1] first row of each sequence; seq_offsets[n_seqs] == n_rows
+ *   p              host; 1 <= l_min <= l_max, l_max >= 2*l_min-1 (else CWL_ERR_INFEASIBLE);
+ *                  theta_hard / delta_dev in nats, +INF disables the test
+ *   chunk_offsets  [n_seqs+1] written: index of the first chunk of each sequence (CSR)
+ *   chunk_start    [cap] written: first global row of the chunk
+ *   chunk_len      [cap] written
+ *   chunk_sum      [cap] written: sum of q over the chunk (int64)
+ *   cap            capacity of the three chunk arrays; n_rows/l_min + n_seqs always suffices
+ *   status_word    one int32, written: 0 or an OR of CWL_STATUS_* bits
+ *   workspace      >= cwl_partition_workspace_bytes(n_rows, n_seqs, p) bytes
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t l_min, l_max;
+    float theta_hard;
+    float delta_dev;
+} cwl_chunk_params;
+
+size_t cwl_partition_workspace_bytes(int64_t n_rows, int32_t n_seqs, const cwl_chunk_params* p);
+
+cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows, const int32_t* seq_offsets,
+                                int32_t n_seqs, const cwl_chunk_params* p /*host*/,
+                                int32_t* chunk_offsets, int32_t* chunk_start, int32_t* chunk_len,
+                                int64_t* chunk_sum, int32_t cap, int32_t* status_word,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_select_ranks -- per-chunk rung of the rank ladder (Sec. III-C; Sec. IV-C, the rule-based
+ * percentile mapping): rank_idx[c] = #{ j : chunk_sum[c] >= tau_q[j] * chunk_len[c] }, where
+ * tau_q[j] is thresholds[j] quantised like the scores.  A mean exactly on a threshold goes up.
+ *
+ *   chunk_sum, chunk_len, chunk_offsets   as written by cwl_partition_chunks
+ *   cap          capacity of chunk_sum / chunk_len / rank_idx; chunks beyond it are ignored
+ *   thresholds   host, [K-1], ascending, nats (the percentile table)
+ *   K            rungs of the ladder, 1 <= K <= CWL_MAX_LADDER
+ *   rank_idx     [cap] written for every existing chunk: 0 .. K-1
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* chunk_len,
+                            const int32_t* chunk_offsets, int32_t n_seqs, int32_t cap,
+                            const float* thresholds /*host*/, int32_t K, int32_t* rank_idx,
+                            void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_chunkwise_lora_linear -- the chunk-segmented, variable-rank LoRA projection with the
+ * boundary cross-fade (Sec. III-C: slice the first r directions of the stored factors;
+ * Sec. III-D: outgoing adapter ramps down linearly while the incoming one ramps up).
+ *
+ * For token t in chunk c (rung k = rank_idx[c], r = ranks[k], s = scales[k]) at offset
+ * j = t - chunk_start[c]:
+ *      D_k(t) = s_k * (x_t . A[:, :r_k]) . B[:r_k, :]
+ *      y_t = x_t W + D_k(t)                                   first chunk of its sequence,
+ *                                                             or j >= blend_w, or blend_w == 0
+ *      y_t = x_t W + (1-l)*D_{k'}(t) + l*D_k(t),  l=(j+1)/(blend_w+1),  k' = rung of chunk c-1
+ * A rung of rank 0 adds nothing.  A token no chunk covers, or whose rank_idx is outside
+ * [0, K), gets the base product only.
+ *
+ *   x [n_rows, d_in] (ldx)    W [d_in, d_out] (ldw)    A [d_in, r_max] (lda)
+ *   B [r_max, d_out] (ldb)    y [n_rows, d_out] (ldy), written; all of element type `dt`
+ *   ranks   host [K], ascending, 0 <= ranks[k] <= r_max      scales  host [K]
+ *   blend_w >= 0
+ *
+ * CWL_F32 : fp32 FMA arithmetic.  CWL_BF16: bf16 operands on the matrix cores, fp32
+ * accumulation, the gated shrink output is rounded to bf16 once, y is rounded to bf16 once.
+ * CWL_BF16 needs d_in % 64 == 0 and d_out % 8 == 0, 16-byte aligned x / y and ldx % 8 == 0,
+ * ldy % 8 == 0 (else CWL_ERR_UNSUPPORTED).
+ *
+ * The static weights can be re-laid out once with cwl_prepack_weights (K-contiguous, padded
+ * ladder) and then used through cwl_chunkwise_lora_linear_packed; the plain entry point does
+ * the same re-layout into its workspace on every call.
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int64_t n_rows, d_in, d_out;
+    int32_t r_max, K;
+    const int32_t* ranks;    /* host [K] */
+    const float* scales;     /* host [K] */
+    int32_t blend_w;
+    cwl_dtype dt;
+    int64_t ldx, ldw, lda, ldb, ldy;
+    int32_t group_rows;      /* 0: rows in token order; 1: group token rows by rank bucket so
+                                that row tiles are rank-homogeneous (same result)             */
+} cwl_linear_desc;
+
+size_t cwl_packed_weights_bytes(const cwl_linear_desc* d);
+cwl_status cwl_prepack_weights(const cwl_linear_desc* d, const void* W, const void* A,
+                               const void* B, void* packed, size_t packed_bytes, void* stream);
+
+size_t cwl_linear_workspace_bytes(const cwl_linear_desc* d);          /* plain entry point  */
+size_t cwl_linear_packed_workspace_bytes(const cwl_linear_desc* d);   /* packed entry point */
+
+cwl_status cwl_chunkwise_lora_linear(const cwl_linear_desc* d, const void* x, const void* W,
+                                     const void* A, const void* B, const int32_t* seq_offsets,
+                                     int32_t n_seqs, const int32_t* chunk_offsets,
+                                     const int32_t* chunk_start, const int32_t* chunk_len,
+                                     const int32_t* rank_idx, void* y, void* workspace,
+                                     size_t workspace_bytes, void* stream);
+
+cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void* x,
+                                            const void* packed, const int32_t* seq_offsets,
+                                            int32_t n_seqs, const int32_t* chunk_offsets,
+                                            const int32_t* chunk_start, const int32_t* chunk_len,
+                                            const int32_t* rank_idx, void* y, void* workspace,
+                                            size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CWL_H */

@@ -1,0 +1,18 @@
+"""CPU oracle for the ChunkWise LoRA hot path -- TEST INFRASTRUCTURE ONLY.
+
+Only the tests, the smoke check and the bench's cpu_baseline leg may import this package; the
+product package never does, and this package never imports the product.  See ``cwl_ref.c`` for
+the arithmetic and ``reference.py`` for the numpy-facing wrapper.
+"""
+from .reference import (  # noqa: F401
+    build,
+    entropy,
+    quantise,
+    quantise_threshold,
+    partition,
+    select,
+    linear,
+    num_threads,
+    set_num_threads,
+    bf16_round,
+)

@@ -1,0 +1,296 @@
+/*
+ * cwl_ref.c -- plain CPU oracle for the ChunkWise LoRA hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of what the
+ * path computes.  It shares no code, header, table or helper with the HIP library; only the
+ * tests, the smoke check and the bench's cpu_baseline leg may build or call it.
+ *
+ * All floating-point work is done in double.  Inputs are the exact fp32 values the device
+ * sees (bf16 inputs are widened to fp32 by the caller, which is exact).
+ *
+ * Paper passages followed (arxiv 2601.21109):
+ *   - Sec. III-A signal (i), Sec. IV-A: next-token entropy from the logits   -> cwl_ref_entropy
+ *   - Sec. III-B, Sec. IV-B: online grouping into chunks under (L_min, L_max)
+ *     and an average-complexity threshold                                     -> cwl_ref_partition
+ *   - Sec. III-C, Sec. IV-C: chunk mean -> rung of the rank ladder            -> cwl_ref_select
+ *   - Sec. III-C (sliced ladder), Sec. III-D (linear cross-fade at joins)     -> cwl_ref_linear
+ *
+ * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
+ * readings taken are written out step by step in the comments of each function.
+ *
+ * Parity pins: every function here is pinned by tests that do not call back into this file's
+ * own formulas (closed forms, library float64 routines, brute force, hand-worked examples).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define CWL_REF_OK 0
+#define CWL_REF_ERR_INVALID 2
+#define CWL_REF_ERR_INFEASIBLE 3
+#define CWL_REF_ERR_CAPACITY 4
+
+int cwl_ref_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void cwl_ref_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Entropy of softmax(z) in nats (Sec. III-A (i)):  H = -sum_v p_v ln p_v,  p = softmax(z).
+ * With m = max z, S = sum exp(z-m), T = sum (z-m) exp(z-m):   H = ln S - T / S.
+ * A logit of -inf has p = 0 and contributes nothing.  A row holding NaN or +inf, or made of
+ * -inf only, has no defined distribution: the result is NaN.
+ * ------------------------------------------------------------------------------------------ */
+void cwl_ref_entropy(const float* logits, int64_t n_rows, int64_t vocab, int64_t row_stride,
+                     double* H) {
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < n_rows; ++t) {
+        const float* z = logits + t * row_stride;
+        double m = -INFINITY;
+        int bad = 0;
+        for (int64_t v = 0; v < vocab; ++v) {
+            double zv = (double)z[v];
+            if (isnan(zv) || (isinf(zv) && zv > 0)) bad = 1;
+            if (zv > m) m = zv;
+        }
+        if (bad || vocab <= 0 || isinf(m)) { H[t] = NAN; continue; }
+        double S = 0.0, T = 0.0;
+        for (int64_t v = 0; v < vocab; ++v) {
+            double zv = (double)z[v];
+            if (isinf(zv)) continue;            /* -inf: probability zero, skip (never 0*inf) */
+            double d = zv - m;
+            double e = exp(d);
+            S += e;
+            T += d * e;
+        }
+        H[t] = log(S) - T / S;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Score -> integer.  The chunk rule and the rung map must give the same answer whatever the
+ * summation order of the entropy, so the fp32 score is turned into Q10 fixed-point nats once:
+ *      q = floor(h * 1024 + 0.5)     evaluated in fp32
+ * (h * 1024 is exact; the only rounding is the one add).  Negative, -0 and NaN map to 0 (NaN
+ * also raises *nan_flag); the result is clamped to 2^20.  Thresholds go through the same
+ * expression but are clamped to 2^21, so that a threshold of +inf can never be met.
+ * ------------------------------------------------------------------------------------------ */
+#define Q_MAX (1 << 20)
+#define QT_MAX (1 << 21)
+
+int32_t cwl_ref_quantise(float h, int32_t* nan_flag) {
+    if (isnan(h)) { if (nan_flag) *nan_flag = 1; return 0; }
+    if (!(h > 0.0f)) return 0;
+    volatile float scaled = h * 1024.0f;           /* volatile: keep the two roundings apart */
+    volatile float shifted = scaled + 0.5f;
+    float f = floorf(shifted);
+    if (f >= (float)Q_MAX) return Q_MAX;
+    return (int32_t)f;
+}
+
+int64_t cwl_ref_quantise_threshold(float h) {
+    if (isnan(h)) return QT_MAX;
+    if (!(h > 0.0f)) return 0;
+    volatile float scaled = h * 1024.0f;
+    volatile float shifted = scaled + 0.5f;
+    float f = floorf(shifted);
+    if (f >= (float)QT_MAX) return QT_MAX;
+    return (int64_t)f;
+}
+
+void cwl_ref_quantise_rows(const float* h, int64_t n, int32_t* q, int32_t* nan_flag) {
+    for (int64_t i = 0; i < n; ++i) q[i] = cwl_ref_quantise(h[i], nan_flag);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Adaptive chunker (Sec. III-B, Sec. IV-B).  Reading of "grouped online ... subject to length
+ * bounds, an average-complexity threshold": a chunk opened at p is extended one token at a time
+ * and is closed at the first end e (chunk = [p, e)) in [p+L_min, p+L_max] at which
+ *      hard :  the chunk's mean score has reached theta           S >= theta_q * n
+ *      enter:  the token that would come next is itself hard      q[e] >= theta_q
+ *      dev  :  the next token leaves the chunk's regime           |q[e]*n - S| > delta_q * n
+ * where S = sum of q over [p, e), n = e - p.  An end is only admissible if it leaves either
+ * nothing or at least L_min tokens behind it, so no tail shorter than L_min is ever stranded.
+ * If nothing fires the chunk runs to the last admissible end.  A sequence shorter than L_min is
+ * one chunk (the only exception to the bounds).  Hard spans are therefore cut every L_min
+ * tokens and easy spans grow to L_max, which is the behaviour Sec. III-B describes.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_partition(const int32_t* q, const int32_t* seq_offsets, int32_t n_seqs,
+                      int32_t l_min, int32_t l_max, int64_t theta_q, int64_t delta_q,
+                      int32_t* chunk_offsets, int32_t* chunk_start, int32_t* chunk_len,
+                      int64_t* chunk_sum, int32_t cap) {
+    if (l_min < 1 || l_max < l_min) return CWL_REF_ERR_INVALID;
+    if ((int64_t)l_max < 2 * (int64_t)l_min - 1) return CWL_REF_ERR_INFEASIBLE;
+    int64_t n_chunks = 0;
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        chunk_offsets[b] = (int32_t)n_chunks;
+        const int64_t base = seq_offsets[b];
+        const int64_t T = (int64_t)seq_offsets[b + 1] - base;
+        if (T < 0) return CWL_REF_ERR_INVALID;
+        if (T == 0) continue;
+        const int32_t* qs = q + base;
+        int64_t* P = (int64_t*)malloc((size_t)(T + 1) * sizeof(int64_t));
+        P[0] = 0;
+        for (int64_t i = 0; i < T; ++i) P[i + 1] = P[i] + qs[i];
+        if (T < l_min) {
+            if (n_chunks < cap) {
+                chunk_start[n_chunks] = (int32_t)base;
+                chunk_len[n_chunks] = (int32_t)T;
+                chunk_sum[n_chunks] = P[T];
+            }
+            ++n_chunks;
+            free(P);
+            continue;
+        }
+        int64_t p = 0;
+        while (p < T) {
+            int64_t last;
+            if (T - p <= l_max) last = T;
+            else last = (p + l_max < T - l_min) ? p + l_max : T - l_min;
+            int64_t e_star = last;
+            int64_t e_hi = (p + l_max < T) ? p + l_max : T;
+            for (int64_t e = p + l_min; e <= e_hi; ++e) {
+                if (!(e <= T - l_min || e == T)) continue;
+                if (e == T) { e_star = e; break; }
+                const int64_t n = e - p;
+                const int64_t S = P[e] - P[p];
+                const int64_t qe = qs[e];
+                const int hard = S >= theta_q * n;
+                const int enter = qe >= theta_q;
+                int64_t d = qe * n - S;
+                if (d < 0) d = -d;
+                const int dev = d > delta_q * n;
+                if (hard || enter || dev) { e_star = e; break; }
+            }
+            if (n_chunks < cap) {
+                chunk_start[n_chunks] = (int32_t)(base + p);
+                chunk_len[n_chunks] = (int32_t)(e_star - p);
+                chunk_sum[n_chunks] = P[e_star] - P[p];
+            }
+            ++n_chunks;
+            p = e_star;
+        }
+        free(P);
+    }
+    chunk_offsets[n_seqs] = (int32_t)n_chunks;
+    return n_chunks > cap ? CWL_REF_ERR_CAPACITY : CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Rung selection (Sec. III-C, Sec. IV-C "rule-based percentile mapping"): the caller's K-1
+ * ascending thresholds are the percentile table; the rung is the number of thresholds the
+ * chunk's mean score reaches,  k = #{ j : sum >= tau_q[j] * len }.  A mean exactly on a
+ * threshold goes up.
+ * ------------------------------------------------------------------------------------------ */
+void cwl_ref_select(const int64_t* chunk_sum, const int32_t* chunk_len, int64_t n_chunks,
+                    const int64_t* tau_q, int32_t K, int32_t* rank_idx) {
+    for (int64_t c = 0; c < n_chunks; ++c) {
+        int32_t k = 0;
+        for (int32_t j = 0; j < K - 1; ++j)
+            if (chunk_sum[c] >= tau_q[j] * (int64_t)chunk_len[c]) ++k;
+        rank_idx[c] = k;
+    }
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Chunk-segmented variable-rank LoRA linear with the boundary cross-fade.
+ *   adapter of rung k on token t (Sec. III-C: first r_k directions of the stored factors):
+ *        D_k(t) = s_k * sum_{i < r_k} (x_t . A[:, i]) * B[i, :]
+ *   token t in chunk c at offset j = t - start_c (Sec. III-D: outgoing ramps down, incoming up):
+ *        first chunk of its sequence, or j >= w, or w == 0:   y_t = x_t W + D_{k_c}(t)
+ *        otherwise, lambda = (j + 1) / (w + 1):
+ *              y_t = x_t W + (1 - lambda) * D_{k_{c-1}}(t) + lambda * D_{k_c}(t)
+ * A rung of rank 0 contributes nothing whatever its scale.  A token that no chunk covers gets
+ * the base product only.  Only the rows listed in `rows` are evaluated (all of them when rows
+ * is NULL); y is [n_sel, d_out] in double, not rounded.
+ * ------------------------------------------------------------------------------------------ */
+static void adapter_term(const double* u, const float* B, int64_t ldb, int64_t d_out,
+                         int32_t r, double s, double weight, double* acc) {
+    if (r <= 0 || weight == 0.0) return;
+    for (int64_t j = 0; j < d_out; ++j) {
+        double d = 0.0;
+        for (int32_t i = 0; i < r; ++i) d += u[i] * (double)B[(int64_t)i * ldb + j];
+        acc[j] += weight * (s * d);
+    }
+}
+
+int cwl_ref_linear(const float* x, int64_t ldx, const float* W, int64_t ldw,
+                   const float* A, int64_t lda, const float* B, int64_t ldb,
+                   int64_t n_rows, int64_t d_in, int64_t d_out, int32_t r_max,
+                   int32_t K, const int32_t* ranks, const float* scales, int32_t blend_w,
+                   const int32_t* seq_offsets, int32_t n_seqs,
+                   const int32_t* chunk_offsets, const int32_t* chunk_start,
+                   const int32_t* chunk_len, const int32_t* rank_idx,
+                   const int64_t* rows, int64_t n_sel, double* y) {
+    if (K < 1 || r_max < 0 || blend_w < 0) return CWL_REF_ERR_INVALID;
+    for (int32_t k = 0; k < K; ++k)
+        if (ranks[k] < 0 || ranks[k] > r_max) return CWL_REF_ERR_INVALID;
+    /* token -> (chunk, is-first-chunk-of-its-sequence); -1 where no chunk covers the token */
+    int32_t* tok_chunk = (int32_t*)malloc((size_t)(n_rows > 0 ? n_rows : 1) * sizeof(int32_t));
+    char* tok_first = (char*)calloc((size_t)(n_rows > 0 ? n_rows : 1), 1);
+    for (int64_t t = 0; t < n_rows; ++t) tok_chunk[t] = -1;
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        for (int32_t c = chunk_offsets[b]; c < chunk_offsets[b + 1]; ++c) {
+            for (int32_t j = 0; j < chunk_len[c]; ++j) {
+                int64_t t = (int64_t)chunk_start[c] + j;
+                if (t < 0 || t >= n_rows) continue;
+                if (t < seq_offsets[b] || t >= seq_offsets[b + 1]) continue;
+                tok_chunk[t] = c;
+                tok_first[t] = (c == chunk_offsets[b]);
+            }
+        }
+    }
+    const int64_t count = rows ? n_sel : n_rows;
+#pragma omp parallel
+    {
+        double* u = (double*)malloc((size_t)(r_max > 0 ? r_max : 1) * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t s_i = 0; s_i < count; ++s_i) {
+            const int64_t t = rows ? rows[s_i] : s_i;
+            double* yt = y + s_i * d_out;
+            const float* xt = x + t * ldx;
+            for (int64_t j = 0; j < d_out; ++j) yt[j] = 0.0;
+            for (int64_t k = 0; k < d_in; ++k) {            /* base product x_t W */
+                const double xv = (double)xt[k];
+                const float* wrow = W + k * ldw;
+                for (int64_t j = 0; j < d_out; ++j) yt[j] += xv * (double)wrow[j];
+            }
+            const int32_t c = tok_chunk[t];
+            if (c < 0) continue;
+            for (int32_t i = 0; i < r_max; ++i) {           /* u = x_t A, all stored directions */
+                double a = 0.0;
+                for (int64_t k = 0; k < d_in; ++k) a += (double)xt[k] * (double)A[k * lda + i];
+                u[i] = a;
+            }
+            const int32_t kc = rank_idx[c];
+            const int64_t j_off = t - chunk_start[c];
+            if (tok_first[t] || blend_w == 0 || j_off >= blend_w) {
+                adapter_term(u, B, ldb, d_out, ranks[kc], (double)scales[kc], 1.0, yt);
+            } else {
+                const double lambda = (double)(j_off + 1) / (double)(blend_w + 1);
+                const int32_t kp = rank_idx[c - 1];
+                adapter_term(u, B, ldb, d_out, ranks[kp], (double)scales[kp], 1.0 - lambda, yt);
+                adapter_term(u, B, ldb, d_out, ranks[kc], (double)scales[kc], lambda, yt);
+            }
+        }
+        free(u);
+    }
+    free(tok_chunk);
+    free(tok_first);
+    return CWL_REF_OK;
+}

@@ -1,0 +1,171 @@
+"""numpy-facing wrapper around the plain C oracle (``cwl_ref.c``) -- TEST INFRASTRUCTURE ONLY.
+
+Argument marshalling only: every number is produced by the C file, in double.  The wrapper holds
+no arithmetic of the method apart from ``bf16_round`` (round-to-nearest-even of a double to the
+bf16 grid, used when a test wants the oracle's output on the device's storage grid).
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cwl_ref.c")
+_LIB = os.path.join(_HERE, "libcwl_ref.so")
+_lib = None
+
+OK, ERR_INVALID, ERR_INFEASIBLE, ERR_CAPACITY = 0, 2, 3, 4
+
+
+def build(force=True):
+    """Compile cwl_ref.c with gcc (-O2, OpenMP over token rows, no fast-math, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-Wall", "-Wextra", _SRC, "-o", _LIB, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build(force=False)
+    lib = ctypes.CDLL(_LIB)
+    i32, i64, f32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    P = ctypes.c_void_p
+    lib.cwl_ref_num_threads.restype = ctypes.c_int
+    lib.cwl_ref_set_num_threads.argtypes = [ctypes.c_int]
+    lib.cwl_ref_entropy.argtypes = [P, i64, i64, i64, P]
+    lib.cwl_ref_entropy.restype = None
+    lib.cwl_ref_quantise_rows.argtypes = [P, i64, P, P]
+    lib.cwl_ref_quantise_rows.restype = None
+    lib.cwl_ref_quantise_threshold.argtypes = [f32]
+    lib.cwl_ref_quantise_threshold.restype = i64
+    lib.cwl_ref_partition.argtypes = [P, P, i32, i32, i32, i64, i64, P, P, P, P, i32]
+    lib.cwl_ref_partition.restype = ctypes.c_int
+    lib.cwl_ref_select.argtypes = [P, P, i64, P, i32, P]
+    lib.cwl_ref_select.restype = None
+    lib.cwl_ref_linear.argtypes = [P, i64, P, i64, P, i64, P, i64, i64, i64, i64, i32,
+                                   i32, P, P, i32, P, i32, P, P, P, P, P, i64, P]
+    lib.cwl_ref_linear.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _arr(a, dtype):
+    return np.ascontiguousarray(np.asarray(a), dtype=dtype)
+
+
+def num_threads():
+    return int(_load().cwl_ref_num_threads())
+
+
+def set_num_threads(n):
+    _load().cwl_ref_set_num_threads(int(n))
+
+
+def entropy(logits):
+    """Row-wise softmax entropy in nats; ``logits`` is [N, V] float32 (exact device values)."""
+    z = _arr(logits, np.float32)
+    assert z.ndim == 2
+    H = np.empty(z.shape[0], dtype=np.float64)
+    _load().cwl_ref_entropy(_ptr(z), z.shape[0], z.shape[1], z.shape[1], _ptr(H))
+    return H
+
+
+def quantise(h):
+    """fp32 scores -> Q10 integers.  Returns (q int32[N], nan_seen bool)."""
+    h = _arr(h, np.float32).ravel()
+    q = np.empty(h.shape[0], dtype=np.int32)
+    flag = np.zeros(1, dtype=np.int32)
+    _load().cwl_ref_quantise_rows(_ptr(h), h.shape[0], _ptr(q), _ptr(flag))
+    return q, bool(flag[0])
+
+
+def quantise_threshold(h):
+    return int(_load().cwl_ref_quantise_threshold(ctypes.c_float(float(np.float32(h)))))
+
+
+def partition(q, seq_offsets, l_min, l_max, theta_q, delta_q, cap=None):
+    """Chunk table of the adaptive chunker.  Returns (status, dict of arrays)."""
+    q = _arr(q, np.int32).ravel()
+    so = _arr(seq_offsets, np.int32).ravel()
+    n_seqs = so.shape[0] - 1
+    if cap is None:
+        cap = int(q.shape[0]) + n_seqs + 1
+    off = np.zeros(n_seqs + 1, dtype=np.int32)
+    start = np.zeros(max(cap, 1), dtype=np.int32)
+    length = np.zeros(max(cap, 1), dtype=np.int32)
+    csum = np.zeros(max(cap, 1), dtype=np.int64)
+    st = _load().cwl_ref_partition(_ptr(q), _ptr(so), n_seqs, int(l_min), int(l_max),
+                                   int(theta_q), int(delta_q), _ptr(off), _ptr(start),
+                                   _ptr(length), _ptr(csum), int(cap))
+    n = min(int(off[-1]), cap) if st in (OK, ERR_CAPACITY) else 0
+    return st, {"chunk_offsets": off, "chunk_start": start[:n].copy(),
+                "chunk_len": length[:n].copy(), "chunk_sum": csum[:n].copy()}
+
+
+def select(chunk_sum, chunk_len, tau_q):
+    cs = _arr(chunk_sum, np.int64).ravel()
+    cl = _arr(chunk_len, np.int32).ravel()
+    tq = _arr(tau_q, np.int64).ravel()
+    out = np.empty(cs.shape[0], dtype=np.int32)
+    _load().cwl_ref_select(_ptr(cs), _ptr(cl), cs.shape[0], _ptr(tq), tq.shape[0] + 1, _ptr(out))
+    return out
+
+
+def linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, chunk_offsets, chunk_start,
+           chunk_len, rank_idx, rows=None):
+    """y[rows] of the chunk-segmented LoRA linear, float64, unrounded.
+
+    x [N, d_in], W [d_in, d_out], A [d_in, r_max], B [r_max, d_out]: float32 arrays holding the
+    exact values the device sees.
+    """
+    x, W, A, B = (_arr(a, np.float32) for a in (x, W, A, B))
+    n_rows, d_in = x.shape
+    d_out = W.shape[1]
+    r_max = A.shape[1]
+    assert W.shape[0] == d_in and A.shape[0] == d_in and B.shape == (r_max, d_out)
+    ranks = _arr(ranks, np.int32).ravel()
+    scales = _arr(scales, np.float32).ravel()
+    K = ranks.shape[0]
+    assert scales.shape[0] == K
+    so = _arr(seq_offsets, np.int32).ravel()
+    co = _arr(chunk_offsets, np.int32).ravel()
+    cs = _arr(chunk_start, np.int32).ravel()
+    cl = _arr(chunk_len, np.int32).ravel()
+    ri = _arr(rank_idx, np.int32).ravel()
+    n_seqs = so.shape[0] - 1
+    assert co.shape[0] == n_seqs + 1 and cs.shape[0] >= co[-1] and ri.shape[0] >= co[-1]
+    if co[-1] > 0:
+        assert ri[:co[-1]].min() >= 0 and ri[:co[-1]].max() < K
+    if rows is None:
+        rows_arr, n_sel, rows_ptr = None, n_rows, ctypes.c_void_p(0)
+    else:
+        rows_arr = _arr(rows, np.int64).ravel()
+        assert rows_arr.size == 0 or (rows_arr.min() >= 0 and rows_arr.max() < n_rows)
+        n_sel, rows_ptr = rows_arr.shape[0], _ptr(rows_arr)
+    y = np.empty((n_sel, d_out), dtype=np.float64)
+    st = _load().cwl_ref_linear(_ptr(x), x.shape[1], _ptr(W), W.shape[1], _ptr(A), A.shape[1],
+                                _ptr(B), B.shape[1], n_rows, d_in, d_out, r_max, K, _ptr(ranks),
+                                _ptr(scales), int(blend_w), _ptr(so), n_seqs, _ptr(co), _ptr(cs),
+                                _ptr(cl), _ptr(ri), rows_ptr, n_sel, _ptr(y))
+    if st != OK:
+        raise ValueError(f"cwl_ref_linear: status {st}")
+    return y
+
+
+def bf16_round(y):
+    """Round float64 values to the bf16 grid (nearest, ties to even), returned as float64."""
+    f = np.asarray(y, dtype=np.float64).astype(np.float32)   # fp32 first: bf16 is its top half
+    bits = f.view(np.uint32).astype(np.uint64)
+    lsb = (bits >> 16) & 1
+    rounded = ((bits + 0x7FFF + lsb) >> 16) << 16
+    out = rounded.astype(np.uint32).view(np.float32)
+    return np.where(np.isfinite(f), out, f).astype(np.float64)
