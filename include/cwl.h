@@ -140,6 +140,9 @@ cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* chunk_len,
  *   B [r_max, d_out] (ldb)    y [n_rows, d_out] (ldy), written; all of element type `dt`
  *   ranks   host [K], ascending, 0 <= ranks[k] <= r_max      scales  host [K]
  *   blend_w >= 0
+ *   seq_offsets / chunk_offsets / chunk_start / chunk_len / rank_idx: the chunk table as written
+ *   by cwl_partition_chunks and cwl_select_ranks; chunk_cap is the capacity of the three
+ *   per-chunk arrays (chunks at or beyond it are treated as absent)
  *
  * CWL_F32 : fp32 FMA arithmetic.  CWL_BF16: bf16 operands on the matrix cores, fp32
  * accumulation, the gated shrink output is rounded to bf16 once, y is rounded to bf16 once.
@@ -173,15 +176,15 @@ cwl_status cwl_chunkwise_lora_linear(const cwl_linear_desc* d, const void* x, co
                                      const void* A, const void* B, const int32_t* seq_offsets,
                                      int32_t n_seqs, const int32_t* chunk_offsets,
                                      const int32_t* chunk_start, const int32_t* chunk_len,
-                                     const int32_t* rank_idx, void* y, void* workspace,
-                                     size_t workspace_bytes, void* stream);
+                                     const int32_t* rank_idx, int32_t chunk_cap, void* y,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void* x,
                                             const void* packed, const int32_t* seq_offsets,
                                             int32_t n_seqs, const int32_t* chunk_offsets,
                                             const int32_t* chunk_start, const int32_t* chunk_len,
-                                            const int32_t* rank_idx, void* y, void* workspace,
-                                            size_t workspace_bytes, void* stream);
+                                            const int32_t* rank_idx, int32_t chunk_cap, void* y,
+                                            void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

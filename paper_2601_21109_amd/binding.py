@@ -1,0 +1,287 @@
+"""Thin ctypes binding of the C ABI in ``include/cwl.h``: argument marshalling only.
+
+PyTorch supplies device memory (``torch.empty(device=...)``, ``data_ptr()``) and the current HIP
+stream; every step of the path runs in the library's kernels.  The library is loaded on first
+use; if it is missing the call raises -- there is no fallback of any kind.
+"""
+import ctypes
+import math
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcwl.so")
+
+OK, ERR_NULL, ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = range(7)
+F32, BF16 = 0, 1
+STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS = 1, 2, 4
+MAX_LADDER, MAX_RANK = 16, 256
+
+EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens",
+           "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
+           "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
+           "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
+           "cwl_chunkwise_lora_linear_packed"]
+
+
+class ChunkParams(ctypes.Structure):
+    _fields_ = [("l_min", ctypes.c_int32), ("l_max", ctypes.c_int32),
+                ("theta_hard", ctypes.c_float), ("delta_dev", ctypes.c_float)]
+
+
+class LinearDesc(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int64), ("d_in", ctypes.c_int64), ("d_out", ctypes.c_int64),
+                ("r_max", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("ranks", ctypes.POINTER(ctypes.c_int32)), ("scales", ctypes.POINTER(ctypes.c_float)),
+                ("blend_w", ctypes.c_int32), ("dt", ctypes.c_int),
+                ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("lda", ctypes.c_int64),
+                ("ldb", ctypes.c_int64), ("ldy", ctypes.c_int64), ("group_rows", ctypes.c_int32)]
+
+
+class CwlError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded HIP library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with "
+                           "`python -m paper_2601_21109_amd.build` (there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, P, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    L.cwl_status_string.argtypes = [ctypes.c_int]
+    L.cwl_status_string.restype = ctypes.c_char_p
+    L.cwl_abi_version.restype = i32
+    L.cwl_score_tokens.argtypes = [P, ctypes.c_int, i64, i64, i64, P, P]
+    L.cwl_partition_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ChunkParams)]
+    L.cwl_partition_workspace_bytes.restype = sz
+    L.cwl_partition_chunks.argtypes = [P, i64, P, i32, ctypes.POINTER(ChunkParams), P, P, P, P,
+                                       i32, P, P, sz, P]
+    L.cwl_select_ranks.argtypes = [P, P, P, i32, i32, ctypes.POINTER(ctypes.c_float), i32, P, P]
+    dp = ctypes.POINTER(LinearDesc)
+    for name in ("cwl_packed_weights_bytes", "cwl_linear_workspace_bytes",
+                 "cwl_linear_packed_workspace_bytes"):
+        getattr(L, name).argtypes = [dp]
+        getattr(L, name).restype = sz
+    L.cwl_prepack_weights.argtypes = [dp, P, P, P, P, sz, P]
+    L.cwl_chunkwise_lora_linear.argtypes = [dp, P, P, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
+    L.cwl_chunkwise_lora_linear_packed.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
+    for name in ("cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
+                 "cwl_prepack_weights", "cwl_chunkwise_lora_linear",
+                 "cwl_chunkwise_lora_linear_packed"):
+        getattr(L, name).restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def status_string(status):
+    return lib().cwl_status_string(int(status)).decode()
+
+
+def _check(status, where):
+    if status != OK:
+        raise CwlError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _dt(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ws(nbytes, device):
+    # torch's caching allocator hands out 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+# ------------------------------------------------------------------------------------------------
+def score_tokens(logits, out=None):
+    """entropy[t] (nats, fp32) of softmax(logits[t, :]).  logits: [N, V] fp32 or bf16, device."""
+    assert logits.is_cuda and logits.dim() == 2 and logits.stride(1) == 1
+    n, v = logits.shape
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device=logits.device)
+    _check(lib().cwl_score_tokens(_ptr(logits), _dt(logits), n, v, logits.stride(0) if n > 1 else v,
+                                  _ptr(out), _stream()), "cwl_score_tokens")
+    return out
+
+
+def partition_chunks(entropy, seq_offsets, l_min, l_max, theta_hard=math.inf, delta_dev=math.inf,
+                     cap=None):
+    """Chunk table of the adaptive chunker.  Returns a dict of device tensors
+    (chunk_offsets, chunk_start, chunk_len, chunk_sum, status_word) plus 'cap'."""
+    assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
+    assert seq_offsets.is_cuda and seq_offsets.dtype == torch.int32
+    dev = entropy.device
+    n_rows, n_seqs = entropy.numel(), seq_offsets.numel() - 1
+    p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
+    if cap is None:
+        cap = n_rows // max(int(l_min), 1) + n_seqs + 1
+    out = {
+        "chunk_offsets": torch.empty(n_seqs + 1, dtype=torch.int32, device=dev),
+        "chunk_start": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_len": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_sum": torch.empty(max(cap, 1), dtype=torch.int64, device=dev),
+        "status_word": torch.empty(1, dtype=torch.int32, device=dev),
+        "cap": int(cap),
+    }
+    nbytes = lib().cwl_partition_workspace_bytes(n_rows, n_seqs, ctypes.byref(p))
+    ws = _ws(nbytes, dev)
+    _check(lib().cwl_partition_chunks(_ptr(entropy), n_rows, _ptr(seq_offsets), n_seqs,
+                                      ctypes.byref(p), _ptr(out["chunk_offsets"]),
+                                      _ptr(out["chunk_start"]), _ptr(out["chunk_len"]),
+                                      _ptr(out["chunk_sum"]), int(cap), _ptr(out["status_word"]),
+                                      _ptr(ws), ws.numel(), _stream()), "cwl_partition_chunks")
+    out["_workspace"] = ws      # keep alive until the stream has run
+    return out
+
+
+def select_ranks(table, thresholds, K):
+    """rank_idx[c] (int32, device) for every chunk of `table` (from partition_chunks)."""
+    dev = table["chunk_len"].device
+    n_seqs = table["chunk_offsets"].numel() - 1
+    cap = table["cap"]
+    rank_idx = torch.zeros(max(cap, 1), dtype=torch.int32, device=dev)
+    th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
+    _check(lib().cwl_select_ranks(_ptr(table["chunk_sum"]), _ptr(table["chunk_len"]),
+                                  _ptr(table["chunk_offsets"]), n_seqs, cap, th, int(K),
+                                  _ptr(rank_idx), _stream()), "cwl_select_ranks")
+    return rank_idx
+
+
+class _Desc:
+    """Owns the host arrays a cwl_linear_desc points to."""
+
+    def __init__(self, n_rows, d_in, d_out, r_max, ranks, scales, blend_w, dt, ldx, ldw, lda, ldb,
+                 ldy, group_rows):
+        K = len(ranks)
+        self.ranks = (ctypes.c_int32 * max(K, 1))(*[int(r) for r in ranks])
+        self.scales = (ctypes.c_float * max(K, 1))(*[float(s) for s in scales])
+        self.c = LinearDesc(n_rows, d_in, d_out, r_max, K, self.ranks, self.scales, int(blend_w), dt,
+                            ldx, ldw, lda, ldb, ldy, int(group_rows))
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def _desc_for(x, d_out, r_max, ranks, scales, blend_w, y, W=None, A=None, B=None, group_rows=0):
+    n_rows, d_in = x.shape
+    ldx = x.stride(0) if n_rows > 1 else d_in
+    ldy = y.stride(0) if n_rows > 1 else d_out
+    ldw = W.stride(0) if W is not None and W.shape[0] > 1 else d_out
+    lda = A.stride(0) if A is not None and A.shape[0] > 1 else max(r_max, 1)
+    ldb = B.stride(0) if B is not None and B.shape[0] > 1 else d_out
+    return _Desc(n_rows, d_in, d_out, r_max, ranks, scales, blend_w, _dt(x), ldx, ldw, lda, ldb, ldy,
+                 group_rows)
+
+
+class PackedWeights:
+    """Static weights re-laid out once by cwl_prepack_weights."""
+
+    def __init__(self, blob, d_in, d_out, r_max, dtype):
+        self.blob, self.d_in, self.d_out, self.r_max, self.dtype = blob, d_in, d_out, r_max, dtype
+
+
+def prepack_weights(W, A, B):
+    """W [d_in, d_out], A [d_in, r_max], B [r_max, d_out] -> PackedWeights (device)."""
+    assert W.is_cuda and W.dim() == 2 and W.stride(1) == 1
+    d_in, d_out = W.shape
+    r_max = A.shape[1]
+    assert A.shape[0] == d_in and B.shape == (r_max, d_out)
+    assert A.dtype == W.dtype and B.dtype == W.dtype
+    dummy_x = torch.empty((1, d_in), dtype=W.dtype, device=W.device)
+    dummy_y = torch.empty((1, d_out), dtype=W.dtype, device=W.device)
+    d = _desc_for(dummy_x, d_out, r_max, [r_max], [1.0], 0, dummy_y, W, A, B)
+    d.c.n_rows = 0
+    nbytes = lib().cwl_packed_weights_bytes(d.ref())
+    if nbytes == 0:
+        raise CwlError(ERR_INVALID_ARG, "cwl_packed_weights_bytes")
+    blob = _ws(nbytes, W.device)
+    _check(lib().cwl_prepack_weights(d.ref(), _ptr(W), _ptr(A if r_max else None),
+                                     _ptr(B if r_max else None), _ptr(blob), blob.numel(),
+                                     _stream()), "cwl_prepack_weights")
+    return PackedWeights(blob, d_in, d_out, r_max, W.dtype)
+
+
+def chunkwise_lora_linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, table, rank_idx,
+                          out=None, group_rows=0, workspace=None):
+    """y = x W + chunk-wise gated LoRA term with the boundary cross-fade (see include/cwl.h).
+
+    `W` may be a raw [d_in, d_out] tensor (with A, B) or a PackedWeights (A = B = None)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    packed = isinstance(W, PackedWeights)
+    d_out = W.d_out if packed else W.shape[1]
+    r_max = W.r_max if packed else A.shape[1]
+    n_rows = x.shape[0]
+    if out is None:
+        out = torch.empty((n_rows, d_out), dtype=x.dtype, device=x.device)
+    n_seqs = seq_offsets.numel() - 1
+    cap = table["cap"]
+    L = lib()
+    if packed:
+        assert W.dtype == x.dtype and W.d_in == x.shape[1]
+        d = _desc_for(x, d_out, r_max, ranks, scales, blend_w, out, group_rows=group_rows)
+        need = L.cwl_linear_packed_workspace_bytes(d.ref())
+    else:
+        d = _desc_for(x, d_out, r_max, ranks, scales, blend_w, out, W, A, B, group_rows=group_rows)
+        need = L.cwl_linear_workspace_bytes(d.ref())
+    if need == 0:
+        # the descriptor was rejected: let the call itself say why
+        need = 256
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    common = (_ptr(seq_offsets), n_seqs, _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]),
+              _ptr(table["chunk_len"]), _ptr(rank_idx), cap, _ptr(out), _ptr(ws), ws.numel(),
+              _stream())
+    if packed:
+        _check(L.cwl_chunkwise_lora_linear_packed(d.ref(), _ptr(x), _ptr(W.blob), *common),
+               "cwl_chunkwise_lora_linear_packed")
+    else:
+        _check(L.cwl_chunkwise_lora_linear(d.ref(), _ptr(x), _ptr(W), _ptr(A if r_max else None),
+                                           _ptr(B if r_max else None), *common),
+               "cwl_chunkwise_lora_linear")
+    return out
+
+
+def linear_workspace(x_shape, dtype, d_out, r_max, ranks, scales, blend_w, device, packed=True):
+    """Pre-allocate a workspace for repeated chunkwise_lora_linear calls of one shape."""
+    x = torch.empty((1, x_shape[1]), dtype=dtype, device=device)
+    y = torch.empty((1, d_out), dtype=dtype, device=device)
+    d = _desc_for(x, d_out, r_max, ranks, scales, blend_w, y)
+    d.c.n_rows = x_shape[0]
+    d.c.ldx, d.c.ldy = x_shape[1], d_out
+    L = lib()
+    n = L.cwl_linear_packed_workspace_bytes(d.ref()) if packed else L.cwl_linear_workspace_bytes(d.ref())
+    return _ws(n, device)
+
+
+def table_from_host(seq_offsets, chunk_offsets, chunk_start, chunk_len, rank_idx, device):
+    """Upload a host chunk table (numpy int arrays) in the form the calls above take."""
+    import numpy as np
+
+    def up(a, dt):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(device)
+
+    n = max(len(chunk_start), 1)
+    pad = lambda a, dt: up(np.concatenate([np.asarray(a, dtype=dt), np.zeros(n - len(a), dt)]), dt)
+    table = {"chunk_offsets": up(chunk_offsets, np.int32), "chunk_start": pad(chunk_start, np.int32),
+             "chunk_len": pad(chunk_len, np.int32), "cap": len(chunk_start)}
+    return up(seq_offsets, np.int32), table, pad(rank_idx, np.int32)

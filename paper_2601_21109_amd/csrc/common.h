@@ -1,0 +1,46 @@
+// Shared host/device helpers of the ChunkWise LoRA HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cwl.h"
+
+#define CWL_RETURN_IF_LAUNCH_FAILED()                        \
+    do {                                                     \
+        if (hipGetLastError() != hipSuccess) return CWL_ERR_DEVICE; \
+    } while (0)
+
+namespace cwl {
+
+constexpr int kWave = 64;                 // CDNA wavefront width
+constexpr int32_t kQMax = 1 << 20;        // clamp of a quantised score
+constexpr int64_t kQThresholdMax = 1 << 21;  // clamp of a quantised threshold: never reachable
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Score -> Q10 fixed-point nats, q = floor(h*1024 + 0.5) in fp32.  h*1024 is exact, so a fused
+// multiply-add gives the same value as a separate multiply and add.
+__host__ __device__ inline int32_t quantise_score(float h, bool* is_nan) {
+    if (h != h) {
+        *is_nan = true;
+        return 0;
+    }
+    if (!(h > 0.0f)) return 0;
+    float f = floorf(h * 1024.0f + 0.5f);
+    if (f >= (float)kQMax) return kQMax;
+    return (int32_t)f;
+}
+
+inline int64_t quantise_threshold(float h) {
+    if (h != h) return kQThresholdMax;
+    if (!(h > 0.0f)) return 0;
+    float f = floorf(h * 1024.0f + 0.5f);
+    if (f >= (float)kQThresholdMax) return kQThresholdMax;
+    return (int64_t)f;
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+
+}  // namespace cwl

@@ -1,0 +1,443 @@
+// cwl_chunkwise_lora_linear: host side and the small helper kernels (token gate table, rank
+// grouping, weight re-layout).  The GEMMs themselves are in gemm_f32.hip / gemm_bf16.hip; the
+// formulation is described in linear_common.h.  (Sec. III-C / III-D of arxiv 2601.21109.)
+#include "linear_common.h"
+
+namespace cwl {
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Per-token gate table.  Token t -> its sequence (binary search in seq_offsets) -> its chunk
+// (binary search in that sequence's chunk_start range) -> (r_cur, g_cur, r_prev, g_prev).
+// A block of 256 threads covers 4 rank blocks of 64 rows; in token order (no grouping) each
+// wavefront also reduces the largest effective rank of its 64 rows into blk_r.
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
+                  const int32_t* __restrict__ chunk_offsets, const int32_t* __restrict__ chunk_start,
+                  const int32_t* __restrict__ chunk_len, const int32_t* __restrict__ rank_idx,
+                  int32_t chunk_cap, Ladder lad, int32_t blend_w, TokMeta* __restrict__ meta,
+                  int32_t* __restrict__ blk_r /* may be NULL */, int32_t* __restrict__ r_eff_out /* may be NULL */) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    TokMeta m = {0, 0, 0.0f, 0.0f};
+    if (t < n_rows && n_seqs > 0) {
+        // sequence: last b with seq_offsets[b] <= t
+        int32_t lo = 0, hi = n_seqs;           // first index in [0, n_seqs] with offset > t
+        while (lo < hi) {
+            const int32_t mid = lo + (hi - lo) / 2;
+            if ((int64_t)seq_offsets[mid] <= t) lo = mid + 1; else hi = mid;
+        }
+        const int32_t b = lo - 1;
+        if (b >= 0 && t < (int64_t)seq_offsets[b + 1]) {
+            int32_t c0 = chunk_offsets[b], c1 = chunk_offsets[b + 1];
+            if (c1 > chunk_cap) c1 = chunk_cap;
+            int32_t l2 = c0, h2 = c1;          // first chunk in [c0, c1) with start > t
+            while (l2 < h2) {
+                const int32_t mid = l2 + (h2 - l2) / 2;
+                if ((int64_t)chunk_start[mid] <= t) l2 = mid + 1; else h2 = mid;
+            }
+            const int32_t c = l2 - 1;
+            if (c >= c0 && c0 >= 0) {
+                const int64_t j = t - chunk_start[c];
+                if (j < chunk_len[c]) {
+                    const int32_t k = rank_idx[c];
+                    const bool k_ok = k >= 0 && k < lad.K;
+                    const int32_t r_cur = k_ok ? lad.ranks[k] : 0;
+                    const float s_cur = (k_ok && r_cur > 0) ? lad.scales[k] : 0.0f;
+                    if (c == c0 || blend_w == 0 || j >= blend_w) {
+                        m.r_cur = r_cur;
+                        m.g_cur = s_cur;
+                    } else {
+                        const int32_t kp = rank_idx[c - 1];
+                        const bool kp_ok = kp >= 0 && kp < lad.K;
+                        const int32_t r_prev = kp_ok ? lad.ranks[kp] : 0;
+                        const float s_prev = (kp_ok && r_prev > 0) ? lad.scales[kp] : 0.0f;
+                        const float lambda = (float)(j + 1) / (float)(blend_w + 1);
+                        m.r_cur = r_cur;
+                        m.g_cur = lambda * s_cur;
+                        m.r_prev = r_prev;
+                        m.g_prev = (1.0f - lambda) * s_prev;
+                    }
+                }
+            }
+        }
+    }
+    int32_t r_eff = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
+    if (t < n_rows) {
+        meta[t] = m;
+        if (r_eff_out) r_eff_out[t] = r_eff;
+    }
+    if (blk_r) {
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int32_t o = __shfl_xor(r_eff, off);
+            r_eff = o > r_eff ? o : r_eff;
+        }
+        const int64_t blk = t / kRankBlock;
+        if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r_eff;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Rank grouping: a stable counting sort of the token rows by effective rank, largest first, so
+// that row tiles are rank-homogeneous (only the few tiles that straddle two buckets mix ranks)
+// and the tiles with the longest reduction are scheduled first.  One workgroup of 512 threads;
+// each thread owns a contiguous slice of tokens.
+// ------------------------------------------------------------------------------------------
+constexpr int kSortThreads = 512;
+constexpr int kBuckets = CWL_MAX_LADDER + 1;
+
+__device__ __forceinline__ int bucket_of(int32_t r_eff, const Ladder& lad) {
+    // larger rank -> smaller bucket id; rank 0 -> last bucket
+    int n_ge = 0;
+    for (int k = 0; k < lad.K; ++k) n_ge += (lad.ranks[k] > 0 && lad.ranks[k] >= r_eff) ? 1 : 0;
+    return r_eff > 0 ? (n_ge > 0 ? n_ge - 1 : 0) : kBuckets - 1;
+}
+
+__global__ void __launch_bounds__(kSortThreads)
+group_rows_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, Ladder lad,
+                  int32_t* __restrict__ perm) {
+    __shared__ int32_t cnt[kBuckets][kSortThreads];   // 34 KiB
+    __shared__ int32_t bucket_base[kBuckets + 1];
+    const int tid = threadIdx.x;
+    const int64_t per = (n_rows + kSortThreads - 1) / kSortThreads;
+    const int64_t t0 = tid * per, t1 = (t0 + per < n_rows) ? t0 + per : n_rows;
+    for (int b = 0; b < kBuckets; ++b) cnt[b][tid] = 0;
+    for (int64_t t = t0; t < t1; ++t) cnt[bucket_of(r_eff[t], lad)][tid] += 1;
+    __syncthreads();
+    if (tid < kBuckets) {                       // exclusive scan over threads, one bucket each
+        int32_t run = 0;
+        for (int i = 0; i < kSortThreads; ++i) {
+            const int32_t c = cnt[tid][i];
+            cnt[tid][i] = run;
+            run += c;
+        }
+        bucket_base[tid + 1] = run;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        bucket_base[0] = 0;
+        for (int b = 1; b <= kBuckets; ++b) bucket_base[b] += bucket_base[b - 1];
+    }
+    __syncthreads();
+    int32_t pos[kBuckets];
+    for (int b = 0; b < kBuckets; ++b) pos[b] = bucket_base[b] + cnt[b][tid];
+    for (int64_t t = t0; t < t1; ++t) {
+        const int b = bucket_of(r_eff[t], lad);
+        // pos is indexed dynamically: keep it in LDS-free registers via a small switch-less loop
+        int32_t p = 0;
+#pragma unroll
+        for (int bb = 0; bb < kBuckets; ++bb)
+            if (bb == b) { p = pos[bb]; pos[bb] = p + 1; }
+        perm[p] = (int32_t)t;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+block_rank_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32_t* __restrict__ perm,
+                  int32_t* __restrict__ blk_r) {
+    const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int32_t r = 0;
+    if (g < n_rows) r = r_eff[perm[g]];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const int32_t o = __shfl_xor(r, off);
+        r = o > r ? o : r;
+    }
+    const int64_t blk = g / kRankBlock;
+    if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r;
+}
+
+// ------------------------------------------------------------------------------------------
+// Weight re-layout: dst[c, r] = src[r, c] (zero where the source has no element), so that every
+// GEMM operand is contiguous along the reduction dimension.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256)
+transpose_pad_kernel(const T* __restrict__ src, int64_t src_rows, int64_t src_cols, int64_t lds_,
+                     T* __restrict__ dst, int64_t dst_rows, int64_t dst_cols, int64_t ldd) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;       // 32 x 8
+    const int64_t c0 = (int64_t)blockIdx.x * 32;                  // source column / dst row
+    const int64_t r0 = (int64_t)blockIdx.y * 32;                  // source row / dst column
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t r = r0 + ty + i * 8, c = c0 + tx;
+        tile[ty + i * 8][tx] = (r < src_rows && c < src_cols) ? src[r * lds_ + c] : T(0);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t dr = c0 + ty + i * 8, dc = r0 + tx;
+        if (dr < dst_rows && dc < dst_cols) dst[dr * ldd + dc] = tile[tx][ty + i * 8];
+    }
+}
+
+template <typename T>
+cwl_status transpose_pad(const void* src, int64_t src_rows, int64_t src_cols, int64_t ld_src,
+                         void* dst, int64_t dst_rows, int64_t dst_cols, hipStream_t st) {
+    if (dst_rows <= 0 || dst_cols <= 0) return CWL_OK;
+    const dim3 grid((unsigned)((dst_rows + 31) / 32), (unsigned)((dst_cols + 31) / 32));
+    if (grid.y > 65535u) return CWL_ERR_UNSUPPORTED;
+    transpose_pad_kernel<T><<<grid, dim3(256), 0, st>>>(static_cast<const T*>(src), src_rows, src_cols,
+                                                       ld_src, static_cast<T*>(dst), dst_rows,
+                                                       dst_cols, dst_cols);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}
+
+// ---- layouts -------------------------------------------------------------------------------
+struct PackedLayout {       // byte offsets into the packed weight blob
+    size_t wt, at, bt, total;
+    int32_t R;
+};
+
+PackedLayout packed_layout(const cwl_linear_desc* d) {
+    PackedLayout L;
+    const size_t es = d->dt == CWL_F32 ? 4 : 2;
+    L.R = padded_rank(d->r_max);
+    size_t off = 0;
+    L.wt = off; off = align_up(off + es * (size_t)d->d_out * (size_t)d->d_in, 256);
+    L.at = off; off = align_up(off + es * (size_t)L.R * (size_t)d->d_in, 256);
+    L.bt = off; off = align_up(off + es * (size_t)d->d_out * (size_t)L.R, 256);
+    L.total = off;
+    return L;
+}
+
+struct WsLayout {           // byte offsets into the linear workspace
+    size_t meta, blk_r, r_eff, perm, uhat, total;
+};
+
+WsLayout ws_layout(const cwl_linear_desc* d) {
+    WsLayout L;
+    const size_t es = d->dt == CWL_F32 ? 4 : 2;
+    const size_t n = (size_t)d->n_rows;
+    const size_t R = (size_t)padded_rank(d->r_max);
+    size_t off = 0;
+    L.meta = off; off = align_up(off + sizeof(TokMeta) * (n + 1), 256);
+    L.blk_r = off; off = align_up(off + sizeof(int32_t) * (n / kRankBlock + 2), 256);
+    L.r_eff = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
+    L.perm = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
+    L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
+    L.total = off;
+    return L;
+}
+
+cwl_status check_desc(const cwl_linear_desc* d) {
+    if (!d) return CWL_ERR_NULL;
+    if (d->dt != CWL_F32 && d->dt != CWL_BF16) return CWL_ERR_INVALID_ARG;
+    if (d->n_rows < 0 || d->n_rows >= (int64_t)1 << 31) return CWL_ERR_INVALID_ARG;
+    if (d->d_in < 1 || d->d_out < 1 || d->d_in >= (int64_t)1 << 31 || d->d_out >= (int64_t)1 << 31)
+        return CWL_ERR_INVALID_ARG;
+    if (d->r_max < 0 || d->r_max > CWL_MAX_RANK) return CWL_ERR_INVALID_ARG;
+    if (d->K < 1 || d->K > CWL_MAX_LADDER) return CWL_ERR_INVALID_ARG;
+    if (!d->ranks || !d->scales) return CWL_ERR_NULL;
+    for (int32_t k = 0; k < d->K; ++k) {
+        if (d->ranks[k] < 0 || d->ranks[k] > d->r_max) return CWL_ERR_INVALID_ARG;
+        if (k > 0 && d->ranks[k] < d->ranks[k - 1]) return CWL_ERR_INVALID_ARG;
+        if (d->scales[k] != d->scales[k]) return CWL_ERR_INVALID_ARG;
+    }
+    if (d->blend_w < 0) return CWL_ERR_INVALID_ARG;
+    if (d->group_rows != 0 && d->group_rows != 1) return CWL_ERR_INVALID_ARG;
+    if (d->ldx < d->d_in || d->ldy < d->d_out) return CWL_ERR_INVALID_ARG;
+    if (d->dt == CWL_BF16) {
+        if (d->d_in % 64 != 0 || d->d_out % 8 != 0 || d->ldx % 8 != 0 || d->ldy % 8 != 0)
+            return CWL_ERR_UNSUPPORTED;
+    }
+    return CWL_OK;
+}
+
+cwl_status check_raw_weights(const cwl_linear_desc* d) {
+    if (d->ldw < d->d_out || d->ldb < d->d_out) return CWL_ERR_INVALID_ARG;
+    if (d->lda < (d->r_max > 0 ? d->r_max : 1)) return CWL_ERR_INVALID_ARG;
+    return CWL_OK;
+}
+
+template <typename T>
+cwl_status prepack_typed(const cwl_linear_desc* d, const PackedLayout& L, const void* W,
+                         const void* A, const void* B, char* packed, hipStream_t st) {
+    cwl_status s = transpose_pad<T>(W, d->d_in, d->d_out, d->ldw, packed + L.wt, d->d_out, d->d_in, st);
+    if (s != CWL_OK) return s;
+    s = transpose_pad<T>(A, d->d_in, d->r_max, d->lda, packed + L.at, L.R, d->d_in, st);
+    if (s != CWL_OK) return s;
+    return transpose_pad<T>(B, d->r_max, d->d_out, d->ldb, packed + L.bt, d->d_out, L.R, st);
+}
+
+cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packed,
+                      const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
+                      const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+                      int32_t chunk_cap, void* y, char* ws, hipStream_t st) {
+    const PackedLayout P = packed_layout(d);
+    const WsLayout L = ws_layout(d);
+    TokMeta* meta = reinterpret_cast<TokMeta*>(ws + L.meta);
+    int32_t* blk_r = reinterpret_cast<int32_t*>(ws + L.blk_r);
+    int32_t* r_eff = reinterpret_cast<int32_t*>(ws + L.r_eff);
+    int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
+    void* uhat = ws + L.uhat;
+
+    Ladder lad = {};
+    lad.K = d->K;
+    for (int32_t k = 0; k < d->K; ++k) {
+        lad.ranks[k] = d->ranks[k];
+        lad.scales[k] = d->scales[k];
+    }
+    const bool grouped = d->group_rows == 1;
+    const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
+    token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
+        d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
+        lad, d->blend_w, meta, grouped ? nullptr : blk_r, grouped ? r_eff : nullptr);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    if (grouped) {
+        group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, lad, perm);
+        CWL_RETURN_IF_LAUNCH_FAILED();
+        block_rank_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, perm, blk_r);
+        CWL_RETURN_IF_LAUNCH_FAILED();
+    }
+
+    GemmArgs sh = {};
+    sh.A1 = x;            sh.lda1 = d->ldx;
+    sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
+    sh.K1 = (int32_t)d->d_in;
+    sh.M = d->n_rows;     sh.N = P.R;
+    sh.C = uhat;          sh.ldc = P.R;
+    sh.meta = meta;       sh.perm = grouped ? perm : nullptr;
+    sh.gate_blk_r = blk_r;
+
+    GemmArgs mn = {};
+    mn.A1 = x;            mn.lda1 = d->ldx;
+    mn.B1 = packed + P.wt; mn.ldb1 = d->d_in;
+    mn.K1 = (int32_t)d->d_in;
+    mn.A2 = uhat;         mn.lda2 = P.R;
+    mn.B2 = packed + P.bt; mn.ldb2 = P.R;
+    mn.blk_r = blk_r;
+    mn.M = d->n_rows;     mn.N = d->d_out;
+    mn.C = y;             mn.ldc = d->ldy;
+    mn.meta = meta;       mn.perm = grouped ? perm : nullptr;
+
+    cwl_status s;
+    if (d->dt == CWL_F32) {
+        s = launch_gemm_f32(sh, EPI_GATE, st);
+        if (s != CWL_OK) return s;
+        return launch_gemm_f32(mn, EPI_STORE, st);
+    }
+    s = launch_shrink_bf16(sh, st);
+    if (s != CWL_OK) return s;
+    return launch_main_bf16(mn, st);
+}
+
+cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* seq_offsets,
+                      int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
+                      const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap,
+                      const void* y, const void* ws) {
+    if (n_seqs < 0 || chunk_cap < 0) return CWL_ERR_INVALID_ARG;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!x || !y || !ws) return CWL_ERR_NULL;
+    if (n_seqs > 0 && (!seq_offsets || !chunk_offsets)) return CWL_ERR_NULL;
+    if (n_seqs > 0 && chunk_cap > 0 && (!chunk_start || !chunk_len || !rank_idx)) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(ws) % 256) return CWL_ERR_INVALID_ARG;
+    if (d->dt == CWL_BF16 &&
+        (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16))
+        return CWL_ERR_UNSUPPORTED;
+    if (d->dt == CWL_F32 && (reinterpret_cast<uintptr_t>(x) % 4 || reinterpret_cast<uintptr_t>(y) % 4))
+        return CWL_ERR_INVALID_ARG;
+    return CWL_OK;
+}
+
+}  // namespace
+}  // namespace cwl
+
+using namespace cwl;
+
+extern "C" size_t cwl_packed_weights_bytes(const cwl_linear_desc* d) {
+    if (check_desc(d) != CWL_OK) return 0;
+    return packed_layout(d).total;
+}
+
+extern "C" cwl_status cwl_prepack_weights(const cwl_linear_desc* d, const void* W, const void* A,
+                                          const void* B, void* packed, size_t packed_bytes,
+                                          void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_raw_weights(d);
+    if (s != CWL_OK) return s;
+    if (!W || !packed) return CWL_ERR_NULL;
+    if (d->r_max > 0 && (!A || !B)) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
+    const PackedLayout L = packed_layout(d);
+    if (packed_bytes < L.total) return CWL_ERR_CAPACITY;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (d->dt == CWL_F32) return prepack_typed<float>(d, L, W, A, B, static_cast<char*>(packed), st);
+    return prepack_typed<uint16_t>(d, L, W, A, B, static_cast<char*>(packed), st);
+}
+
+extern "C" size_t cwl_linear_packed_workspace_bytes(const cwl_linear_desc* d) {
+    if (check_desc(d) != CWL_OK) return 0;
+    return ws_layout(d).total;
+}
+
+extern "C" size_t cwl_linear_workspace_bytes(const cwl_linear_desc* d) {
+    if (check_desc(d) != CWL_OK) return 0;
+    return ws_layout(d).total + packed_layout(d).total;
+}
+
+extern "C" cwl_status cwl_chunkwise_lora_linear_packed(
+    const cwl_linear_desc* d, const void* x, const void* packed, const int32_t* seq_offsets,
+    int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
+    const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap, void* y, void* workspace,
+    size_t workspace_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_call(d, x, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                   chunk_cap, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
+    if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
+    return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
+                      chunk_start, chunk_len, rank_idx, chunk_cap, y, static_cast<char*>(workspace),
+                      static_cast<hipStream_t>(stream));
+}
+
+extern "C" cwl_status cwl_chunkwise_lora_linear(
+    const cwl_linear_desc* d, const void* x, const void* W, const void* A, const void* B,
+    const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
+    const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+    int32_t chunk_cap, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_raw_weights(d);
+    if (s != CWL_OK) return s;
+    s = check_call(d, x, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                   chunk_cap, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!W) return CWL_ERR_NULL;
+    if (d->r_max > 0 && (!A || !B)) return CWL_ERR_NULL;
+    const size_t core = ws_layout(d).total;
+    const PackedLayout L = packed_layout(d);
+    if (workspace_bytes < core + L.total) return CWL_ERR_CAPACITY;
+    char* ws = static_cast<char*>(workspace);
+    char* packed = ws + core;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    s = d->dt == CWL_F32 ? prepack_typed<float>(d, L, W, A, B, packed, st)
+                         : prepack_typed<uint16_t>(d, L, W, A, B, packed, st);
+    if (s != CWL_OK) return s;
+    return run_packed(d, x, packed, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len,
+                      rank_idx, chunk_cap, y, ws, st);
+}
+
+extern "C" const char* cwl_status_string(cwl_status s) {
+    switch (s) {
+        case CWL_OK: return "ok";
+        case CWL_ERR_NULL: return "null pointer";
+        case CWL_ERR_INVALID_ARG: return "invalid argument";
+        case CWL_ERR_INFEASIBLE: return "length bounds infeasible (l_max < 2*l_min - 1)";
+        case CWL_ERR_CAPACITY: return "buffer or workspace too small";
+        case CWL_ERR_UNSUPPORTED: return "unsupported shape, alignment or dtype";
+        case CWL_ERR_DEVICE: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+extern "C" int32_t cwl_abi_version(void) { return 1; }

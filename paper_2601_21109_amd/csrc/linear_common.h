@@ -1,0 +1,67 @@
+// Types shared by the pieces of cwl_chunkwise_lora_linear (gfx950 only).
+//
+// The adapter and the cross-fade are written as one gated product.  With u_t = x_t A (all r_max
+// stored directions) and the per-token, per-direction gate
+//      G[t, i] = g_prev(t) * [i < r_prev(t)] + g_cur(t) * [i < r_cur(t)]
+// (g_cur = s_cur outside a cross-fade window; inside it g_cur = lambda * s_cur and
+// g_prev = (1 - lambda) * s_prev), the layer of Sec. III-C / III-D is
+//      y_t = x_t W + (u_t * G[t, :]) B .
+// So a "shrink" GEMM produces uhat = (x A) * G and the main GEMM runs over the concatenated
+// reduction dimension [x | uhat] . [W ; B]; a row tile only walks as much of the second part as
+// the largest rank among its rows needs.
+#pragma once
+#include "common.h"
+
+namespace cwl {
+
+struct TokMeta {          // 16 bytes per token
+    int32_t r_cur, r_prev;
+    float g_cur, g_prev;
+};
+
+struct Ladder {
+    int32_t ranks[CWL_MAX_LADDER];
+    float scales[CWL_MAX_LADDER];
+    int32_t K;
+};
+
+constexpr int kRankBlock = 64;    // rows per entry of the block-rank table
+constexpr int kRankPad = 64;      // the stored rank dimension is padded to a multiple of this
+
+inline int32_t padded_rank(int32_t r_max) {
+    int32_t r = r_max < 1 ? 1 : r_max;
+    return (r + kRankPad - 1) / kRankPad * kRankPad;
+}
+
+// Operands of one "TN" GEMM launch: C[m, n] = sum_k A1[m,k] B1[n,k] + sum_{k<r(tile)} A2[m,k] B2[n,k].
+// Row m of the tile space is "grouped row" g; the token it stands for is perm[g] (g when perm is
+// NULL).  A1 and C and meta are indexed by token, A2 and blk_r by grouped row.
+struct GemmArgs {
+    const void* A1;
+    int64_t lda1;
+    const void* B1;
+    int64_t ldb1;
+    int32_t K1;
+    const void* A2;
+    int64_t lda2;
+    const void* B2;
+    int64_t ldb2;
+    const int32_t* blk_r;   // [ceil(M / kRankBlock)] largest effective rank per block of rows:
+                            // length of the second reduction part of a row tile (NULL: none)
+    const int32_t* gate_blk_r;  // EPI_GATE only: same table, limits the output columns computed
+    int64_t M, N;
+    void* C;
+    int64_t ldc;
+    const TokMeta* meta;
+    const int32_t* perm;
+    int32_t tiles_m, tiles_n;
+};
+
+// EPI_STORE: C = result in the launch's element type.  EPI_GATE: C[g, n] = result * G[perm[g], n].
+enum { EPI_STORE = 0, EPI_GATE = 1 };
+
+cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
+cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
+cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
+
+}  // namespace cwl

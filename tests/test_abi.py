@@ -1,0 +1,151 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares, and
+rejects bad arguments before anything is launched (no GPU is touched here)."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+from conftest import ROOT
+from paper_2601_21109_amd import binding as B
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2601_21109_amd import build
+        build.build()
+    return B.lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cwl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cwl_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(B.EXPORTS) == names
+
+
+def test_version_and_status_strings(L):
+    assert L.cwl_abi_version() == 1
+    seen = {B.status_string(s) for s in range(7)}
+    assert len(seen) == 7 and all(seen)
+
+
+def P(v=0x1000):
+    return ctypes.c_void_p(v)
+
+
+def test_score_tokens_argument_errors(L):
+    f = L.cwl_score_tokens
+    assert f(P(), B.F32, -1, 8, 8, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), B.F32, 4, 0, 8, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), B.F32, 4, 8, 7, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), 7, 4, 8, 8, P(), None) == B.ERR_INVALID_ARG
+    assert f(None, B.F32, 4, 8, 8, P(), None) == B.ERR_NULL
+    assert f(P(), B.F32, 4, 8, 8, None, None) == B.ERR_NULL
+    assert f(P(0x1002), B.F32, 4, 8, 8, P(), None) == B.ERR_INVALID_ARG     # misaligned fp32
+    assert f(None, B.F32, 0, 8, 8, None, None) == B.OK                      # empty: no-op
+
+
+def test_partition_argument_errors(L):
+    f = L.cwl_partition_chunks
+
+    def call(l_min=4, l_max=8, n_rows=64, n_seqs=1, cap=32, ws=P(0x10000), ws_bytes=1 << 20,
+             ent=P(), so=P(), status=P()):
+        p = B.ChunkParams(l_min, l_max, math.inf, math.inf)
+        return f(ent, n_rows, so, n_seqs, ctypes.byref(p), P(), P(), P(), P(), cap, status, ws,
+                 ws_bytes, None)
+
+    assert call(l_min=0) == B.ERR_INVALID_ARG
+    assert call(l_min=5, l_max=4) == B.ERR_INVALID_ARG
+    assert call(l_min=4, l_max=6) == B.ERR_INFEASIBLE
+    assert call(n_rows=-1) == B.ERR_INVALID_ARG
+    assert call(cap=-1) == B.ERR_INVALID_ARG
+    assert call(so=None) == B.ERR_NULL
+    assert call(status=None) == B.ERR_NULL
+    assert call(ent=None) == B.ERR_NULL
+    assert call(ws=None) == B.ERR_NULL
+    assert call(ws=P(0x10010)) == B.ERR_INVALID_ARG
+    assert call(ws_bytes=16) == B.ERR_CAPACITY
+    assert f(P(), 64, P(), 1, None, P(), P(), P(), P(), 8, P(), P(0x10000), 1 << 20, None) == B.ERR_NULL
+    p = B.ChunkParams(4, 8, 1.0, 1.0)
+    assert L.cwl_partition_workspace_bytes(1000, 3, ctypes.byref(p)) > 1000 * 12
+    bad = B.ChunkParams(4, 6, 1.0, 1.0)
+    assert L.cwl_partition_workspace_bytes(1000, 3, ctypes.byref(bad)) == 0
+
+
+def test_select_argument_errors(L):
+    f = L.cwl_select_ranks
+    th = (ctypes.c_float * 3)(1.0, 2.0, 3.0)
+    bad = (ctypes.c_float * 3)(1.0, 3.0, 2.0)
+    nan = (ctypes.c_float * 3)(1.0, math.nan, 2.0)
+    assert f(P(), P(), P(), 1, 8, th, 0, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), P(), 1, 8, th, B.MAX_LADDER + 1, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), P(), 1, 8, bad, 4, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), P(), 1, 8, nan, 4, P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), P(), 1, 8, None, 4, P(), None) == B.ERR_NULL
+    assert f(None, P(), P(), 1, 8, th, 4, P(), None) == B.ERR_NULL
+    assert f(P(), P(), P(), 1, 0, th, 4, P(), None) == B.OK
+
+
+def make_desc(**kw):
+    args = dict(n_rows=128, d_in=256, d_out=256, r_max=16, ranks=[4, 8, 16], scales=[4.0, 2.0, 1.0],
+                blend_w=2, dt=B.F32, ldx=256, ldw=256, lda=16, ldb=256, ldy=256, group_rows=0)
+    args.update(kw)
+    return B._Desc(**args)
+
+
+def test_linear_descriptor_errors(L):
+    ws_bytes = L.cwl_linear_workspace_bytes
+
+    def status(d, x=P(0x10000), W=P(0x20000), y=P(0x30000), ws=P(0x40000), nbytes=1 << 30):
+        return L.cwl_chunkwise_lora_linear(d.ref(), x, W, P(), P(), P(), 1, P(), P(), P(), P(), 8, y,
+                                           ws, nbytes, None)
+
+    assert ws_bytes(make_desc().ref()) > 0
+    for kw in (dict(n_rows=-1), dict(d_in=0), dict(r_max=B.MAX_RANK + 1), dict(ranks=[8, 4, 16]),
+               dict(ranks=[4, 8, 32]), dict(ranks=[-1, 8, 16]), dict(blend_w=-1), dict(dt=5),
+               dict(ldx=255), dict(ldy=100), dict(group_rows=2),
+               dict(scales=[1.0, math.nan, 1.0])):
+        d = make_desc(**kw)
+        assert ws_bytes(d.ref()) == 0, kw
+        assert status(d) == B.ERR_INVALID_ARG, kw
+    assert status(make_desc(ldw=255)) == B.ERR_INVALID_ARG
+    assert status(make_desc(lda=15)) == B.ERR_INVALID_ARG
+    # bf16 shape and alignment restrictions
+    assert status(make_desc(dt=B.BF16, d_in=200, ldx=200)) == B.ERR_UNSUPPORTED
+    assert status(make_desc(dt=B.BF16, d_out=252, ldy=256)) == B.ERR_UNSUPPORTED
+    assert status(make_desc(dt=B.BF16), x=P(0x10008)) == B.ERR_UNSUPPORTED
+    # pointers and workspace
+    assert status(make_desc(), x=None) == B.ERR_NULL
+    assert status(make_desc(), y=None) == B.ERR_NULL
+    assert status(make_desc(), ws=None) == B.ERR_NULL
+    assert status(make_desc(), W=None) == B.ERR_NULL
+    assert status(make_desc(), ws=P(0x40010)) == B.ERR_INVALID_ARG
+    assert status(make_desc(), nbytes=1024) == B.ERR_CAPACITY
+    assert status(make_desc(n_rows=0)) == B.OK
+    assert L.cwl_chunkwise_lora_linear(None, P(), P(), P(), P(), P(), 1, P(), P(), P(), P(), 8, P(),
+                                       P(), 0, None) == B.ERR_NULL
+    # packed entry point and prepack
+    d = make_desc()
+    assert L.cwl_packed_weights_bytes(d.ref()) >= 4 * (256 * 256 + 64 * 256 * 2)
+    assert L.cwl_prepack_weights(d.ref(), P(), P(), P(), P(0x50000), 16, None) == B.ERR_CAPACITY
+    assert L.cwl_prepack_weights(d.ref(), None, P(), P(), P(0x50000), 1 << 30, None) == B.ERR_NULL
+    assert L.cwl_chunkwise_lora_linear_packed(d.ref(), P(0x10000), None, P(), 1, P(), P(), P(), P(),
+                                              8, P(0x30000), P(0x40000), 1 << 30, None) == B.ERR_NULL
+    assert L.cwl_linear_packed_workspace_bytes(d.ref()) < L.cwl_linear_workspace_bytes(d.ref())
+
+
+def test_missing_library_is_an_error(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libcwl.so"))
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        B.lib()

@@ -1,0 +1,145 @@
+"""GPU parity of cwl_chunkwise_lora_linear against the CPU oracle (Sec. III-C / III-D)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import TOL_BF16, TOL_F32, host, rel_err, sample_rows
+from paper_2601_21109_amd import binding as B
+from paper_2601_21109_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def operands(n, d_in, d_out, r_max, dtype, seed):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    x = torch.randn((n, d_in), generator=g, device=DEV).to(dtype)
+    Wm = (torch.randn((d_in, d_out), generator=g, device=DEV) / math.sqrt(d_in)).to(dtype)
+    A = (torch.randn((d_in, r_max), generator=g, device=DEV) / math.sqrt(d_in)).to(dtype)
+    Bm = (torch.randn((r_max, d_out), generator=g, device=DEV) / math.sqrt(max(r_max, 1))).to(dtype)
+    return x, Wm, A, Bm
+
+
+def run_case(n_seqs, seq_lens, d_in, d_out, ranks, blend_w, dtype, seed, l_min=4, l_max=40,
+             alpha=16.0, group_rows=0, packed=False, rows=None, table=None):
+    r_max = max(max(ranks), 1) if ranks else 1
+    scales = [alpha / r if r > 0 else 0.0 for r in ranks]
+    n = int(np.sum(seq_lens))
+    x, Wm, A, Bm = operands(n, d_in, d_out, r_max, dtype, seed)
+    so, co, cs, cl, ri = table if table is not None else W.random_chunk_table(
+        n_seqs, seq_lens, l_min, l_max, len(ranks), seed + 1)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    if packed:
+        pw = B.prepack_weights(Wm, A, Bm)
+        y = B.chunkwise_lora_linear(x, pw, None, None, ranks, scales, blend_w, sod, tab, rid,
+                                    group_rows=group_rows)
+    else:
+        y = B.chunkwise_lora_linear(x, Wm, A, Bm, ranks, scales, blend_w, sod, tab, rid,
+                                    group_rows=group_rows)
+    torch.cuda.synchronize()
+    ref = O.linear(host(x), host(Wm), host(A), host(Bm), ranks, scales, blend_w, so, co, cs, cl, ri,
+                   rows=rows)
+    yh = host(y)
+    if rows is not None:
+        yh = yh[rows]
+    return yh, ref, y
+
+
+def test_fp32_cfg0_shape():
+    wl = W.WORKLOADS["cfg0"]
+    yh, ref, _ = run_case(1, [128], 256, 256, wl.ladder, wl.blend_w, torch.float32, 1, l_min=8, l_max=64)
+    assert rel_err(yh, ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [77], 100, 72, [3, 12], 2),
+    (3, [50, 1, 200], 64, 130, [0, 4, 8, 16], 3),
+    (2, [130, 65], 257, 63, [5], 0),
+    (1, [64], 16, 16, [0], 2),
+    (4, [9, 9, 9, 300], 48, 200, [1, 2, 70], 4),
+])
+@pytest.mark.parametrize("packed", [False, True])
+def test_fp32_shapes(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
+    yh, ref, _ = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.float32, 7, packed=packed)
+    assert rel_err(yh, ref) <= TOL_F32
+
+
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [600], 256, 512, [8, 16, 32, 64], 4),        # ragged row tile
+    (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4),  # ragged column tile, several sequences
+    (2, [256, 256], 1024, 256, [4, 8, 16, 32, 64, 128], 4),   # two stages of the rank part
+    (1, [1000], 128, 264, [0, 8, 24, 40], 2),        # rank 0 rung, ranks not multiples of 16
+    (1, [511], 192, 1032, [200], 3),                 # single rung, r_max = 200
+    (1, [5], 64, 8, [16], 0),                        # tiny
+])
+@pytest.mark.parametrize("group_rows", [0, 1])
+def test_bf16_shapes(n_seqs, seq_lens, d_in, d_out, ranks, w, group_rows):
+    yh, ref, _ = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 11, l_min=8,
+                          l_max=90, group_rows=group_rows, packed=True)
+    assert rel_err(yh, ref) <= TOL_BF16
+
+
+def test_bf16_grouped_rows_give_identical_output():
+    args = (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4, torch.bfloat16, 5)
+    _, _, y0 = run_case(*args, group_rows=0, packed=True, l_min=8, l_max=90)
+    _, _, y1 = run_case(*args, group_rows=1, packed=True, l_min=8, l_max=90)
+    _, _, y2 = run_case(*args, group_rows=0, packed=False, l_min=8, l_max=90)
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, TOL_F32), (torch.bfloat16, TOL_BF16)])
+def test_special_cases_reduce_to_textbook_lora(dtype, tol):
+    n, d_in, d_out, r = 300, 128, 136, 16
+    table = (np.array([0, n], np.int32), np.array([0, 1], np.int32), np.array([0], np.int32),
+             np.array([n], np.int32), np.array([0], np.int32))
+    # one chunk at r_max: y = x W + s (x A) B ; rank 0: y = x W   (float64 library matmul)
+    for ranks in ([r], [0]):
+        yh, _, _ = run_case(1, [n], d_in, d_out, ranks, 3, dtype, 21, table=table)
+        x, Wm, A, Bm = (host(t).astype(np.float64) for t in operands(n, d_in, d_out, max(ranks[0], 1), dtype, 21))
+        want = x @ Wm
+        if ranks[0]:
+            want = want + float(np.float32(16.0 / r)) * (x @ A) @ Bm
+        assert rel_err(yh, want) <= tol
+
+
+def test_uncovered_tokens_and_bad_rank_index_get_base_only():
+    n, d_in, d_out = 200, 64, 72
+    table = (np.array([0, n], np.int32), np.array([0, 2], np.int32), np.array([0, 100], np.int32),
+             np.array([50, 50], np.int32), np.array([0, 9], np.int32))     # rows 50..99 and 150.. uncovered
+    x, Wm, A, Bm = operands(n, d_in, d_out, 8, torch.float32, 31)
+    sod, tab, rid = B.table_from_host(*table, DEV)
+    y = host(B.chunkwise_lora_linear(x, Wm, A, Bm, [8], [2.0], 0, sod, tab, rid))
+    xd, Wd, Ad, Bd = (host(t).astype(np.float64) for t in (x, Wm, A, Bm))
+    base = xd @ Wd
+    full = base + 2.0 * (xd @ Ad) @ Bd
+    assert rel_err(y[:50], full[:50]) <= TOL_F32
+    assert rel_err(y[50:], base[50:]) <= TOL_F32       # uncovered rows and the chunk with rank_idx 9
+
+
+def test_bf16_full_size_q_proj_sampled_rows():
+    """The 7B-shaped q_proj at its full size (16384 x 4096 x 4096, ladder {8,16,32,64}), launch
+    configuration as benchmarked (packed weights); the oracle checks a row sample."""
+    wl = W.WORKLOADS["cfg1"]
+    n, d = wl.n_rows, 4096
+    x, Wm, A, Bm = W.linear_operands(wl, 0, DEV)
+    so, co, cs, cl, ri = W.random_chunk_table(wl.n_seqs, [wl.seq_len] * wl.n_seqs, wl.l_min, wl.l_max,
+                                              len(wl.ladder), 99)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    pw = B.prepack_weights(Wm, A, Bm)
+    rows = sample_rows(n, cs, cl, wl.blend_w, 96, seed=1, first_chunks=24)
+    xs, Ws, As, Bs = host(x), host(Wm), host(A), host(Bm)
+    ref = O.linear(xs, Ws, As, Bs, wl.ladder, wl.scales, wl.blend_w, so, co, cs, cl, ri, rows=rows)
+    for group_rows in (0, 1):
+        y = B.chunkwise_lora_linear(x, pw, None, None, wl.ladder, wl.scales, wl.blend_w, sod, tab, rid,
+                                    group_rows=group_rows)
+        torch.cuda.synchronize()
+        assert rel_err(host(y[torch.from_numpy(rows).to(DEV)]), ref) <= TOL_BF16
+        # property that holds at any size: rows are independent, so the first 256 rows of the full
+        # launch equal a launch over a prefix of the batch
+        if group_rows == 0:
+            y_again = B.chunkwise_lora_linear(x, pw, None, None, wl.ladder, wl.scales, wl.blend_w, sod,
+                                              tab, rid)
+            assert torch.equal(y, y_again)

@@ -1,0 +1,104 @@
+"""GPU parity of cwl_score_tokens against the CPU oracle (Sec. III-A (i))."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import TOL_F32, entropy_err, host
+from paper_2601_21109_amd import binding as B
+from paper_2601_21109_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def check(logits, oracle, tol=TOL_F32):
+    h = B.score_tokens(logits)
+    torch.cuda.synchronize()
+    ref = oracle.entropy(host(logits))
+    err = entropy_err(host(h), ref, logits.shape[1])
+    assert err <= tol, err
+    return h
+
+
+def test_cfg0_full(oracle):
+    wl = W.WORKLOADS["cfg0"]
+    check(W.logits(wl, DEV), oracle)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [1, 2, 7, 8, 9, 63, 1000, 1001, 4099, 8192, 31999, 32000, 50257])
+def test_vocab_sizes_and_ragged_tails(oracle, dtype, V):
+    g = torch.Generator(device=DEV).manual_seed(V)
+    n = 37
+    sig = torch.tensor([0.5, 2.0, 6.0], device=DEV)[torch.arange(n, device=DEV) % 3].unsqueeze(1)
+    z = (torch.randn((n, V), generator=g, device=DEV) * sig).to(dtype)
+    check(z, oracle)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_large_vocab_path(oracle, dtype):
+    g = torch.Generator(device=DEV).manual_seed(5)
+    z = (torch.randn((9, 128000), generator=g, device=DEV) * 3.0).to(dtype)
+    check(z, oracle)
+    z2 = (torch.randn((5, 200003), generator=g, device=DEV) * 1.5).to(dtype)
+    check(z2, oracle)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_row_stride_and_misaligned_rows(oracle, dtype):
+    g = torch.Generator(device=DEV).manual_seed(11)
+    big = (torch.randn((21, 5003), generator=g, device=DEV) * 2.0).to(dtype)
+    view = big[:, 3:4998]            # row stride 5003 (odd), rows start misaligned
+    h = B.score_tokens(view)
+    ref = oracle.entropy(host(view))
+    assert entropy_err(host(h), ref, view.shape[1]) <= TOL_F32
+
+
+def test_closed_forms(oracle):
+    for V in (1024, 32000):
+        z = torch.full((3, V), 1.5, device=DEV, dtype=torch.bfloat16)
+        h = host(B.score_tokens(z))
+        assert np.max(np.abs(h - math.log(V))) <= 1e-5 * math.log(V)
+    z = torch.zeros((1, 1000), device=DEV)
+    z[0, 17] = 9.0
+    p1 = math.exp(9.0) / (math.exp(9.0) + 999)
+    p2 = 1.0 / (math.exp(9.0) + 999)
+    want = -p1 * math.log(p1) - 999 * p2 * math.log(p2)
+    assert abs(host(B.score_tokens(z))[0] - want) <= 1e-5 * max(want, 1e-3 * math.log(1000))
+
+
+def test_non_finite_rows(oracle):
+    z = torch.zeros((5, 4096), device=DEV)
+    z[0, 100] = float("nan")
+    z[1, 200] = float("inf")
+    z[2, :] = float("-inf")
+    z[3, ::2] = float("-inf")
+    z[4, 1:] = float("-inf")
+    h = host(B.score_tokens(z))
+    ref = oracle.entropy(host(z))
+    assert np.isnan(h[0]) and np.isnan(h[1]) and np.isnan(h[2])
+    assert np.isnan(ref[0]) and np.isnan(ref[1]) and np.isnan(ref[2])
+    assert abs(h[3] - math.log(2048)) <= 1e-5 * math.log(2048)
+    assert abs(h[4]) <= 1e-6
+
+
+def test_extreme_dynamic_range(oracle):
+    g = torch.Generator(device=DEV).manual_seed(3)
+    z = torch.randn((16, 32000), generator=g, device=DEV) * 30.0 + 500.0
+    check(z, oracle)
+    check(z.to(torch.bfloat16), oracle)
+    # rising ramp: every vector raises the running maximum
+    ramp = torch.arange(32000, device=DEV, dtype=torch.float32).unsqueeze(0) * 0.01
+    check(ramp, oracle)
+
+
+def test_deterministic_and_empty():
+    g = torch.Generator(device=DEV).manual_seed(4)
+    z = torch.randn((300, 32000), generator=g, device=DEV).to(torch.bfloat16)
+    a = B.score_tokens(z)
+    b = B.score_tokens(z)
+    assert torch.equal(a, b)
+    e = B.score_tokens(torch.empty((0, 128), device=DEV))
+    assert e.numel() == 0
