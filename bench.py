@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the ChunkWise LoRA hot path on one MI355X.
+
+One step = one pass of the whole hot path over one batch of synthetic input that is already
+resident in HBM: score_tokens -> partition_chunks -> select_ranks -> chunkwise_lora_linear
+(packed weights).  Prints ONE JSON line.  Besides the headline tokens/s it reports the roofline
+position of the dominant kernel (the main MFMA GEMM, timed with HIP events around its launches
+inside the timed region), the scoring kernel's HBM rate, the same linear at fixed r_max and at
+rank 0, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--proj", type=int, default=0)
+    ap.add_argument("--group-rows", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-variants", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2601_21109_amd import binding as B
+    from paper_2601_21109_amd import workloads as W
+
+    dev = "cuda:0"
+    wl = W.WORKLOADS[args.workload]
+    pname, d_in, d_out = wl.projections[args.proj]
+    N, K = wl.n_rows, len(wl.ladder)
+    bf16 = wl.dtype == torch.bfloat16
+
+    # ---- resident inputs --------------------------------------------------------------------
+    so = W.seq_offsets(wl)
+    sod = torch.from_numpy(so).to(dev)
+    logits = W.logits(wl, dev)
+    x, Wm, A, Bm = W.linear_operands(wl, args.proj, dev)
+    packed = B.prepack_weights(Wm, A, Bm)          # static weights: re-laid out once, untimed
+    y = torch.empty((N, d_out), dtype=wl.dtype, device=dev)
+    h = torch.empty(N, dtype=torch.float32, device=dev)
+    ws = B.linear_workspace((N, d_in), wl.dtype, d_out, wl.r_max, wl.ladder, wl.scales, wl.blend_w, dev)
+    table = B.partition_chunks(B.score_tokens(logits, out=h), sod, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+    ri = B.select_ranks(table, wl.taus(), K)
+    torch.cuda.synchronize()
+
+    def step():
+        B.score_tokens(logits, out=h)
+        B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), out=table)
+        B.select_ranks(table, wl.taus(), K, out=ri)
+        B.chunkwise_lora_linear(x, packed, None, None, wl.ladder, wl.scales, wl.blend_w, sod, table, ri,
+                                out=y, group_rows=args.group_rows, workspace=ws)
+
+    def timed(fn, steps, warmup):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        return max(e0.elapsed_time(e1), 0.0) / steps, wall / steps
+
+    # ---- the timed region: K whole-path steps, per-kernel events on -----------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    ms_step, ms_wall = timed(step, args.steps, 0)
+    prof = {name: B.profile_read(slot) for name, slot in
+            (("score", B.PROF_SCORE), ("partition", B.PROF_PARTITION), ("select", B.PROF_SELECT),
+             ("meta", B.PROF_META), ("shrink", B.PROF_SHRINK), ("main", B.PROF_MAIN))}
+    B.profile_enable(False)
+    ms_step = max(ms_step, ms_wall) if ms_step <= 0 else ms_step
+    kern_ms = {k: (v[0] / v[1] if v[1] else None) for k, v in prof.items()}
+
+    # ---- chunk statistics and algorithmic work --------------------------------------------------
+    n_chunks = int(table["chunk_offsets"][-1].item())
+    cl = table["chunk_len"][:n_chunks].cpu().numpy()
+    cs = table["chunk_start"][:n_chunks].cpu().numpy()
+    co = table["chunk_offsets"].cpu().numpy()
+    rk = np.asarray(wl.ladder)[ri[:n_chunks].cpu().numpy()]
+    r_eff = np.zeros(N, dtype=np.int64)
+    for b in range(wl.n_seqs):
+        for c in range(co[b], co[b + 1]):
+            r_eff[cs[c]:cs[c] + cl[c]] = rk[c]
+            if c > co[b] and wl.blend_w:
+                w = min(wl.blend_w, cl[c])
+                r_eff[cs[c]:cs[c] + w] = max(rk[c], rk[c - 1])
+    flops_base = 2.0 * N * d_in * d_out
+    flops_alg = flops_base + 2.0 * float(r_eff.sum()) * (d_in + d_out)     # whole linear
+    flops_main = flops_base + 2.0 * float(r_eff.sum()) * d_out             # what the main kernel runs
+    flops_fixed = flops_base + 2.0 * N * wl.r_max * (d_in + d_out)
+    esz = 2 if bf16 else 4
+
+    out = {
+        "metric": "chunkwise_lora_hot_path_tokens_per_s",
+        "value": N / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}:{pname}", "n_rows": N, "n_seqs": wl.n_seqs,
+                   "seq_len": wl.seq_len, "vocab": wl.vocab, "d_in": d_in, "d_out": d_out,
+                   "ladder": wl.ladder, "l_min": wl.l_min, "l_max": wl.l_max, "blend_w": wl.blend_w,
+                   "group_rows": args.group_rows, "weights": "prepacked"},
+        "kernel_ms": kern_ms,
+        "chunks": {"count": n_chunks, "mean_len": float(cl.mean()) if n_chunks else 0.0,
+                   "tokens_by_rank": {str(r): int(cl[rk == r].sum()) for r in wl.ladder},
+                   "mean_r_eff": float(r_eff.mean())},
+    }
+    if kern_ms["main"]:
+        ach = flops_main / (kern_ms["main"] * 1e-3) / 1e12
+        out["roofline"] = {"kernel": "gemm_bf16_tn_kernel<256,256> (x W + uhat B)" if bf16 else "gemm_f32_tn_kernel",
+                           "bound": "mfma" if bf16 else "alu", "achieved": ach,
+                           "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
+                           "frac": ach / (PEAK_BF16_TFLOPS if bf16 else 157.3), "traffic": None,
+                           "avg_launch_ms": kern_ms["main"], "flops_per_launch": flops_main}
+    if kern_ms["score"]:
+        bytes_score = N * (wl.vocab * esz + 4.0)
+        gbs = bytes_score / (kern_ms["score"] * 1e-3) / 1e9
+        out["roofline_score_tokens"] = {"kernel": "score_tokens_kernel", "bound": "hbm", "achieved": gbs,
+                                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                                        "traffic": None, "avg_launch_ms": kern_ms["score"],
+                                        "bytes_per_launch": bytes_score}
+    lin_ms = sum(kern_ms[k] or 0.0 for k in ("meta", "shrink", "main"))
+    out["linear"] = {"ms": lin_ms, "tokens_per_s": N / (lin_ms * 1e-3) if lin_ms else None,
+                     "effective_tflops": flops_alg / (lin_ms * 1e-3) / 1e12 if lin_ms else None,
+                     "frac_of_bf16_peak": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if lin_ms else None}
+
+    # ---- same kernels at fixed r_max and at rank 0 ------------------------------------------------
+    if not args.no_variants:
+        def variant(ranks, scales):
+            one = np.zeros(n_chunks, dtype=np.int32)
+            rid = torch.from_numpy(one).to(dev)
+            fn = lambda: B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, wl.blend_w, sod,
+                                                 table, rid, out=y, group_rows=args.group_rows, workspace=ws)
+            ms, _ = timed(fn, args.steps, args.warmup)
+            return ms
+        ms_chunk, _ = timed(lambda: B.chunkwise_lora_linear(x, packed, None, None, wl.ladder, wl.scales,
+                                                            wl.blend_w, sod, table, ri, out=y,
+                                                            group_rows=args.group_rows, workspace=ws),
+                            args.steps, args.warmup)
+        ms_fixed = variant([wl.r_max], [wl.alpha / wl.r_max])
+        ms_zero = variant([0], [0.0])
+        out["linear_variants"] = {
+            "chunkwise": {"ms": ms_chunk, "effective_tflops": flops_alg / ms_chunk / 1e9},
+            "fixed_r_max": {"ms": ms_fixed, "effective_tflops": flops_fixed / ms_fixed / 1e9},
+            "rank_0": {"ms": ms_zero, "effective_tflops": flops_base / ms_zero / 1e9},
+            "speedup_vs_fixed_r_max": ms_fixed / ms_chunk,
+            "lora_flop_share_at_r_max": wl.r_max * (d_in + d_out) / (d_in * d_out),
+        }
+
+    # ---- the CPU oracle on a bounded sample of the same workload ---------------------------------
+    if not args.no_cpu_baseline:
+        import oracle as O
+        n_ent = min(N, 2048)
+        n_lin = min(N, 256 if d_in * d_out > 1 << 22 else 2048)
+        rows_e = np.linspace(0, N - 1, n_ent).astype(np.int64)
+        rows_l = np.unique(np.linspace(0, N - 1, n_lin).astype(np.int64))
+        lg = logits[torch.from_numpy(rows_e).to(dev)].float().cpu().numpy()
+        xh, Wh, Ah, Bh = (t.float().cpu().numpy() for t in (x, Wm, A, Bm))
+        hh = h.cpu().numpy()
+        t0 = time.perf_counter(); O.entropy(lg); t_ent = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        q, _ = O.quantise(hh)
+        st, tab = O.partition(q, so, wl.l_min, wl.l_max, O.quantise_threshold(wl.theta()),
+                              O.quantise_threshold(wl.delta()))
+        rid = O.select(tab["chunk_sum"], tab["chunk_len"], [O.quantise_threshold(t) for t in wl.taus()])
+        t_part = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.linear(xh, Wh, Ah, Bh, wl.ladder, wl.scales, wl.blend_w, so, tab["chunk_offsets"],
+                 tab["chunk_start"], tab["chunk_len"], rid, rows=rows_l)
+        t_lin = time.perf_counter() - t0
+        per_tok = t_ent / n_ent + t_part / N + t_lin / len(rows_l)
+        out["cpu_baseline"] = {"value": 1.0 / per_tok, "unit": "tokens/s", "cores": O.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"entropy on {n_ent} rows ({t_ent:.2f} s), partition+select on all "
+                                         f"{N} rows ({t_part:.3f} s), linear on {len(rows_l)} rows "
+                                         f"({t_lin:.2f} s); tokens/s extrapolated from the per-row times"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

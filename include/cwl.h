@@ -186,6 +186,25 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
                                             const int32_t* rank_idx, int32_t chunk_cap, void* y,
                                             void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method): per-kernel durations from HIP events.
+ * cwl_profile_enable(1) creates the events on first use (this is the one place the library
+ * creates runtime objects), zeroes the counters and makes every later launch of a tracked kernel
+ * record an event pair on its stream; cwl_profile_enable(0) stops that.  cwl_profile_read waits
+ * for the recorded launches of `slot` (the most recent 256 at most) and returns their summed
+ * duration in milliseconds and their count.  Host-side, not thread-safe.
+ * ------------------------------------------------------------------------------------------- */
+#define CWL_PROF_SCORE 0      /* the entropy kernel of cwl_score_tokens                  */
+#define CWL_PROF_PARTITION 1  /* all kernels of cwl_partition_chunks                     */
+#define CWL_PROF_SELECT 2     /* the kernel of cwl_select_ranks                          */
+#define CWL_PROF_META 3       /* gate table / grouping kernels of the linear             */
+#define CWL_PROF_SHRINK 4     /* shrink GEMM (x A, gated)                                */
+#define CWL_PROF_MAIN 5       /* main GEMM (x W + uhat B)                                */
+#define CWL_PROF_SLOTS 6
+
+cwl_status cwl_profile_enable(int32_t on);
+cwl_status cwl_profile_read(int32_t slot, double* total_ms /*host*/, int64_t* launches /*host*/);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,8 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
-           "cwl_chunkwise_lora_linear_packed"]
+           "cwl_chunkwise_lora_linear_packed", "cwl_profile_enable", "cwl_profile_read"]
+PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
 
 
 class ChunkParams(ctypes.Structure):
@@ -75,7 +76,9 @@ def lib():
     L.cwl_prepack_weights.argtypes = [dp, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear.argtypes = [dp, P, P, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
-    for name in ("cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
+    L.cwl_profile_enable.argtypes = [i32]
+    L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    for name in ("cwl_profile_enable", "cwl_profile_read", "cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
                  "cwl_prepack_weights", "cwl_chunkwise_lora_linear",
                  "cwl_chunkwise_lora_linear_packed"):
         getattr(L, name).restype = ctypes.c_int
@@ -126,41 +129,44 @@ def score_tokens(logits, out=None):
 
 
 def partition_chunks(entropy, seq_offsets, l_min, l_max, theta_hard=math.inf, delta_dev=math.inf,
-                     cap=None):
+                     cap=None, out=None):
     """Chunk table of the adaptive chunker.  Returns a dict of device tensors
-    (chunk_offsets, chunk_start, chunk_len, chunk_sum, status_word) plus 'cap'."""
+    (chunk_offsets, chunk_start, chunk_len, chunk_sum, status_word) plus 'cap'.  A dict returned
+    by an earlier call of the same shape can be passed as `out` to reuse its buffers."""
     assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
     assert seq_offsets.is_cuda and seq_offsets.dtype == torch.int32
     dev = entropy.device
     n_rows, n_seqs = entropy.numel(), seq_offsets.numel() - 1
     p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
-    if cap is None:
+    if out is not None:
+        cap = out["cap"]
+    elif cap is None:
         cap = n_rows // max(int(l_min), 1) + n_seqs + 1
-    out = {
+    nbytes = lib().cwl_partition_workspace_bytes(n_rows, n_seqs, ctypes.byref(p))
+    out = out if out is not None else {
         "chunk_offsets": torch.empty(n_seqs + 1, dtype=torch.int32, device=dev),
         "chunk_start": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
         "chunk_len": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
         "chunk_sum": torch.empty(max(cap, 1), dtype=torch.int64, device=dev),
         "status_word": torch.empty(1, dtype=torch.int32, device=dev),
         "cap": int(cap),
+        "_workspace": _ws(nbytes, dev),
     }
-    nbytes = lib().cwl_partition_workspace_bytes(n_rows, n_seqs, ctypes.byref(p))
-    ws = _ws(nbytes, dev)
+    ws = out["_workspace"]
     _check(lib().cwl_partition_chunks(_ptr(entropy), n_rows, _ptr(seq_offsets), n_seqs,
                                       ctypes.byref(p), _ptr(out["chunk_offsets"]),
                                       _ptr(out["chunk_start"]), _ptr(out["chunk_len"]),
                                       _ptr(out["chunk_sum"]), int(cap), _ptr(out["status_word"]),
                                       _ptr(ws), ws.numel(), _stream()), "cwl_partition_chunks")
-    out["_workspace"] = ws      # keep alive until the stream has run
     return out
 
 
-def select_ranks(table, thresholds, K):
+def select_ranks(table, thresholds, K, out=None):
     """rank_idx[c] (int32, device) for every chunk of `table` (from partition_chunks)."""
     dev = table["chunk_len"].device
     n_seqs = table["chunk_offsets"].numel() - 1
     cap = table["cap"]
-    rank_idx = torch.zeros(max(cap, 1), dtype=torch.int32, device=dev)
+    rank_idx = out if out is not None else torch.zeros(max(cap, 1), dtype=torch.int32, device=dev)
     th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
     _check(lib().cwl_select_ranks(_ptr(table["chunk_sum"]), _ptr(table["chunk_len"]),
                                   _ptr(table["chunk_offsets"]), n_seqs, cap, th, int(K),
@@ -285,3 +291,15 @@ def table_from_host(seq_offsets, chunk_offsets, chunk_start, chunk_len, rank_idx
     table = {"chunk_offsets": up(chunk_offsets, np.int32), "chunk_start": pad(chunk_start, np.int32),
              "chunk_len": pad(chunk_len, np.int32), "cap": len(chunk_start)}
     return up(seq_offsets, np.int32), table, pad(rank_idx, np.int32)
+
+
+def profile_enable(on=True):
+    """Turn per-kernel HIP-event timing on (and reset it) or off."""
+    _check(lib().cwl_profile_enable(1 if on else 0), "cwl_profile_enable")
+
+
+def profile_read(slot):
+    """(total milliseconds, launches) of the recorded launches of one tracked kernel slot."""
+    ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+    _check(lib().cwl_profile_read(int(slot), ctypes.byref(ms), ctypes.byref(n)), "cwl_profile_read")
+    return ms.value, n.value

@@ -43,4 +43,8 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
     return __uint_as_float(bits16 << 16);
 }
 
+// optional event timing around tracked kernels (profile.hip); no-ops unless enabled
+void prof_begin(int slot, hipStream_t st);
+void prof_end(int slot, hipStream_t st);
+
 }  // namespace cwl

@@ -283,6 +283,7 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     }
     const bool grouped = d->group_rows == 1;
     const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
+    prof_begin(CWL_PROF_META, st);
     token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
         d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
         lad, d->blend_w, meta, grouped ? nullptr : blk_r, grouped ? r_eff : nullptr);
@@ -293,6 +294,7 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
         block_rank_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, perm, blk_r);
         CWL_RETURN_IF_LAUNCH_FAILED();
     }
+    prof_end(CWL_PROF_META, st);
 
     GemmArgs sh = {};
     sh.A1 = x;            sh.lda1 = d->ldx;
@@ -315,14 +317,14 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     mn.meta = meta;       mn.perm = grouped ? perm : nullptr;
 
     cwl_status s;
-    if (d->dt == CWL_F32) {
-        s = launch_gemm_f32(sh, EPI_GATE, st);
-        if (s != CWL_OK) return s;
-        return launch_gemm_f32(mn, EPI_STORE, st);
-    }
-    s = launch_shrink_bf16(sh, st);
+    prof_begin(CWL_PROF_SHRINK, st);
+    s = d->dt == CWL_F32 ? launch_gemm_f32(sh, EPI_GATE, st) : launch_shrink_bf16(sh, st);
+    prof_end(CWL_PROF_SHRINK, st);
     if (s != CWL_OK) return s;
-    return launch_main_bf16(mn, st);
+    prof_begin(CWL_PROF_MAIN, st);
+    s = d->dt == CWL_F32 ? launch_gemm_f32(mn, EPI_STORE, st) : launch_main_bf16(mn, st);
+    prof_end(CWL_PROF_MAIN, st);
+    return s;
 }
 
 cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* seq_offsets,

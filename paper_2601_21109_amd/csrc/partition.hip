@@ -308,6 +308,7 @@ extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t theta_q = cwl::quantise_threshold(p->theta_hard);
     const int64_t delta_q = cwl::quantise_threshold(p->delta_dev);
+    cwl::prof_begin(CWL_PROF_PARTITION, s);
     partition_init_kernel<<<1, 1, 0, s>>>(status_word);
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (n_seqs == 0) {
@@ -321,6 +322,7 @@ extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
     CWL_RETURN_IF_LAUNCH_FAILED();
     partition_compact_kernel<<<dim3((unsigned)n_seqs), dim3(kThreads), 0, s>>>(
         n_seqs, ws, chunk_offsets, chunk_start, chunk_len, chunk_sum, cap, status_word);
+    cwl::prof_end(CWL_PROF_PARTITION, s);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }
@@ -341,8 +343,10 @@ extern "C" cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* 
     if (!chunk_sum || !chunk_len || !chunk_offsets || !rank_idx) return CWL_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const unsigned blocks = (unsigned)((cap + 255) / 256);
+    cwl::prof_begin(CWL_PROF_SELECT, s);
     select_ranks_kernel<<<dim3(blocks), dim3(256), 0, s>>>(chunk_sum, chunk_len, chunk_offsets,
                                                            n_seqs, cap, th, K, rank_idx);
+    cwl::prof_end(CWL_PROF_SELECT, s);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }

@@ -170,6 +170,7 @@ cwl_status launch(const void* logits, int64_t n_rows, int64_t vocab, int64_t row
                   float* entropy, hipStream_t st) {
     const int64_t row_bytes = vocab * (int64_t)sizeof(T);
     const T* lp = static_cast<const T*>(logits);
+    cwl::prof_begin(CWL_PROF_SCORE, st);
     if (row_bytes <= 16 * 1024) {
         const int64_t blocks = (n_rows + 3) / 4;
         score_tokens_kernel<T, 1><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
@@ -178,6 +179,7 @@ cwl_status launch(const void* logits, int64_t n_rows, int64_t vocab, int64_t row
     } else {
         score_tokens_kernel<T, 16><<<dim3((unsigned)n_rows), dim3(1024), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
     }
+    cwl::prof_end(CWL_PROF_SCORE, st);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }
