@@ -3,13 +3,21 @@
 // One "TN" GEMM kernel, C[m, n] = sum_k A[m, k] B[n, k], both operands K-contiguous, is used
 // twice: as the shrink (A = x, B = A^T, epilogue multiplies by the gate and writes uhat) and as
 // the main product over the concatenated reduction dimension [x | uhat] . [W^T | B^T]^T, where a
-// row tile only walks ceil(r_tile / 16) MFMA steps of the second part.
+// row tile only walks ceil(r_tile / 32) stages of the second part.
 //
-// Data path (gfx950): global -> LDS with global_load_lds_dwordx4 (no staging registers), two
-// LDS stages of BK = 64; LDS rows are 128 bytes with the 16-byte chunk index XOR-swizzled by
-// (row / 2) % 8 so that ds_read_b128 of 16 consecutive rows touches 16 distinct bank groups;
-// v_mfma_f32_32x32x16_bf16 with fp32 accumulators.  The weight fragment is the MFMA's first
-// operand, so each lane ends up with 4 consecutive output columns of one row and stores 8 bytes.
+// Data path (gfx950):
+//   * global -> LDS with global_load_lds_dwordx4 (no staging registers) into a ring of NST
+//     stages of BK = 32 (64-byte LDS rows, the 16-byte chunk index XOR-swizzled by (row / 4) % 4
+//     so that ds_read_b128 of 16 consecutive rows touches all 64 banks once).  NST - 1 stages are
+//     in flight while one is consumed: the L2 / fabric latency under load is far longer than one
+//     stage of MFMA work, and a two-stage scheme measured latency-bound.
+//   * LDS -> registers with ds_read_b128, fragments double buffered: the two k-steps of a stage
+//     alternate between two register sets, the next set is fetched while the MFMAs of the
+//     current one run.
+//   * v_mfma_f32_32x32x16_bf16, fp32 accumulators.  The weight fragment is the MFMA's first
+//     operand, so each lane ends with 4 consecutive output columns of one row (8-byte stores).
+//   * one workgroup barrier per stage, placed between the two k-steps: by then this wave's
+//     fragment reads of the stage are in registers and its loads of the next stage have landed.
 #include "linear_common.h"
 
 namespace cwl {
@@ -19,8 +27,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
-constexpr int BK = 64;            // elements of K per LDS stage
-constexpr int ROW_BYTES = BK * 2;  // 128
+constexpr int BK = 32;             // elements of K per LDS stage
+constexpr int ROW_BYTES = BK * 2;  // 64
 
 __device__ __forceinline__ void load_lds_16(const void* gptr, char* lds_wave_base) {
     __builtin_amdgcn_global_load_lds(
@@ -28,10 +36,18 @@ __device__ __forceinline__ void load_lds_16(const void* gptr, char* lds_wave_bas
         (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 
+// s_waitcnt with explicit counts (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] |
+// vmcnt[5:4] at [15:14]); expcnt is left at its maximum.
+template <int VM, int LGKM>
+__device__ __forceinline__ void wait_cnt() {
+    static_assert(VM >= 0 && VM < 64 && LGKM >= 0 && LGKM < 16, "counter range");
+    __builtin_amdgcn_s_waitcnt((VM & 15) | (7 << 4) | ((LGKM & 15) << 8) | ((VM >> 4) << 14));
+}
+
 // Workgroup id -> (row tile, column tile).  Consecutive workgroup ids go round-robin over the 8
 // XCDs, each with its own L2, so XCD x is given the x-th contiguous eighth of a tile order in
-// which GROUP_M row tiles sweep all column tiles before moving on: the tiles in flight on one
-// XCD share a few x panels and walk the same weight panels.
+// which GROUP_M row tiles sweep all column tiles before moving on: the 32 tiles in flight on one
+// XCD form an 8 x 4 patch that shares 8 x panels and 4 weight panels.
 __device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* bm, int* bn) {
     constexpr int kXcd = 8, GROUP_M = 8;
     const int64_t n_tiles = (int64_t)tiles_m * tiles_n;
@@ -49,27 +65,30 @@ __device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* bm, i
     return true;
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int NST, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) {
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;     // wave tile
     constexpr int MI = TM / 32, NI = TN / 32;     // 32x32 MFMA blocks per wave tile
     constexpr int ROWS = BM + BN;
-    constexpr int LOADS = ROWS / 8 / NW;          // 1 KiB load instructions per wave per stage
+    constexpr int LOADS = ROWS / 16 / NW;         // 1 KiB load instructions per wave per stage
     constexpr int STAGE_BYTES = ROWS * ROW_BYTES;
-    static_assert(ROWS % (8 * NW) == 0, "tile rows must split evenly over the waves");
+    constexpr int N_DS = MI + NI, N_MFMA = MI * NI;
+    static_assert(ROWS % (16 * NW) == 0, "tile rows must split evenly over the waves");
     static_assert(BM % 16 == 0 && BN % 16 == 0 && TM % 32 == 0 && TN % 32 == 0, "tile shape");
     static_assert(BM % kRankBlock == 0, "row tile must cover whole rank blocks");
+    static_assert(NST >= 2 && (NST - 1) * LOADS < 64, "ring depth");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int bm, bn;
     if (!tile_coords(a.tiles_m, a.tiles_n, &bm, &bn)) return;
     const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: stage addresses stay in SGPRs
     const int wm = wave / WN, wn = wave % WN;
 
-    // largest effective rank among the rows of this tile
+    // largest effective rank among the rows of this tile: length of the second reduction part
     int32_t r_tile = 0;
     if (a.blk_r) {
         const int64_t n_blk = (a.M + kRankBlock - 1) / kRankBlock;
@@ -82,7 +101,23 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
             }
         }
     }
-    // ---- loader set-up: instruction j of this wave fills rows 8j .. 8j+7 of the stage ----
+    // shrink: output columns (adapter directions) at or beyond the block's largest effective rank
+    // are gated to zero anyway, so their MFMAs are skipped; a rank-0 block skips the whole loop
+    bool ni_on[NI];
+#pragma unroll
+    for (int ni = 0; ni < NI; ++ni) ni_on[ni] = true;
+    int KS = a.K1 / BK;                               // stages of the first part
+    if (EPI == EPI_GATE && a.gate_blk_r) {
+        const int32_t r_blk = a.gate_blk_r[m0 / kRankBlock];
+#pragma unroll
+        for (int ni = 0; ni < NI; ++ni) ni_on[ni] = (wn * TN + ni * 32) < r_blk;
+        if (r_blk == 0) KS = 0;
+    }
+    const int TS = (r_tile + BK - 1) / BK;            // stages of the second part (uhat columns
+                                                      // beyond a row's rank are zero)
+    const int S = KS + TS;
+
+    // ---- loader set-up: instruction j of this wave fills rows 16j .. 16j+15 of the stage ----
     const __bf16* gp[LOADS];          // current global address of this lane's 16 bytes
     int32_t grow[LOADS];              // row in the second operand pair (grouped row / column)
     int lchunk[LOADS];
@@ -90,10 +125,10 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
         const int j = wave * LOADS + i;
-        const int row_cat = 8 * j + (lane >> 3);
-        is_a[i] = (8 * j) < BM;                       // wave-uniform
+        const int row_cat = 16 * j + (lane >> 2);
+        is_a[i] = (16 * j) < BM;                      // wave-uniform
         const int r = is_a[i] ? row_cat : row_cat - BM;
-        lchunk[i] = (lane & 7) ^ ((r >> 1) & 7);
+        lchunk[i] = (lane & 3) ^ ((r >> 2) & 3);
         if (is_a[i]) {
             int64_t g = m0 + r;
             if (g > a.M - 1) g = a.M - 1;
@@ -107,22 +142,33 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
             gp[i] = static_cast<const __bf16*>(a.B1) + n * a.ldb1 + lchunk[i] * 8;
         }
     }
-
-    auto issue_loads = [&](int stage) {
-        char* base = smem + stage * STAGE_BYTES + wave * LOADS * 1024;
+    int issued = 0;                   // stages issued so far (wave-uniform)
+    auto issue_next = [&](int buf) {
+        if (issued == KS) {
+            // switch the loaders to the second operand pair (uhat, B^T)
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) {
+                if (is_a[i])
+                    gp[i] = static_cast<const __bf16*>(a.A2) + (int64_t)grow[i] * a.lda2 + lchunk[i] * 8;
+                else
+                    gp[i] = static_cast<const __bf16*>(a.B2) + (int64_t)grow[i] * a.ldb2 + lchunk[i] * 8;
+            }
+        }
+        char* base = smem + buf * STAGE_BYTES + wave * LOADS * 1024;
 #pragma unroll
         for (int i = 0; i < LOADS; ++i) {
             load_lds_16(gp[i], base + i * 1024);
             gp[i] += BK;
         }
+        ++issued;
     };
 
     // ---- fragment addressing ----
     const int l32 = lane & 31, h = lane >> 5;
-    const int sw = (l32 >> 1) & 7;
-    int koff[4];
+    const int sw = (l32 >> 2) & 3;
+    int koff[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + h) ^ sw) * 16;
+    for (int kk = 0; kk < 2; ++kk) koff[kk] = ((2 * kk + h) ^ sw) * 16;
     const int a_base = (wm * TM + l32) * ROW_BYTES;
     const int b_base = BM * ROW_BYTES + (wn * TN + l32) * ROW_BYTES;
 
@@ -134,68 +180,86 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.0f;
 
-    // shrink: output columns (adapter directions) at or beyond the block's largest effective rank
-    // are gated to zero anyway, so their MFMAs are skipped; a rank-0 block skips the whole loop
-    bool ni_on[NI];
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto read_frags = [&](int buf, int kk, int f) {
+        const char* sb = smem + buf * STAGE_BYTES;
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni) ni_on[ni] = true;
-    int KS = a.K1 / BK;                               // stages of the first part
-    if (EPI == EPI_GATE && a.gate_blk_r) {
-        const int32_t r_blk = a.gate_blk_r[m0 / kRankBlock];
+        for (int mi = 0; mi < MI; ++mi)
+            af[f][mi] = *reinterpret_cast<const bf16x8*>(sb + a_base + mi * 32 * ROW_BYTES + koff[kk]);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) ni_on[ni] = (wn * TN + ni * 32) < r_blk;
-        if (r_blk == 0) KS = 0;
-    }
-    const int TS = (r_tile + BK - 1) / BK;            // stages of the second part
-    const int S = KS + TS;
-    const int last_steps = (r_tile - (TS - 1) * BK + 15) / 16;   // MFMA k-steps of the last stage
-
-    auto compute = [&](int stage, int steps) {
-        const char* sb = smem + stage * STAGE_BYTES;
+        for (int ni = 0; ni < NI; ++ni)
+            bfr[f][ni] = *reinterpret_cast<const bf16x8*>(sb + b_base + ni * 32 * ROW_BYTES + koff[kk]);
+    };
+    auto mfma_step = [&](int f) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            if (kk < steps) {   // steps is 4 (a constant after inlining) except in the last stage
-                bf16x8 af[MI], bfr[NI];
+        for (int ni = 0; ni < NI; ++ni)
+            if (EPI != EPI_GATE || ni_on[ni])
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    af[mi] = *reinterpret_cast<const bf16x8*>(sb + a_base + mi * 32 * ROW_BYTES + koff[kk]);
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    bfr[ni] = *reinterpret_cast<const bf16x8*>(sb + b_base + ni * 32 * ROW_BYTES + koff[kk]);
-#pragma unroll
-                for (int ni = 0; ni < NI; ++ni)
-                    if (ni_on[ni])
-#pragma unroll
-                        for (int mi = 0; mi < MI; ++mi)
-                            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ni], af[mi], acc[ni][mi], 0, 0, 0);
-            }
+                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[f][ni], af[f][mi], acc[ni][mi], 0, 0, 0);
+    };
+    // issue order inside a group: one MFMA (its operands are already in registers), then the LDS
+    // reads of the next k-step, then the rest
+    auto order_first_half = [&]() {
+        if (EPI == EPI_STORE) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, N_DS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA - 1, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto order_second_half = [&]() {
+        if (EPI == EPI_STORE) {
+            __builtin_amdgcn_sched_group_barrier(0x100, N_DS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, LOADS, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, N_MFMA - 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto stage_barrier = [&]() {
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- main loop: two LDS stages, loads of stage s+1 overlap the MFMAs of stage s ----
-    // Only the last stage of the second part can be partial; it is peeled off the loop.
-    const int n_full = (TS > 0) ? S - 1 : S;
-    if (S > 0) issue_loads(0);
-    for (int s = 0; s < n_full; ++s) {
-        __syncthreads();   // waits for this wave's loads, then for everyone's
-        if (s + 1 < S) {
-            if (s + 1 == KS) {
-                // switch the loaders to the second operand pair (uhat, B^T)
+    // ---- prologue: fill the ring, wait for stage 0 ----
 #pragma unroll
-                for (int i = 0; i < LOADS; ++i) {
-                    if (is_a[i])
-                        gp[i] = static_cast<const __bf16*>(a.A2) + (int64_t)grow[i] * a.lda2 + lchunk[i] * 8;
-                    else
-                        gp[i] = static_cast<const __bf16*>(a.B2) + (int64_t)grow[i] * a.ldb2 + lchunk[i] * 8;
-                }
-            }
-            issue_loads((s + 1) & 1);
-        }
-        compute(s & 1, 4);
+    for (int p = 0; p < NST; ++p)
+        if (p < S) issue_next(p);
+    if (S >= NST) wait_cnt<(NST - 1) * LOADS, 15>();
+    else wait_cnt<0, 15>();
+    stage_barrier();
+    if (S > 0) read_frags(0, 0, 0);
+    int buf = 0;
+    int s = 0;
+    // ---- steady state: stage s releases its buffer to stage s + NST ----
+    for (; s + NST < S; ++s) {
+        const int nxt = (buf + 1 == NST) ? 0 : buf + 1;
+        read_frags(buf, 1, 1);
+        mfma_step(0);
+        order_first_half();
+        wait_cnt<(NST - 2) * LOADS, 0>();   // my reads of this stage are in registers, my loads of
+        stage_barrier();                    // stage s+1 have landed ... and everybody's
+        read_frags(nxt, 0, 0);
+        issue_next(buf);
+        mfma_step(1);
+        order_second_half();
+        buf = nxt;
     }
-    if (TS > 0) {
-        __syncthreads();
-        compute((S - 1) & 1, last_steps);
+    // ---- drain: nothing left to issue ----
+    for (; s < S; ++s) {
+        const int nxt = (buf + 1 == NST) ? 0 : buf + 1;
+        read_frags(buf, 1, 1);
+        mfma_step(0);
+        order_first_half();
+        if (s + 1 < S) {
+            wait_cnt<0, 0>();
+            stage_barrier();
+            read_frags(nxt, 0, 0);
+        }
+        mfma_step(1);
+        __builtin_amdgcn_sched_barrier(0);
+        buf = nxt;
     }
 
     // ---- epilogue ----
@@ -232,10 +296,11 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     }
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+template <int BM, int BN, int WM, int WN, int NST, int EPI>
 cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
-    constexpr int smem_bytes = 2 * (BM + BN) * ROW_BYTES;
-    auto kern = gemm_bf16_tn_kernel<BM, BN, WM, WN, EPI>;
+    constexpr int smem_bytes = NST * (BM + BN) * ROW_BYTES;
+    static_assert(smem_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+    auto kern = gemm_bf16_tn_kernel<BM, BN, WM, WN, NST, EPI>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -257,17 +322,19 @@ cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
 }  // namespace
 
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
+    // 64-row tiles (one rank block), all padded directions as columns; deep rings because the
+    // shrink streams x once and is bound by memory latency x bytes in flight
     switch (a.N) {
-        case 64: return launch_cfg<64, 64, 2, 2, EPI_GATE>(a, st);
-        case 128: return launch_cfg<64, 128, 2, 2, EPI_GATE>(a, st);
-        case 192: return launch_cfg<64, 192, 2, 2, EPI_GATE>(a, st);
-        case 256: return launch_cfg<64, 256, 2, 2, EPI_GATE>(a, st);
+        case 64: return launch_cfg<64, 64, 2, 2, 8, EPI_GATE>(a, st);
+        case 128: return launch_cfg<64, 128, 2, 2, 6, EPI_GATE>(a, st);
+        case 192: return launch_cfg<64, 192, 2, 2, 4, EPI_GATE>(a, st);
+        case 256: return launch_cfg<64, 256, 2, 2, 4, EPI_GATE>(a, st);
         default: return CWL_ERR_UNSUPPORTED;
     }
 }
 
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st) {
-    return launch_cfg<256, 256, 2, 4, EPI_STORE>(a, st);
+    return launch_cfg<256, 256, 2, 4, 4, EPI_STORE>(a, st);
 }
 
 }  // namespace cwl
