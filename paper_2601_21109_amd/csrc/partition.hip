@@ -7,8 +7,8 @@
 // and a ballot picks the first admissible end at which a test fires.  Chunks go to a staging
 // area whose per-sequence offset is the worst-case chunk count of the preceding sequences.
 // (Well-formed offsets never overflow the staging area; writes are bounds-checked all the same.)
-// Kernel 2 (one workgroup per sequence): turns the per-sequence counts into CSR offsets and
-// copies the staged chunks to their final place.
+// Kernel 2 (one workgroup per sequence): turns the per-sequence counts into CSR offsets, copies the
+// staged chunks to their final place and writes the status word.
 #include "common.h"
 
 namespace {
@@ -26,6 +26,7 @@ struct PartWs {             // layout of the workspace
     int64_t* st_sum;        // [stage_cap]
     int32_t* seq_count;     // [n_seqs]
     int32_t* seq_stage;     // [n_seqs]
+    int32_t* seq_status;    // [n_seqs] status bits met in each sequence
     int64_t stage_cap;
 };
 
@@ -46,6 +47,7 @@ __host__ size_t part_ws_layout(int64_t n_rows, int32_t n_seqs, int32_t l_min, vo
     size_t o_len = take(sizeof(int32_t) * (size_t)stage_cap);
     size_t o_cnt = take(sizeof(int32_t) * (size_t)(n_seqs + 1));
     size_t o_stage = take(sizeof(int32_t) * (size_t)(n_seqs + 1));
+    size_t o_status = take(sizeof(int32_t) * (size_t)(n_seqs + 1));
     if (ws) {
         ws->P = reinterpret_cast<int64_t*>(b + o_P);
         ws->st_sum = reinterpret_cast<int64_t*>(b + o_sum);
@@ -54,6 +56,7 @@ __host__ size_t part_ws_layout(int64_t n_rows, int32_t n_seqs, int32_t l_min, vo
         ws->st_len = reinterpret_cast<int32_t*>(b + o_len);
         ws->seq_count = reinterpret_cast<int32_t*>(b + o_cnt);
         ws->seq_stage = reinterpret_cast<int32_t*>(b + o_stage);
+        ws->seq_status = reinterpret_cast<int32_t*>(b + o_status);
         ws->stage_cap = stage_cap;
     }
     if (stage_cap_out) *stage_cap_out = stage_cap;
@@ -101,32 +104,13 @@ __device__ __forceinline__ int64_t chunk_bound(int64_t T, int32_t l_min) {
 
 __global__ void partition_init_kernel(int32_t* status_word) { *status_word = 0; }
 
-__global__ void __launch_bounds__(kThreads)
-partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
-                     const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t l_min,
-                     int32_t l_max, int64_t theta_q, int64_t delta_q, PartWs ws,
-                     int32_t* status_word) {
-    __shared__ int64_t red[4];
-    __shared__ int64_t wave_tot[4];
+constexpr int kLdsTokens = 8192;   // sequences up to this length keep q and P in LDS
+constexpr size_t kLdsBytes = sizeof(int64_t) * (kLdsTokens + 1) + sizeof(int32_t) * kLdsTokens;
+
+// Quantise the scores of one sequence and scan them: q[t], P[t+1] = q[0] + .. + q[t], P[0] = 0.
+__device__ void quantise_and_scan(const float* __restrict__ h, int64_t T, int32_t* q, int64_t* P,
+                                  int64_t* wave_tot /*LDS[4]*/, bool* saw_nan) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int32_t b = blockIdx.x;
-    bool bad = false, saw_nan = false;
-    int64_t base, T;
-    seq_extent(seq_offsets, b, n_rows, &base, &T, &bad);
-    if (b == n_seqs - 1 && (int64_t)seq_offsets[n_seqs] != n_rows) bad = true;
-
-    // staging offset: worst-case chunk count of the sequences before this one
-    int64_t mine = 0;
-    for (int32_t bb = tid; bb < b; bb += kThreads) {
-        int64_t s0, t0;
-        bool ignore = false;
-        seq_extent(seq_offsets, bb, n_rows, &s0, &t0, &ignore);
-        mine += chunk_bound(t0, l_min);
-    }
-    const int64_t stage_off = block_sum_i64(mine, red);
-
-    // quantise + inclusive scan of q into P (T + 1 entries for this sequence)
-    const int64_t pbase = base + b;
     int64_t carry = 0;
     for (int64_t t0 = 0; t0 < T; t0 += kThreads * kItems) {
         const int64_t idx0 = t0 + (int64_t)tid * kItems;
@@ -137,8 +121,8 @@ partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
             const int64_t t = idx0 + i;
             int32_t qv = 0;
             if (t < T) {
-                qv = quantise_score(entropy[base + t], &saw_nan);
-                ws.q[base + t] = qv;
+                qv = quantise_score(h[t], saw_nan);
+                q[t] = qv;
             }
             sum += qv;
             local[i] = sum;
@@ -162,19 +146,19 @@ partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
 #pragma unroll
         for (int i = 0; i < kItems; ++i) {
             const int64_t t = idx0 + i;
-            if (t < T) ws.P[pbase + t + 1] = excl + local[i];
+            if (t < T) P[t + 1] = excl + local[i];
         }
         carry += total;
     }
-    if (tid == 0) ws.P[pbase] = 0;
-    if (bad) atomicOr(status_word, (int32_t)CWL_STATUS_BAD_OFFSETS);
-    if (saw_nan) atomicOr(status_word, (int32_t)CWL_STATUS_NAN_SCORE);
-    __syncthreads();   // P and q of this sequence are visible to the whole workgroup
+    if (tid == 0) P[0] = 0;
+}
 
-    if (wave != 0) return;
-    // ---- boundary placement by one wavefront ----
-    const int64_t* P = ws.P + pbase;
-    const int32_t* q = ws.q + base;
+// Boundary placement for one sequence by one wavefront: 64 candidate ends per step, a ballot picks
+// the first admissible end at which a test fires.  Returns the number of chunks.
+__device__ int32_t place_boundaries(const int32_t* q, const int64_t* P, int64_t base, int64_t T,
+                                    int32_t l_min, int32_t l_max, int64_t theta_q, int64_t delta_q,
+                                    const PartWs& ws, int64_t stage_off) {
+    const int lane = threadIdx.x & 63;
     int32_t n_chunks = 0;
     if (T > 0 && T < l_min) {
         if (lane == 0 && stage_off < ws.stage_cap) {
@@ -182,47 +166,94 @@ partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
             ws.st_len[stage_off] = (int32_t)T;
             ws.st_sum[stage_off] = P[T];
         }
-        n_chunks = 1;
-    } else {
-        int64_t p = 0;
-        while (p < T) {
-            const int64_t e_hi = (p + l_max < T) ? p + l_max : T;
-            int64_t e_star = (T - p <= l_max) ? T : ((p + l_max < T - l_min) ? p + l_max : T - l_min);
-            const int64_t Pp = P[p];
-            for (int64_t e0 = p + l_min; e0 <= e_hi; e0 += 64) {
-                const int64_t e = e0 + lane;
-                bool fire = false;
-                if (e <= e_hi && (e <= T - l_min || e == T)) {
-                    if (e == T) {
-                        fire = true;
-                    } else {
-                        const int64_t n = e - p;
-                        const int64_t S = P[e] - Pp;
-                        const int64_t qe = q[e];
-                        int64_t d = qe * n - S;
-                        if (d < 0) d = -d;
-                        fire = (S >= theta_q * n) || (qe >= theta_q) || (d > delta_q * n);
-                    }
-                }
-                const unsigned long long mask = __ballot(fire);
-                if (mask) {
-                    e_star = e0 + (__ffsll(mask) - 1);
-                    break;
-                }
-            }
-            const int64_t slot = stage_off + n_chunks;
-            if (lane == 0 && slot < ws.stage_cap) {
-                ws.st_start[slot] = (int32_t)(base + p);
-                ws.st_len[slot] = (int32_t)(e_star - p);
-                ws.st_sum[slot] = P[e_star] - Pp;
-            }
-            ++n_chunks;
-            p = e_star;
-        }
+        return 1;
     }
-    if (lane == 0) {
+    int64_t p = 0;
+    while (p < T) {
+        const int64_t e_hi = (p + l_max < T) ? p + l_max : T;
+        int64_t e_star = (T - p <= l_max) ? T : ((p + l_max < T - l_min) ? p + l_max : T - l_min);
+        const int64_t Pp = P[p];
+        for (int64_t e0 = p + l_min; e0 <= e_hi; e0 += 64) {
+            const int64_t e = e0 + lane;
+            bool fire = false;
+            if (e <= e_hi && (e <= T - l_min || e == T)) {
+                if (e == T) {
+                    fire = true;
+                } else {
+                    const int64_t n = e - p;
+                    const int64_t S = P[e] - Pp;
+                    const int64_t qe = q[e];
+                    int64_t d = qe * n - S;
+                    if (d < 0) d = -d;
+                    fire = (S >= theta_q * n) || (qe >= theta_q) || (d > delta_q * n);
+                }
+            }
+            const unsigned long long mask = __ballot(fire);
+            if (mask) {
+                e_star = e0 + (__ffsll(mask) - 1);
+                break;
+            }
+        }
+        const int64_t slot = stage_off + n_chunks;
+        if (lane == 0 && slot < ws.stage_cap) {
+            ws.st_start[slot] = (int32_t)(base + p);
+            ws.st_len[slot] = (int32_t)(e_star - p);
+            ws.st_sum[slot] = P[e_star] - Pp;
+        }
+        ++n_chunks;
+        p = e_star;
+    }
+    return n_chunks;
+}
+
+__global__ void __launch_bounds__(kThreads)
+partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
+                     const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t l_min,
+                     int32_t l_max, int64_t theta_q, int64_t delta_q, PartWs ws) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    __shared__ int64_t red[4];
+    __shared__ int64_t wave_tot[4];
+    const int tid = threadIdx.x, wave = tid >> 6;
+    const int32_t b = blockIdx.x;
+    bool bad = false, saw_nan = false;
+    int64_t base, T;
+    seq_extent(seq_offsets, b, n_rows, &base, &T, &bad);
+    if (b == n_seqs - 1 && (int64_t)seq_offsets[n_seqs] != n_rows) bad = true;
+
+    // staging offset: worst-case chunk count of the sequences before this one
+    int64_t mine = 0;
+    for (int32_t bb = tid; bb < b; bb += kThreads) {
+        int64_t s0, t0;
+        bool ignore = false;
+        seq_extent(seq_offsets, bb, n_rows, &s0, &t0, &ignore);
+        mine += chunk_bound(t0, l_min);
+    }
+    const int64_t stage_off = block_sum_i64(mine, red);
+
+    // q and P of this sequence live in LDS when they fit (the boundary placement is a chain of
+    // dependent look-ups, so their latency is the run time), else in the workspace
+    const bool in_lds = T <= kLdsTokens;
+    int32_t n_chunks;
+    if (in_lds) {
+        int64_t* P = reinterpret_cast<int64_t*>(lds_raw);
+        int32_t* q = reinterpret_cast<int32_t*>(lds_raw + sizeof(int64_t) * (kLdsTokens + 1));
+        quantise_and_scan(entropy + base, T, q, P, wave_tot, &saw_nan);
+        __syncthreads();
+        n_chunks = wave == 0 ? place_boundaries(q, P, base, T, l_min, l_max, theta_q, delta_q, ws, stage_off) : 0;
+    } else {
+        int64_t* P = ws.P + base + b;
+        int32_t* q = ws.q + base;
+        quantise_and_scan(entropy + base, T, q, P, wave_tot, &saw_nan);
+        __syncthreads();   // P and q of this sequence are visible to the whole workgroup
+        n_chunks = wave == 0 ? place_boundaries(q, P, base, T, l_min, l_max, theta_q, delta_q, ws, stage_off) : 0;
+    }
+    // status bits met in this sequence, combined over sequences by the compact kernel
+    const int32_t nan_any = __syncthreads_or(saw_nan ? 1 : 0);
+    const int32_t bad_any = __syncthreads_or(bad ? 1 : 0);
+    if (tid == 0) {
         ws.seq_count[b] = n_chunks;
         ws.seq_stage[b] = (int32_t)stage_off;
+        ws.seq_status[b] = (nan_any ? (int32_t)CWL_STATUS_NAN_SCORE : 0) | (bad_any ? (int32_t)CWL_STATUS_BAD_OFFSETS : 0);
     }
 }
 
@@ -241,7 +272,19 @@ partition_compact_kernel(int32_t n_seqs, PartWs ws, int32_t* __restrict__ chunk_
     if (tid == 0) {
         chunk_offsets[b] = (int32_t)first;
         if (b == n_seqs - 1) chunk_offsets[n_seqs] = (int32_t)(first + count);
-        if (first + count > cap) atomicOr(status_word, (int32_t)CWL_STATUS_CAPACITY);
+    }
+    if (b == n_seqs - 1) {
+        // the last workgroup knows the total: it writes the status word (no atomics, no pre-clear)
+        int32_t bits = 0;
+        for (int32_t bb = tid; bb < n_seqs; bb += kThreads) bits |= ws.seq_status[bb];
+        // __syncthreads_or tells whether any thread's value is non-zero: combine bit by bit
+        const int32_t nan_any = __syncthreads_or(bits & (int32_t)CWL_STATUS_NAN_SCORE);
+        const int32_t bad_any = __syncthreads_or(bits & (int32_t)CWL_STATUS_BAD_OFFSETS);
+        if (tid == 0) {
+            int32_t w = (nan_any ? (int32_t)CWL_STATUS_NAN_SCORE : 0) | (bad_any ? (int32_t)CWL_STATUS_BAD_OFFSETS : 0);
+            if (first + count > cap) w |= (int32_t)CWL_STATUS_CAPACITY;
+            *status_word = w;
+        }
     }
     for (int32_t i = tid; i < count; i += kThreads) {
         const int64_t dst = first + i;
@@ -308,17 +351,24 @@ extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t theta_q = cwl::quantise_threshold(p->theta_hard);
     const int64_t delta_q = cwl::quantise_threshold(p->delta_dev);
-    cwl::prof_begin(CWL_PROF_PARTITION, s);
-    partition_init_kernel<<<1, 1, 0, s>>>(status_word);
-    CWL_RETURN_IF_LAUNCH_FAILED();
     if (n_seqs == 0) {
-        // chunk_offsets[0] = 0 is written by the compact kernel only when sequences exist
-        hipLaunchKernelGGL(partition_init_kernel, dim3(1), dim3(1), 0, s, chunk_offsets);
+        // no sequences: status 0, chunk_offsets[0] = 0
+        partition_init_kernel<<<1, 1, 0, s>>>(status_word);
+        CWL_RETURN_IF_LAUNCH_FAILED();
+        partition_init_kernel<<<1, 1, 0, s>>>(chunk_offsets);
         CWL_RETURN_IF_LAUNCH_FAILED();
         return CWL_OK;
     }
-    partition_seq_kernel<<<dim3((unsigned)n_seqs), dim3(kThreads), 0, s>>>(
-        entropy, n_rows, seq_offsets, n_seqs, p->l_min, p->l_max, theta_q, delta_q, ws, status_word);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(partition_seq_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
+            return CWL_ERR_DEVICE;
+        attr_set = true;
+    }
+    cwl::prof_begin(CWL_PROF_PARTITION, s);
+    partition_seq_kernel<<<dim3((unsigned)n_seqs), dim3(kThreads), kLdsBytes, s>>>(
+        entropy, n_rows, seq_offsets, n_seqs, p->l_min, p->l_max, theta_q, delta_q, ws);
     CWL_RETURN_IF_LAUNCH_FAILED();
     partition_compact_kernel<<<dim3((unsigned)n_seqs), dim3(kThreads), 0, s>>>(
         n_seqs, ws, chunk_offsets, chunk_start, chunk_len, chunk_sum, cap, status_word);

@@ -15,6 +15,9 @@ namespace {
 constexpr float kLog2e = 1.44269504088896340736f;
 constexpr float kLn2 = 0.69314718055994530942f;
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
 struct EntState {
     float c, S, W;
 };
@@ -56,8 +59,9 @@ template <>
 struct Vec<float> {
     static constexpr int N = 4;
     __device__ static __forceinline__ void load(const float* p, float (&z)[4]) {
-        const float4 v = *reinterpret_cast<const float4*>(p);
-        z[0] = v.x; z[1] = v.y; z[2] = v.z; z[3] = v.w;
+        // streamed once: non-temporal, so the logits do not displace reusable lines from the caches
+        const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+        z[0] = v[0]; z[1] = v[1]; z[2] = v[2]; z[3] = v[3];
     }
     __device__ static __forceinline__ float one(const float* p) { return *p; }
 };
@@ -65,8 +69,8 @@ template <>
 struct Vec<uint16_t> {   // bf16 bit patterns
     static constexpr int N = 8;
     __device__ static __forceinline__ void load(const uint16_t* p, float (&z)[8]) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        const uint32_t w[4] = {v[0], v[1], v[2], v[3]};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             z[2 * i] = __uint_as_float(w[i] << 16);
@@ -80,9 +84,10 @@ struct Vec<uint16_t> {   // bf16 bit patterns
 
 template <int N>
 __device__ __forceinline__ void ent_add_vec(EntState& s, float& m, const float (&z)[N]) {
-    float vm = z[0];
+    float vm = z[0];   // nested in threes so that the compiler forms v_max3_f32
 #pragma unroll
-    for (int i = 1; i < N; ++i) vm = fmaxf(vm, z[i]);
+    for (int i = 1; i + 1 < N; i += 2) vm = fmaxf(fmaxf(vm, z[i]), z[i + 1]);
+    if (N % 2 == 0) vm = fmaxf(vm, z[N - 1]);
     if (vm > m) {
         m = vm;
         ent_raise_offset(s, vm * kLog2e);
@@ -92,23 +97,24 @@ __device__ __forceinline__ void ent_add_vec(EntState& s, float& m, const float (
     for (int i = 0; i < N; ++i) ent_add(s, off, z[i]);
 }
 
-// WAVES wavefronts cooperate on one row; a block of 256 threads holds 4 / WAVES rows
-// (WAVES = 16: 1024 threads, one row).
+// WAVES wavefronts cooperate on one row.  WAVES = 1: a block of 256 threads holds 4 rows;
+// otherwise one row per block of WAVES * 64 threads.
 template <typename T, int WAVES>
-__global__ void __launch_bounds__(WAVES >= 4 ? WAVES * 64 : 256)
+__global__ void __launch_bounds__(WAVES >= 2 ? WAVES * 64 : 256)
 score_tokens_kernel(const T* __restrict__ logits, int64_t n_rows, int64_t vocab,
                     int64_t row_stride, float* __restrict__ entropy) {
     constexpr int VEC = Vec<T>::N;
     constexpr int UNROLL = 4;
     constexpr int GROUP = WAVES * 64;                     // threads per row
-    constexpr int ROWS_PER_BLOCK = (WAVES >= 4) ? 1 : 4 / WAVES;
+    constexpr int ROWS_PER_BLOCK = (WAVES >= 2) ? 1 : 4;
     const int tid = threadIdx.x;
     const int g_tid = tid % GROUP;
     const int64_t row = (int64_t)blockIdx.x * ROWS_PER_BLOCK + tid / GROUP;
     const bool row_ok = row < n_rows;
 
-    EntState s = {-INFINITY, 0.0f, 0.0f};
-    float m = -INFINITY;
+    // two independent online states per thread: shorter dependency chains through S and W
+    EntState s = {-INFINITY, 0.0f, 0.0f}, s2 = {-INFINITY, 0.0f, 0.0f};
+    float m = -INFINITY, m2 = -INFINITY;
     if (row_ok) {
         const T* rp = logits + row * row_stride;
         // split the row into unaligned head, 16-byte vectors, tail
@@ -125,7 +131,10 @@ score_tokens_kernel(const T* __restrict__ logits, int64_t n_rows, int64_t vocab,
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) Vec<T>::load(vp + (i + (int64_t)u * GROUP) * VEC, z[u]);
 #pragma unroll
-            for (int u = 0; u < UNROLL; ++u) ent_add_vec<VEC>(s, m, z[u]);
+            for (int u = 0; u < UNROLL; ++u) {
+                if (u & 1) ent_add_vec<VEC>(s2, m2, z[u]);
+                else ent_add_vec<VEC>(s, m, z[u]);
+            }
         }
         for (; i < nvec; i += GROUP) {
             float z[VEC];
@@ -141,6 +150,7 @@ score_tokens_kernel(const T* __restrict__ logits, int64_t n_rows, int64_t vocab,
         }
     }
 
+    ent_merge(s, s2);
     // merge across the 64 lanes
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
@@ -171,10 +181,14 @@ cwl_status launch(const void* logits, int64_t n_rows, int64_t vocab, int64_t row
     const int64_t row_bytes = vocab * (int64_t)sizeof(T);
     const T* lp = static_cast<const T*>(logits);
     cwl::prof_begin(CWL_PROF_SCORE, st);
+    // threads per row: enough 16-byte loads per thread to amortise the state merge, enough
+    // blocks per CU to keep HBM busy (measured best on 64 KB rows: 2 wavefronts per row)
     if (row_bytes <= 16 * 1024) {
         const int64_t blocks = (n_rows + 3) / 4;
         score_tokens_kernel<T, 1><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
-    } else if (row_bytes <= 160 * 1024) {
+    } else if (row_bytes <= 128 * 1024) {
+        score_tokens_kernel<T, 2><<<dim3((unsigned)n_rows), dim3(128), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
+    } else if (row_bytes <= 512 * 1024) {
         score_tokens_kernel<T, 4><<<dim3((unsigned)n_rows), dim3(256), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
     } else {
         score_tokens_kernel<T, 16><<<dim3((unsigned)n_rows), dim3(1024), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
