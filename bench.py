@@ -32,7 +32,23 @@ def parse():
     ap.add_argument("--group-rows", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings against)")
     return ap.parse_args()
+
+
+def read_traffic(tag):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a
+    plain copy of known size), from the committed summary profiles/pmc_traffic_<tag>.txt."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", f"pmc_traffic_{tag}.txt")
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch."):
+                key, val = line.split(":", 1)
+                out[key.split(".", 1)[1].strip()] = float(val.split()[0])
+    return out
 
 
 def main():
@@ -86,6 +102,13 @@ def main():
         wall = (time.perf_counter() - t0) * 1e3
         return max(e0.elapsed_time(e1), 0.0) / steps, wall / steps
 
+    if args.calibrate_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)              # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- the timed region: K whole-path steps, per-kernel events on -----------------------------
     for _ in range(args.warmup):
         step()
@@ -138,19 +161,20 @@ def main():
                    "tokens_by_rank": {str(r): int(cl[rk == r].sum()) for r in wl.ladder},
                    "mean_r_eff": float(r_eff.mean())},
     }
+    traffic = read_traffic(f"{wl.name}_{pname}")
     if kern_ms["main"]:
         ach = flops_main / (kern_ms["main"] * 1e-3) / 1e12
         out["roofline"] = {"kernel": "gemm_bf16_tn_kernel<256,256> (x W + uhat B)" if bf16 else "gemm_f32_tn_kernel",
                            "bound": "mfma" if bf16 else "alu", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
-                           "frac": ach / (PEAK_BF16_TFLOPS if bf16 else 157.3), "traffic": None,
+                           "frac": ach / (PEAK_BF16_TFLOPS if bf16 else 157.3), "traffic": traffic.get("main"),
                            "avg_launch_ms": kern_ms["main"], "flops_per_launch": flops_main}
     if kern_ms["score"]:
         bytes_score = N * (wl.vocab * esz + 4.0)
         gbs = bytes_score / (kern_ms["score"] * 1e-3) / 1e9
         out["roofline_score_tokens"] = {"kernel": "score_tokens_kernel", "bound": "hbm", "achieved": gbs,
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                                        "traffic": None, "avg_launch_ms": kern_ms["score"],
+                                        "traffic": traffic.get("score"), "avg_launch_ms": kern_ms["score"],
                                         "bytes_per_launch": bytes_score}
     lin_ms = sum(kern_ms[k] or 0.0 for k in ("meta", "shrink", "main"))
     out["linear"] = {"ms": lin_ms, "tokens_per_s": N / (lin_ms * 1e-3) if lin_ms else None,
