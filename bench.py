@@ -207,8 +207,10 @@ def main():
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------------
     if not args.no_cpu_baseline:
         import oracle as O
-        n_ent = min(N, 2048)
-        n_lin = min(N, 256 if d_in * d_out > 1 << 22 else 2048)
+        # bounded sample, sized for roughly 10-20 s of host work: entropy on every row when the logits
+        # are at most ~1 GB (else 4096 rows), the linear on about 2.7e11 multiply-adds worth of rows
+        n_ent = N if N * wl.vocab * esz <= 1.1e9 else min(N, 4096)
+        n_lin = int(max(64, min(N, 2.7e11 // (d_in * d_out))))
         rows_e = np.linspace(0, N - 1, n_ent).astype(np.int64)
         rows_l = np.unique(np.linspace(0, N - 1, n_lin).astype(np.int64))
         lg = logits[torch.from_numpy(rows_e).to(dev)].float().cpu().numpy()

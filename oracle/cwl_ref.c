@@ -217,7 +217,9 @@ void cwl_ref_select(const int64_t* chunk_sum, const int32_t* chunk_len, int64_t 
  *              y_t = x_t W + (1 - lambda) * D_{k_{c-1}}(t) + lambda * D_{k_c}(t)
  * A rung of rank 0 contributes nothing whatever its scale.  A token that no chunk covers gets
  * the base product only.  Only the rows listed in `rows` are evaluated (all of them when rows
- * is NULL); y is [n_sel, d_out] in double, not rounded.
+ * is NULL); y is [n_sel, d_out] in double, not rounded.  With x_compact != 0 the array x holds
+ * just the listed rows, in the order of `rows` (x[i] is token rows[i]); the chunk table still
+ * refers to the original token numbering.
  * ------------------------------------------------------------------------------------------ */
 static void adapter_term(const double* u, const float* B, int64_t ldb, int64_t d_out,
                          int32_t r, double s, double weight, double* acc) {
@@ -236,7 +238,7 @@ int cwl_ref_linear(const float* x, int64_t ldx, const float* W, int64_t ldw,
                    const int32_t* seq_offsets, int32_t n_seqs,
                    const int32_t* chunk_offsets, const int32_t* chunk_start,
                    const int32_t* chunk_len, const int32_t* rank_idx,
-                   const int64_t* rows, int64_t n_sel, double* y) {
+                   const int64_t* rows, int64_t n_sel, int32_t x_compact, double* y) {
     if (K < 1 || r_max < 0 || blend_w < 0) return CWL_REF_ERR_INVALID;
     for (int32_t k = 0; k < K; ++k)
         if (ranks[k] < 0 || ranks[k] > r_max) return CWL_REF_ERR_INVALID;
@@ -263,7 +265,7 @@ int cwl_ref_linear(const float* x, int64_t ldx, const float* W, int64_t ldw,
         for (int64_t s_i = 0; s_i < count; ++s_i) {
             const int64_t t = rows ? rows[s_i] : s_i;
             double* yt = y + s_i * d_out;
-            const float* xt = x + t * ldx;
+            const float* xt = x + ((rows && x_compact) ? s_i : t) * ldx;
             for (int64_t j = 0; j < d_out; ++j) yt[j] = 0.0;
             for (int64_t k = 0; k < d_in; ++k) {            /* base product x_t W */
                 const double xv = (double)xt[k];

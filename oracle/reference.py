@@ -48,7 +48,7 @@ def _load():
     lib.cwl_ref_select.argtypes = [P, P, i64, P, i32, P]
     lib.cwl_ref_select.restype = None
     lib.cwl_ref_linear.argtypes = [P, i64, P, i64, P, i64, P, i64, i64, i64, i64, i32,
-                                   i32, P, P, i32, P, i32, P, P, P, P, P, i64, P]
+                                   i32, P, P, i32, P, i32, P, P, P, P, P, i64, i32, P]
     lib.cwl_ref_linear.restype = ctypes.c_int
     _lib = lib
     return lib
@@ -121,14 +121,18 @@ def select(chunk_sum, chunk_len, tau_q):
 
 
 def linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, chunk_offsets, chunk_start,
-           chunk_len, rank_idx, rows=None):
+           chunk_len, rank_idx, rows=None, x_compact=False):
     """y[rows] of the chunk-segmented LoRA linear, float64, unrounded.
 
     x [N, d_in], W [d_in, d_out], A [d_in, r_max], B [r_max, d_out]: float32 arrays holding the
-    exact values the device sees.
+    exact values the device sees.  With ``x_compact`` x holds only the listed rows (x[i] is token
+    rows[i]) -- for large inputs of which only a row sample is brought to the host.
     """
     x, W, A, B = (_arr(a, np.float32) for a in (x, W, A, B))
     n_rows, d_in = x.shape
+    if x_compact:
+        assert rows is not None and len(rows) == n_rows
+        n_rows = int(np.asarray(seq_offsets).ravel()[-1])
     d_out = W.shape[1]
     r_max = A.shape[1]
     assert W.shape[0] == d_in and A.shape[0] == d_in and B.shape == (r_max, d_out)
@@ -155,7 +159,7 @@ def linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, chunk_offsets, chunk
     st = _load().cwl_ref_linear(_ptr(x), x.shape[1], _ptr(W), W.shape[1], _ptr(A), A.shape[1],
                                 _ptr(B), B.shape[1], n_rows, d_in, d_out, r_max, K, _ptr(ranks),
                                 _ptr(scales), int(blend_w), _ptr(so), n_seqs, _ptr(co), _ptr(cs),
-                                _ptr(cl), _ptr(ri), rows_ptr, n_sel, _ptr(y))
+                                _ptr(cl), _ptr(ri), rows_ptr, n_sel, 1 if x_compact else 0, _ptr(y))
     if st != OK:
         raise ValueError(f"cwl_ref_linear: status {st}")
     return y

@@ -1,0 +1,82 @@
+"""GPU parity at the full sizes of the larger workloads (7B MLP projections, the six-rung ladder
+with r_max = 128, the 70B-shaped 8192 x 8192 projection, the 128000-entry vocabulary), in the
+launch configuration the benchmark uses (packed weights).  The oracle evaluates a row sample:
+every cross-fade row and chunk edge of the first chunks plus uniformly drawn rows."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import TOL_BF16, TOL_F32, entropy_err, host, rel_err, sample_rows
+from paper_2601_21109_amd import binding as B
+from paper_2601_21109_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.mark.parametrize("name,proj,n_uniform", [
+    ("cfg2", 0, 48),     # up_proj   4096 -> 11008, 65536 rows
+    ("cfg2", 2, 32),     # down_proj 11008 -> 4096
+    ("cfg3", 0, 64),     # q_proj with the ladder {4, .., 128}
+    ("cfg4", 0, 40),     # 8192 -> 8192, one sequence of 32768 tokens, 8-token cross-fade
+])
+@pytest.mark.parametrize("group_rows", [0, 1])
+def test_linear_full_size_sampled(name, proj, n_uniform, group_rows):
+    wl = W.WORKLOADS[name]
+    x, Wm, A, Bm = W.linear_operands(wl, proj, DEV)
+    so, co, cs, cl, ri = W.random_chunk_table(wl.n_seqs, [wl.seq_len] * wl.n_seqs, wl.l_min, wl.l_max,
+                                              len(wl.ladder), 1000 + wl.index)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    pw = B.prepack_weights(Wm, A, Bm)
+    y = B.chunkwise_lora_linear(x, pw, None, None, wl.ladder, wl.scales, wl.blend_w, sod, tab, rid,
+                                group_rows=group_rows)
+    torch.cuda.synchronize()
+    rows = sample_rows(wl.n_rows, cs, cl, wl.blend_w, n_uniform, seed=wl.index, first_chunks=10)
+    idx = torch.from_numpy(rows).to(DEV)
+    ref = O.linear(host(x[idx]), host(Wm), host(A), host(Bm), wl.ladder, wl.scales, wl.blend_w, so, co,
+                   cs, cl, ri, rows=rows, x_compact=True)
+    assert rel_err(host(y[idx]), ref) <= TOL_BF16
+    # every rung of the ladder occurs among the sampled rows' chunks
+    assert len(set(ri.tolist())) == len(wl.ladder)
+
+
+def test_scoring_128k_vocab_tile():
+    """One 4096-row tile of the 128000-entry-vocabulary workload (the long-context workload streams
+    its logits in such tiles through one reused buffer)."""
+    wl = W.WORKLOADS["cfg4"]
+    sig = W.token_sigmas(wl)
+    h = torch.empty(2 * wl.logit_tile_rows, dtype=torch.float32, device=DEV)
+    rows = np.arange(0, wl.logit_tile_rows, 97)
+    for tile in range(2):
+        r0 = tile * wl.logit_tile_rows
+        z = W.logits_rows(wl, r0, r0 + wl.logit_tile_rows, DEV, sigmas=sig)
+        B.score_tokens(z, out=h[r0:r0 + wl.logit_tile_rows])
+        torch.cuda.synchronize()
+        ref = O.entropy(host(z[torch.from_numpy(rows).to(DEV)]))
+        assert entropy_err(host(h)[r0 + rows], ref, wl.vocab) <= TOL_F32
+    # the three difficulty levels of the generator are all present and well separated
+    lv = host(h) / np.log(wl.vocab)
+    assert lv.min() < 0.3 and lv.max() > 0.95
+
+
+def test_cfg3_skewed_mix_table_bit_exact():
+    """Chunk table of the 32 x 2048 workload with the 70 % / 30 % sigma mix, from scores with the
+    level structure of its logits (full-size logits are 4.2 GB; the table only needs the scores)."""
+    from helpers import assert_tables_equal, gpu_table_to_host, oracle_table
+    wl = W.WORKLOADS["cfg3"]
+    sig = W.token_sigmas(wl)
+    rng = np.random.RandomState(3)
+    level = np.where(sig < 1.0, 0.988, 0.19) * np.log(wl.vocab)
+    h = (level + rng.randn(wl.n_rows) * 0.02 * np.log(wl.vocab)).astype(np.float32)
+    so = W.seq_offsets(wl)
+    hd, sod = torch.from_numpy(h).to(DEV), torch.from_numpy(so).to(DEV)
+    table = B.partition_chunks(hd, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+    ri = B.select_ranks(table, wl.taus(), len(wl.ladder))
+    torch.cuda.synchronize()
+    gpu = gpu_table_to_host(table, ri)
+    ref = oracle_table(h, so, wl)
+    assert gpu["status"] == 0
+    assert_tables_equal(gpu, ref)
+    frac_top = gpu["chunk_len"][gpu["rank_idx"] == len(wl.ladder) - 1].sum() / wl.n_rows
+    assert 0.55 < frac_top < 0.85       # low sigma = near-uniform = hard: about 70 % of tokens on the top rung

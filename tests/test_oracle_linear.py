@@ -184,3 +184,14 @@ def test_bf16_round_helper(oracle):
     v = np.array([1.0, 1.00390625, 1.001953125, 3.14159, -2.71828, 1e-3, 65504.0, 0.0])
     want = torch.tensor(v, dtype=torch.float64).to(torch.float32).to(torch.bfloat16).double().numpy()
     assert np.array_equal(oracle.bf16_round(v), want)
+
+
+def test_compact_x_equals_full_x(oracle):
+    rng = np.random.RandomState(12)
+    so, co, cs, cl = table3()
+    x, W, A, B = rand_ops(rng, 31, 8, 9, 4)
+    args = ([1, 4], [2.0, 0.5], 2, so, co, cs, cl, [0, 1, 1, 0, 1])
+    rows = [30, 7, 8, 20, 0]
+    full = oracle.linear(x, W, A, B, *args, rows=rows)
+    compact = oracle.linear(x[rows], W, A, B, *args, rows=rows, x_compact=True)
+    assert np.array_equal(full, compact)
