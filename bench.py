@@ -181,26 +181,40 @@ def main():
                      "effective_tflops": flops_alg / (lin_ms * 1e-3) / 1e12 if lin_ms else None,
                      "frac_of_bf16_peak": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if lin_ms else None}
 
-    # ---- same kernels at fixed r_max and at rank 0 ------------------------------------------------
+    # ---- same kernels at fixed r_max and at rank 0 (launches interleaved so that clock and
+    #      temperature drift hit the three variants alike) ----------------------------------------
     if not args.no_variants:
-        def variant(ranks, scales):
-            one = np.zeros(n_chunks, dtype=np.int32)
-            rid = torch.from_numpy(one).to(dev)
-            fn = lambda: B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, wl.blend_w, sod,
-                                                 table, rid, out=y, group_rows=args.group_rows, workspace=ws)
-            ms, _ = timed(fn, args.steps, args.warmup)
-            return ms
-        ms_chunk, _ = timed(lambda: B.chunkwise_lora_linear(x, packed, None, None, wl.ladder, wl.scales,
-                                                            wl.blend_w, sod, table, ri, out=y,
-                                                            group_rows=args.group_rows, workspace=ws),
-                            args.steps, args.warmup)
-        ms_fixed = variant([wl.r_max], [wl.alpha / wl.r_max])
-        ms_zero = variant([0], [0.0])
+        zero_idx = torch.zeros(max(n_chunks, 1), dtype=torch.int32, device=dev)
+
+        def make(ranks, scales, rid):
+            return lambda: B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, wl.blend_w, sod,
+                                                   table, rid, out=y, group_rows=args.group_rows,
+                                                   workspace=ws)
+        fns = {"chunkwise": make(wl.ladder, wl.scales, ri),
+               "fixed_r_max": make([wl.r_max], [wl.alpha / wl.r_max], zero_idx),
+               "rank_0": make([0], [0.0], zero_idx)}
+        for fn in fns.values():
+            for _ in range(args.warmup):
+                fn()
+        torch.cuda.synchronize()
+        tot = {k: 0.0 for k in fns}
+        block = 5
+        rounds = max(1, args.steps // block)
+        for _ in range(rounds):
+            for k, fn in fns.items():
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(block):
+                    fn()
+                e1.record()
+                e1.synchronize()
+                tot[k] += e0.elapsed_time(e1)
+        ms_v = {k: v / (rounds * block) for k, v in tot.items()}
         out["linear_variants"] = {
-            "chunkwise": {"ms": ms_chunk, "effective_tflops": flops_alg / ms_chunk / 1e9},
-            "fixed_r_max": {"ms": ms_fixed, "effective_tflops": flops_fixed / ms_fixed / 1e9},
-            "rank_0": {"ms": ms_zero, "effective_tflops": flops_base / ms_zero / 1e9},
-            "speedup_vs_fixed_r_max": ms_fixed / ms_chunk,
+            "chunkwise": {"ms": ms_v["chunkwise"], "effective_tflops": flops_alg / ms_v["chunkwise"] / 1e9},
+            "fixed_r_max": {"ms": ms_v["fixed_r_max"], "effective_tflops": flops_fixed / ms_v["fixed_r_max"] / 1e9},
+            "rank_0": {"ms": ms_v["rank_0"], "effective_tflops": flops_base / ms_v["rank_0"] / 1e9},
+            "speedup_vs_fixed_r_max": ms_v["fixed_r_max"] / ms_v["chunkwise"],
             "lora_flop_share_at_r_max": wl.r_max * (d_in + d_out) / (d_in * d_out),
         }
 

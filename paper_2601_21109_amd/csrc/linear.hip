@@ -6,6 +6,20 @@
 namespace cwl {
 namespace {
 
+constexpr int kSortThreads = 512;
+constexpr int kBuckets = CWL_MAX_LADDER + 1;
+
+__device__ __forceinline__ int bucket_of(int32_t r_eff, const Ladder& lad) {
+    // larger rank -> smaller bucket id; rank 0 -> last bucket.  The loop runs over the fixed
+    // capacity with constant indices so that the ladder stays in scalar registers.
+    int n_ge = 0;
+#pragma unroll
+    for (int k = 0; k < CWL_MAX_LADDER; ++k)
+        n_ge += (k < lad.K && lad.ranks[k] > 0 && lad.ranks[k] >= r_eff) ? 1 : 0;
+    return r_eff > 0 ? (n_ge > 0 ? n_ge - 1 : 0) : kBuckets - 1;
+}
+
+
 // ------------------------------------------------------------------------------------------
 // Per-token gate table.  Token t -> its sequence (binary search in seq_offsets) -> its chunk
 // (binary search in that sequence's chunk_start range) -> (r_cur, g_cur, r_prev, g_prev).
@@ -18,6 +32,19 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
                   const int32_t* __restrict__ chunk_len, const int32_t* __restrict__ rank_idx,
                   int32_t chunk_cap, Ladder lad, int32_t blend_w, TokMeta* __restrict__ meta,
                   int32_t* __restrict__ blk_r /* may be NULL */, int32_t* __restrict__ r_eff_out /* may be NULL */) {
+    // the ladder is indexed by a per-thread rung: keep a copy in LDS
+    __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
+    __shared__ float lad_scales[CWL_MAX_LADDER];
+    if (threadIdx.x < CWL_MAX_LADDER) {
+        int32_t r = 0;
+        float sc = 0.0f;
+#pragma unroll
+        for (int k = 0; k < CWL_MAX_LADDER; ++k)
+            if (k == (int)threadIdx.x) { r = lad.ranks[k]; sc = lad.scales[k]; }
+        lad_ranks[threadIdx.x] = r;
+        lad_scales[threadIdx.x] = sc;
+    }
+    __syncthreads();
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     TokMeta m = {0, 0, 0.0f, 0.0f};
     if (t < n_rows && n_seqs > 0) {
@@ -42,16 +69,16 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
                 if (j < chunk_len[c]) {
                     const int32_t k = rank_idx[c];
                     const bool k_ok = k >= 0 && k < lad.K;
-                    const int32_t r_cur = k_ok ? lad.ranks[k] : 0;
-                    const float s_cur = (k_ok && r_cur > 0) ? lad.scales[k] : 0.0f;
+                    const int32_t r_cur = k_ok ? lad_ranks[k] : 0;
+                    const float s_cur = (k_ok && r_cur > 0) ? lad_scales[k] : 0.0f;
                     if (c == c0 || blend_w == 0 || j >= blend_w) {
                         m.r_cur = r_cur;
                         m.g_cur = s_cur;
                     } else {
                         const int32_t kp = rank_idx[c - 1];
                         const bool kp_ok = kp >= 0 && kp < lad.K;
-                        const int32_t r_prev = kp_ok ? lad.ranks[kp] : 0;
-                        const float s_prev = (kp_ok && r_prev > 0) ? lad.scales[kp] : 0.0f;
+                        const int32_t r_prev = kp_ok ? lad_ranks[kp] : 0;
+                        const float s_prev = (kp_ok && r_prev > 0) ? lad_scales[kp] : 0.0f;
                         const float lambda = (float)(j + 1) / (float)(blend_w + 1);
                         m.r_cur = r_cur;
                         m.g_cur = lambda * s_cur;
@@ -65,7 +92,7 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
     int32_t r_eff = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
     if (t < n_rows) {
         meta[t] = m;
-        if (r_eff_out) r_eff_out[t] = r_eff;
+        if (r_eff_out) r_eff_out[t] = r_eff | (bucket_of(r_eff, lad) << 16);   // rank and its sort bucket
     }
     if (blk_r) {
 #pragma unroll
@@ -82,54 +109,151 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
 // Rank grouping: a stable counting sort of the token rows by effective rank, largest first, so
 // that row tiles are rank-homogeneous (only the few tiles that straddle two buckets mix ranks)
 // and the tiles with the longest reduction are scheduled first.  One workgroup of 512 threads;
-// each thread owns a contiguous slice of tokens.
+// bucket ids are staged in LDS a segment at a time, each thread owns a contiguous slice of it.
 // ------------------------------------------------------------------------------------------
-constexpr int kSortThreads = 512;
-constexpr int kBuckets = CWL_MAX_LADDER + 1;
+constexpr int kSortSeg = 32768;     // tokens staged in LDS at a time (one byte each)
 
-__device__ __forceinline__ int bucket_of(int32_t r_eff, const Ladder& lad) {
-    // larger rank -> smaller bucket id; rank 0 -> last bucket
-    int n_ge = 0;
-    for (int k = 0; k < lad.K; ++k) n_ge += (lad.ranks[k] > 0 && lad.ranks[k] >= r_eff) ? 1 : 0;
-    return r_eff > 0 ? (n_ge > 0 ? n_ge - 1 : 0) : kBuckets - 1;
+// sum over the block of kBuckets counters per thread; result in tot[] (LDS), valid after the call
+__device__ void block_bucket_sums(const int32_t (&cnt)[kBuckets], int32_t (*wave_tot)[kSortThreads / 64],
+                                  int32_t* tot) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) {
+        int32_t v = cnt[b];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+        if (lane == 0) wave_tot[b][wave] = v;
+    }
+    __syncthreads();
+    if (tid < kBuckets) {
+        int32_t run = 0;
+        for (int w = 0; w < kSortThreads / 64; ++w) run += wave_tot[tid][w];
+        tot[tid] = run;
+    }
+    __syncthreads();
+}
+
+// stage the bucket ids of one segment in LDS: 8 independent loads in flight per thread
+__device__ __forceinline__ void stage_buckets(const int32_t* __restrict__ packed, int seg_len, uint8_t* bk) {
+    for (int base = threadIdx.x; base < seg_len; base += 8 * kSortThreads) {
+        int32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * kSortThreads;
+            v[u] = i < seg_len ? packed[i] : 0;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + u * kSortThreads;
+            if (i < seg_len) bk[i] = (uint8_t)(v[u] >> 16);
+        }
+    }
+}
+
+// counts of one thread's contiguous slice [i0, i1) of the staged segment, run by run (tokens of one
+// chunk share a bucket); the bucket index is only known at run time, so every update is a compare
+// against all bucket ids and the counters stay in registers
+__device__ __forceinline__ void count_slice(const uint8_t* bk, int i0, int i1, int32_t (&cnt)[kBuckets]) {
+    for (int i = i0; i < i1;) {
+        const int bkt = bk[i];
+        int j = i + 1;
+        while (j < i1 && bk[j] == bkt) ++j;
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) cnt[b] += (b == bkt) ? (j - i) : 0;
+        i = j;
+    }
 }
 
 __global__ void __launch_bounds__(kSortThreads)
-group_rows_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, Ladder lad,
+group_rows_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff /* rank | bucket << 16 */,
                   int32_t* __restrict__ perm) {
-    __shared__ int32_t cnt[kBuckets][kSortThreads];   // 34 KiB
-    __shared__ int32_t bucket_base[kBuckets + 1];
-    const int tid = threadIdx.x;
-    const int64_t per = (n_rows + kSortThreads - 1) / kSortThreads;
-    const int64_t t0 = tid * per, t1 = (t0 + per < n_rows) ? t0 + per : n_rows;
-    for (int b = 0; b < kBuckets; ++b) cnt[b][tid] = 0;
-    for (int64_t t = t0; t < t1; ++t) cnt[bucket_of(r_eff[t], lad)][tid] += 1;
-    __syncthreads();
-    if (tid < kBuckets) {                       // exclusive scan over threads, one bucket each
-        int32_t run = 0;
-        for (int i = 0; i < kSortThreads; ++i) {
-            const int32_t c = cnt[tid][i];
-            cnt[tid][i] = run;
-            run += c;
-        }
-        bucket_base[tid + 1] = run;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        bucket_base[0] = 0;
-        for (int b = 1; b <= kBuckets; ++b) bucket_base[b] += bucket_base[b - 1];
-    }
-    __syncthreads();
-    int32_t pos[kBuckets];
-    for (int b = 0; b < kBuckets; ++b) pos[b] = bucket_base[b] + cnt[b][tid];
-    for (int64_t t = t0; t < t1; ++t) {
-        const int b = bucket_of(r_eff[t], lad);
-        // pos is indexed dynamically: keep it in LDS-free registers via a small switch-less loop
-        int32_t p = 0;
+    constexpr int kWaves = kSortThreads / 64;
+    __shared__ uint8_t bk[kSortSeg];                 // bucket id of every token of the segment
+    __shared__ int32_t wave_tot[kBuckets][kWaves];
+    __shared__ int32_t tot[kBuckets];
+    __shared__ int32_t run_base[kBuckets];           // next free slot of every bucket
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const bool one_segment = n_rows <= kSortSeg;
+
+    // pass 1: bucket totals -> first slot of every bucket
+    int32_t cnt[kBuckets];
 #pragma unroll
-        for (int bb = 0; bb < kBuckets; ++bb)
-            if (bb == b) { p = pos[bb]; pos[bb] = p + 1; }
-        perm[p] = (int32_t)t;
+    for (int b = 0; b < kBuckets; ++b) cnt[b] = 0;
+    for (int64_t seg0 = 0; seg0 < n_rows; seg0 += kSortSeg) {
+        const int seg_len = (int)((n_rows - seg0 < kSortSeg) ? n_rows - seg0 : kSortSeg);
+        stage_buckets(r_eff + seg0, seg_len, bk);
+        __syncthreads();
+        const int per = (seg_len + kSortThreads - 1) / kSortThreads;
+        const int i0 = tid * per < seg_len ? tid * per : seg_len;
+        const int i1 = i0 + per < seg_len ? i0 + per : seg_len;
+        count_slice(bk, i0, i1, cnt);
+        if (!one_segment) __syncthreads();
+    }
+    block_bucket_sums(cnt, wave_tot, tot);
+    if (tid == 0) {
+        int32_t run = 0;
+        for (int b = 0; b < kBuckets; ++b) {
+            run_base[b] = run;
+            run += tot[b];
+        }
+    }
+    __syncthreads();
+
+    // pass 2: segment by segment; inside a segment every thread owns a contiguous slice, so the
+    // order (segment, thread, position in slice) is token order and the sort is stable
+    for (int64_t seg0 = 0; seg0 < n_rows; seg0 += kSortSeg) {
+        const int seg_len = (int)((n_rows - seg0 < kSortSeg) ? n_rows - seg0 : kSortSeg);
+        if (!one_segment) {
+            stage_buckets(r_eff + seg0, seg_len, bk);
+            __syncthreads();
+        }
+        const int per = (seg_len + kSortThreads - 1) / kSortThreads;
+        const int i0 = tid * per < seg_len ? tid * per : seg_len;
+        const int i1 = i0 + per < seg_len ? i0 + per : seg_len;
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) cnt[b] = 0;
+        count_slice(bk, i0, i1, cnt);
+        // exclusive scan over threads, bucket by bucket: shuffles inside a wave, LDS across waves
+        int32_t excl[kBuckets];
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) {
+            int32_t v = cnt[b];
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int32_t o = __shfl_up(v, off);
+                if (lane >= off) v += o;
+            }
+            excl[b] = v - cnt[b];
+            if (lane == 63) wave_tot[b][wave] = v;
+        }
+        __syncthreads();
+        if (tid < kBuckets) {
+            int32_t run = 0;
+            for (int w = 0; w < kWaves; ++w) {
+                const int32_t c = wave_tot[tid][w];
+                wave_tot[tid][w] = run;
+                run += c;
+            }
+            tot[tid] = run;
+        }
+        __syncthreads();
+        int32_t pos[kBuckets];
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) pos[b] = run_base[b] + wave_tot[b][wave] + excl[b];
+        for (int i = i0; i < i1;) {
+            const int bkt = bk[i];
+            int j = i + 1;
+            while (j < i1 && bk[j] == bkt) ++j;
+            int32_t p = 0;
+#pragma unroll
+            for (int b = 0; b < kBuckets; ++b)
+                if (b == bkt) { p = pos[b]; pos[b] = p + (j - i); }
+            for (int k = i; k < j; ++k) perm[p + (k - i)] = (int32_t)(seg0 + k);
+            i = j;
+        }
+        __syncthreads();
+        if (tid < kBuckets) run_base[tid] += tot[tid];
+        __syncthreads();
     }
 }
 
@@ -138,7 +262,7 @@ block_rank_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32
                   int32_t* __restrict__ blk_r) {
     const int64_t g = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int32_t r = 0;
-    if (g < n_rows) r = r_eff[perm[g]];
+    if (g < n_rows) r = r_eff[perm[g]] & 0xffff;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         const int32_t o = __shfl_xor(r, off);
@@ -289,7 +413,7 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
         lad, d->blend_w, meta, grouped ? nullptr : blk_r, grouped ? r_eff : nullptr);
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (grouped) {
-        group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, lad, perm);
+        group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, perm);
         CWL_RETURN_IF_LAUNCH_FAILED();
         block_rank_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, perm, blk_r);
         CWL_RETURN_IF_LAUNCH_FAILED();
