@@ -164,7 +164,7 @@ def main():
     traffic = read_traffic(f"{wl.name}_{pname}")
     if kern_ms["main"]:
         ach = flops_main / (kern_ms["main"] * 1e-3) / 1e12
-        out["roofline"] = {"kernel": "gemm_bf16_tn_kernel<256,256> (x W + uhat B)" if bf16 else "gemm_f32_tn_kernel",
+        out["roofline"] = {"kernel": "main_bf16_kernel (x W + uhat B)" if bf16 else "gemm_f32_tn_kernel",
                            "bound": "mfma" if bf16 else "alu", "achieved": ach,
                            "peak": PEAK_BF16_TFLOPS if bf16 else 157.3, "unit": "TFLOP/s",
                            "frac": ach / (PEAK_BF16_TFLOPS if bf16 else 157.3), "traffic": traffic.get("main"),

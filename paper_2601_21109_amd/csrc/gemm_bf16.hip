@@ -1,9 +1,10 @@
-// bf16 matrix-core path of cwl_chunkwise_lora_linear (see linear_common.h for the formulation).
+// bf16 matrix-core shrink of cwl_chunkwise_lora_linear (see linear_common.h for the formulation).
 //
-// One "TN" GEMM kernel, C[m, n] = sum_k A[m, k] B[n, k], both operands K-contiguous, is used
-// twice: as the shrink (A = x, B = A^T, epilogue multiplies by the gate and writes uhat) and as
-// the main product over the concatenated reduction dimension [x | uhat] . [W^T | B^T]^T, where a
-// row tile only walks ceil(r_tile / 32) stages of the second part.
+// A "TN" GEMM kernel, C[m, n] = sum_k A[m, k] B[n, k], both operands K-contiguous, with tile
+// shape, wave grid and ring depth as template parameters.  The library uses it as the shrink
+// (A = x, B = A^T, epilogue multiplies by the gate and writes uhat); with EPI_STORE it also
+// computes the two-part product [x | uhat] . [W^T | B^T]^T, which the 256 x 256 kernel in
+// gemm_bf16_main.hip specialises.
 //
 // Data path (gfx950):
 //   * global -> LDS with global_load_lds_dwordx4 (no staging registers) into a ring of NST
@@ -18,52 +19,15 @@
 //     operand, so each lane ends with 4 consecutive output columns of one row (8-byte stores).
 //   * one workgroup barrier per stage, placed between the two k-steps: by then this wave's
 //     fragment reads of the stage are in registers and its loads of the next stage have landed.
-#include "linear_common.h"
+#include "mfma_util.h"
 
 namespace cwl {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+using namespace mfma;
 
 constexpr int BK = 32;             // elements of K per LDS stage
 constexpr int ROW_BYTES = BK * 2;  // 64
-
-__device__ __forceinline__ void load_lds_16(const void* gptr, char* lds_wave_base) {
-    __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)gptr,
-        (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
-}
-
-// s_waitcnt with explicit counts (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] |
-// vmcnt[5:4] at [15:14]); expcnt is left at its maximum.
-template <int VM, int LGKM>
-__device__ __forceinline__ void wait_cnt() {
-    static_assert(VM >= 0 && VM < 64 && LGKM >= 0 && LGKM < 16, "counter range");
-    __builtin_amdgcn_s_waitcnt((VM & 15) | (7 << 4) | ((LGKM & 15) << 8) | ((VM >> 4) << 14));
-}
-
-// Workgroup id -> (row tile, column tile).  Consecutive workgroup ids go round-robin over the 8
-// XCDs, each with its own L2, so XCD x is given the x-th contiguous eighth of a tile order in
-// which GROUP_M row tiles sweep all column tiles before moving on: the 32 tiles in flight on one
-// XCD form an 8 x 4 patch that shares 8 x panels and 4 weight panels.
-__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* bm, int* bn) {
-    constexpr int kXcd = 8, GROUP_M = 8;
-    const int64_t n_tiles = (int64_t)tiles_m * tiles_n;
-    const int64_t per_xcd = (n_tiles + kXcd - 1) / kXcd;
-    const int64_t wg = blockIdx.x;
-    const int64_t tile = (wg % kXcd) * per_xcd + wg / kXcd;
-    if (tile >= n_tiles) return false;
-    const int64_t band_size = (int64_t)GROUP_M * tiles_n;
-    const int64_t band = tile / band_size;
-    const int64_t in_band = tile % band_size;
-    const int64_t first_m = band * GROUP_M;
-    const int64_t gm = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
-    *bm = (int)(first_m + in_band % gm);
-    *bn = (int)(in_band / gm);
-    return true;
-}
 
 template <int BM, int BN, int WM, int WN, int NST, int EPI>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) {
@@ -331,10 +295,6 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
         case 256: return launch_cfg<64, 256, 2, 2, 4, EPI_GATE>(a, st);
         default: return CWL_ERR_UNSUPPORTED;
     }
-}
-
-cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st) {
-    return launch_cfg<256, 256, 2, 4, 4, EPI_STORE>(a, st);
 }
 
 }  // namespace cwl
