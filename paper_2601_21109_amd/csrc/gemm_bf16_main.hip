@@ -12,12 +12,18 @@
 //     of a fragment (32 rows x 2 chunks) is conflict-free.
 //   * Fragments are double buffered in registers across the four k-steps of a stage; the single
 //     workgroup barrier of a stage sits before the last k-step.
+//   * A stage's eight load instructions per wave are not issued as a burst: the address unit
+//     takes one 64-lane instruction every ~18 cycles, a wave stays in issue until its loads are
+//     taken, and with all eight waves bursting together that held the MFMAs back for more than
+//     a thousand cycles per stage.  Two loads go into every k-step, each between MFMAs.
 //   * v_mfma_f32_32x32x16_bf16, fp32 accumulators, weight fragment as the first operand.
 //   * Epilogue through LDS: the tile is written as bf16 into a 256 x 512 B image and read back
 //     row-wise, so each global store instruction writes two whole 512-byte row segments instead
 //     of 16-byte pieces of 32 different rows.
 //   * The second reduction part (uhat . B^T) walks only ceil(r_tile / 64) stages, r_tile = largest
 //     effective rank among the tile's rows; uhat is zero beyond a row's own rank.
+#include <type_traits>
+
 #include "mfma_util.h"
 
 namespace cwl {
@@ -82,35 +88,44 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
         rowB[i] = (int32_t)n;
         gpB[i] = static_cast<const __bf16*>(a.B1) + n * a.ldb1 + lchunk[i] * 8;
     }
-    int issuedA = 0, issuedB = 0;                    // stages issued per operand (wave-uniform)
-    auto issue_A = [&](int buf) {
-        if (issuedA == KS) {
+    // Loads are requested two instructions ("a pair") at a time so that they can sit between MFMAs:
+    // a wave that issues a burst of loads is held until the address unit has taken them all, and
+    // its MFMAs wait behind them.  cntA / cntB count pairs; pair 2t of an operand starts stage t.
+    int cntA = 0, cntB = 0;
+    auto switch_A = [&]() {           // from x to uhat
 #pragma unroll
-            for (int i = 0; i < LOADS; ++i)
-                gpA[i] = static_cast<const __bf16*>(a.A2) + (int64_t)rowA[i] * a.lda2 + lchunk[i] * 8;
-        }
+        for (int i = 0; i < LOADS; ++i)
+            gpA[i] = static_cast<const __bf16*>(a.A2) + (int64_t)rowA[i] * a.lda2 + lchunk[i] * 8;
+    };
+    auto switch_B = [&]() {           // from W^T to B^T
+#pragma unroll
+        for (int i = 0; i < LOADS; ++i)
+            gpB[i] = static_cast<const __bf16*>(a.B2) + (int64_t)rowB[i] * a.ldb2 + lchunk[i] * 8;
+    };
+    auto pair_A = [&](int buf, int pair, auto checked) {
+        if (checked.value && cntA == 2 * KS) switch_A();
         char* base = smem + buf * SLOT_BYTES + wave * LOADS * 1024;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
+        for (int i = 2 * pair; i < 2 * pair + 2; ++i) {
             load_lds_16(gpA[i], base + i * 1024);
             gpA[i] += BK;
         }
-        ++issuedA;
+        ++cntA;
     };
-    auto issue_B = [&](int buf) {
-        if (issuedB == KS) {
-#pragma unroll
-            for (int i = 0; i < LOADS; ++i)
-                gpB[i] = static_cast<const __bf16*>(a.B2) + (int64_t)rowB[i] * a.ldb2 + lchunk[i] * 8;
-        }
+    auto pair_B = [&](int buf, int pair, auto checked) {
+        if (checked.value && cntB == 2 * KS) switch_B();
         char* base = smem + buf * SLOT_BYTES + wave * LOADS * 1024;
 #pragma unroll
-        for (int i = 0; i < LOADS; ++i) {
+        for (int i = 2 * pair; i < 2 * pair + 2; ++i) {
             load_lds_16(gpB[i], base + i * 1024);
             gpB[i] += BK;
         }
-        ++issuedB;
+        ++cntB;
     };
+    constexpr std::true_type kChecked{};
+    constexpr std::false_type kUnchecked{};
+    auto issue_A = [&](int buf) { pair_A(buf, 0, kChecked); pair_A(buf, 1, kChecked); };
+    auto issue_B = [&](int buf) { pair_B(buf, 0, kChecked); pair_B(buf, 1, kChecked); };
 
     // ---- fragment addressing ----
     const int l32 = lane & 31, h = lane >> 5;
@@ -147,12 +162,20 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
             for (int mi = 0; mi < MI; ++mi)
                 acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[f][ni], af[f][mi], acc[ni][mi], 0, 0, 0);
     };
-    // issue order inside a k-step: one MFMA (its operands are already in registers), then the LDS
-    // reads of the next k-step, then the rest
-    auto order_step = [&]() {
+    // issue order inside a k-step: one MFMA (its operands are already in registers), the LDS reads
+    // of the next k-step, then the remaining MFMAs with the step's two loads spaced out among them
+    auto order_step = [&](bool with_loads) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - 1, 0);
+        if (with_loads) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        } else {
+            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - 1, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
     };
     auto next_buf = [](int v) { return v + 1 == NSLOT ? 0 : v + 1; };
@@ -165,29 +188,49 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
     else wait_cnt<0, 15>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    int bA = 0, bB = 1;                              // buffers of the stage being computed
+    int bA = 0, bB = 1;               // buffers of the stage being computed
+    int pB = 0, pA = 0;               // buffers released at the previous barrier: they take the weight
+                                      // half of stage s+1 (second pair still to request) and the x half of s+2
     read_frags(bA, bB, 0, 0);
-    for (int s = 0; s < S; ++s) {
-        const int nA = next_buf(bB), nB = next_buf(nA);   // buffers of stage s + 1
-        read_frags(bA, bB, 1, 1); mfma_step(0); order_step();
-        read_frags(bA, bB, 2, 0); mfma_step(1); order_step();
-        read_frags(bA, bB, 3, 1); mfma_step(0); order_step();
+
+    // Stage s, k-steps 0..2, barrier, k-step 3.  Requests in program order: weights of stage s+1
+    // (second pair), x of stage s+2 (both pairs), barrier, weights of stage s+2 (first pair).  At
+    // the barrier everything but the x half just requested must have landed.
+    auto stage_general = [&](int s) {
+        const int nA = next_buf(bB), nB = next_buf(nA);
+        const bool pendB = s >= 1 && s + 1 < S, pendA = s >= 1 && s + 2 < S, newB = s + 2 < S;
+        read_frags(bA, bB, 1, 1); if (pendB) pair_B(pB, 1, kChecked); mfma_step(0); order_step(false);
+        read_frags(bA, bB, 2, 0); if (pendA) pair_A(pA, 0, kChecked); mfma_step(1); order_step(false);
+        read_frags(bA, bB, 3, 1); if (pendA) pair_A(pA, 1, kChecked); mfma_step(0); order_step(false);
         if (s + 1 < S) {
-            // my fragment reads of stage s are in registers; both halves of stage s+1 have landed
-            // (the x half of stage s+2 may still be in flight)
-            if (s + 3 < S) wait_cnt<LOADS, 0>();
+            if (s + 2 < S) wait_cnt<LOADS, 0>();
             else wait_cnt<0, 0>();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             read_frags(nA, nB, 0, 0);
-            if (s + 2 < S) issue_B(bA);              // weight half of stage s+2
-            if (s + 3 < S) issue_A(bB);              // x half of stage s+3
+            if (newB) pair_B(bA, 0, kChecked);
         }
         mfma_step(1);
         __builtin_amdgcn_sched_barrier(0);
-        bA = nA;
-        bB = nB;
+        pB = bA; pA = bB; bA = nA; bB = nB;
+    };
+    int s = 0;
+    if (S > 0) { stage_general(0); s = 1; }
+    // steady state: no request of this stage starts the second reduction part (that happens in
+    // stage KS-2) and all of them exist, so the body is one branch-free block
+    const int steady_end = (KS - 3 < S - 3) ? KS - 3 : S - 3;      // last steady stage
+    for (; s <= steady_end; ++s) {
+        const int nA = next_buf(bB), nB = next_buf(nA);
+        read_frags(bA, bB, 1, 1); pair_B(pB, 1, kUnchecked); mfma_step(0); order_step(true);
+        read_frags(bA, bB, 2, 0); pair_A(pA, 0, kUnchecked); mfma_step(1); order_step(true);
+        read_frags(bA, bB, 3, 1); pair_A(pA, 1, kUnchecked); mfma_step(0); order_step(true);
+        wait_cnt<LOADS, 0>();
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        read_frags(nA, nB, 0, 0); pair_B(bA, 0, kUnchecked); mfma_step(1); order_step(true);
+        pB = bA; pA = bB; bA = nA; bB = nB;
     }
+    for (; s < S; ++s) stage_general(s);
 
     // ---- epilogue through LDS ----
     // accumulator register v of block (ni, mi): column n = ni*32 + 8*(v/4) + 4*h + v%4, row
