@@ -297,4 +297,9 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
     }
 }
 
+// Two-part product with 64-bit lane addresses (rows gathered through a.perm).
+cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st) {
+    return launch_cfg<256, 256, 2, 4, 4, EPI_STORE>(a, st);
+}
+
 }  // namespace cwl

@@ -1,27 +1,34 @@
 // Main bf16 product of cwl_chunkwise_lora_linear: y = [x | uhat] . [W^T | B^T]^T (see
-// linear_common.h for the formulation), one 256 x 256 output tile per workgroup of 8 waves.
+// linear_common.h for the formulation), one 256 x 256 output tile per workgroup of 4 waves.
 //
-// Data path (gfx950):
+// Design (gfx950), with the measurements that led to it:
+//   * Four waves, one per SIMD, each owning a 128 x 128 quarter of the tile: a k-step of 32 needs
+//     16 fragment reads (ds_read_b128) for 64 MFMAs, a third less LDS traffic than eight waves of
+//     128 x 64.  v_mfma_f32_16x16x32_bf16 with the 256 fp32 accumulators in AGPRs; on this
+//     power-limited part the 16x16x32 shape sustained a higher clock than 32x32x16 on the same data.
 //   * A stage covers 64 elements of the reduction dimension, so every global_load_lds_dwordx4
 //     fetches whole 128-byte lines (8 rows x 128 B per instruction).  The x half and the weight
 //     half of a stage are separate 32 KiB "slots"; five slots form the ring (160 KiB, all of a
-//     compute unit's LDS): two are being consumed, three are in flight.  Slots are issued in the
-//     order x0 w0 x1 w1 ...; after the barrier that retires stage s the two buffers it held take
-//     the weight half of stage s+2 and the x half of stage s+3.
+//     compute unit's LDS): two are being consumed, three are in flight.  After the barrier that
+//     retires stage s the two buffers it held take the weight half of stage s+2 and then the x
+//     half of stage s+3.
+//   * Load instructions are never issued as a burst.  The address unit takes one 64-lane
+//     instruction every ~18 cycles and a wave stays in issue until its loads are taken; bursts
+//     after the barrier held the MFMAs back for more than a thousand cycles per stage.  Here
+//     every load sits between MFMAs (one per six), as do the LDS reads (two per MFMA at the
+//     start of a k-step), by way of sched_group_barrier.
+//   * Loads use a scalar base plus a 32-bit lane offset, so the reduction loop advances two
+//     scalar pointers and does no vector address arithmetic.
 //   * LDS rows are 128 B with the 16-byte chunk index XORed by (row / 2) % 8: the ds_read_b128
-//     of a fragment (32 rows x 2 chunks) is conflict-free.
-//   * Fragments are double buffered in registers across the four k-steps of a stage; the single
-//     workgroup barrier of a stage sits before the last k-step.
-//   * A stage's eight load instructions per wave are not issued as a burst: the address unit
-//     takes one 64-lane instruction every ~18 cycles, a wave stays in issue until its loads are
-//     taken, and with all eight waves bursting together that held the MFMAs back for more than
-//     a thousand cycles per stage.  Two loads go into every k-step, each between MFMAs.
-//   * v_mfma_f32_32x32x16_bf16, fp32 accumulators, weight fragment as the first operand.
+//     of a fragment (16 rows x 4 chunks) is conflict-free.
+//   * One workgroup barrier per stage, between its two k-steps; fragments are double buffered
+//     in registers across k-steps.
 //   * Epilogue through LDS: the tile is written as bf16 into a 256 x 512 B image and read back
-//     row-wise, so each global store instruction writes two whole 512-byte row segments instead
-//     of 16-byte pieces of 32 different rows.
+//     row-wise, so each global store instruction writes two whole 512-byte row segments.
 //   * The second reduction part (uhat . B^T) walks only ceil(r_tile / 64) stages, r_tile = largest
 //     effective rank among the tile's rows; uhat is zero beyond a row's own rank.
+// Rows gathered through a permutation (rank grouping) are served by the general kernel in
+// gemm_bf16.hip instead: its loaders keep 64-bit lane addresses.
 #include <type_traits>
 
 #include "mfma_util.h"
@@ -31,19 +38,20 @@ namespace {
 
 using namespace mfma;
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int WM = 2, WN = 4;                       // wave grid
-constexpr int TM = BM / WM, TN = BN / WN;           // 128 x 64 per wave
-constexpr int MI = TM / 32, NI = TN / 32;           // 4 x 2 MFMA blocks
+constexpr int TM = 128, TN = 128;                   // per wave (2 x 2 waves)
+constexpr int MB = TM / 16, NB = TN / 16;           // 16 x 16 MFMA blocks per wave tile
 constexpr int ROW_BYTES = BK * 2;                   // 128
 constexpr int SLOT_BYTES = 256 * ROW_BYTES;         // 32 KiB: 256 rows of one operand
 constexpr int NSLOT = 5;
-constexpr int LOADS = 4;                            // load instructions per wave per slot
+constexpr int LPW = 8;                              // load instructions per wave per slot
 constexpr int SMEM_BYTES = NSLOT * SLOT_BYTES;
-static_assert(BM == 256 && BN == 256, "one slot holds 256 rows");
+constexpr int64_t kMaxLd = (int64_t)1 << 22;        // keeps 256 rows x ld x 2 bytes inside 32 bits
 static_assert(BM * BN * 2 <= SMEM_BYTES, "the output image reuses the ring");
 
-__global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
+__global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int bm, bn;
@@ -51,7 +59,7 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
     const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WN, wn = wave % WN;
+    const int wm = wave >> 1, wn = wave & 1;
 
     // largest effective rank among the rows of this tile: length of the second reduction part
     int32_t r_tile = 0;
@@ -69,202 +77,195 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
     const int KS = a.K1 / BK;                        // stages of the first part (>= 1)
     const int S = KS + (r_tile + BK - 1) / BK;       // plus those of the second part
 
-    // ---- loaders: wave w fills rows 32w .. 32w+31 of a slot, 8 rows per instruction ----
-    const __bf16* gpA[LOADS];
-    const __bf16* gpB[LOADS];
-    int32_t rowA[LOADS], rowB[LOADS];                // grouped row / output column, clamped
-    int lchunk[LOADS];
+    // ---- loaders: wave w fills rows 64w .. 64w+63 of a slot, instruction i rows 64w+8i .. +7 ----
+    // address = scalar (first row of the tile, current k) + lane offset; rows past the end of the
+    // matrix are clamped to its last row (their products are never stored)
+    uint32_t voffA[LPW], voffB[LPW];
+    const char* sA;
+    const char* sB;
+    auto set_A = [&](const void* base, int64_t ld) {
+        sA = static_cast<const char*>(base) + m0 * ld * 2;
 #pragma unroll
-    for (int i = 0; i < LOADS; ++i) {
-        const int r = wave * 32 + i * 8 + (lane >> 3);
-        lchunk[i] = (lane & 7) ^ ((r >> 1) & 7);
-        int64_t g = m0 + r;
-        if (g > a.M - 1) g = a.M - 1;
-        rowA[i] = (int32_t)g;
-        const int64_t t = a.perm ? (int64_t)a.perm[g] : g;
-        gpA[i] = static_cast<const __bf16*>(a.A1) + t * a.lda1 + lchunk[i] * 8;
-        int64_t n = n0 + r;
-        if (n > a.N - 1) n = a.N - 1;
-        rowB[i] = (int32_t)n;
-        gpB[i] = static_cast<const __bf16*>(a.B1) + n * a.ldb1 + lchunk[i] * 8;
-    }
-    // Loads are requested two instructions ("a pair") at a time so that they can sit between MFMAs:
-    // a wave that issues a burst of loads is held until the address unit has taken them all, and
-    // its MFMAs wait behind them.  cntA / cntB count pairs; pair 2t of an operand starts stage t.
-    int cntA = 0, cntB = 0;
-    auto switch_A = [&]() {           // from x to uhat
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            gpA[i] = static_cast<const __bf16*>(a.A2) + (int64_t)rowA[i] * a.lda2 + lchunk[i] * 8;
-    };
-    auto switch_B = [&]() {           // from W^T to B^T
-#pragma unroll
-        for (int i = 0; i < LOADS; ++i)
-            gpB[i] = static_cast<const __bf16*>(a.B2) + (int64_t)rowB[i] * a.ldb2 + lchunk[i] * 8;
-    };
-    auto pair_A = [&](int buf, int pair, auto checked) {
-        if (checked.value && cntA == 2 * KS) switch_A();
-        char* base = smem + buf * SLOT_BYTES + wave * LOADS * 1024;
-#pragma unroll
-        for (int i = 2 * pair; i < 2 * pair + 2; ++i) {
-            load_lds_16(gpA[i], base + i * 1024);
-            gpA[i] += BK;
+        for (int i = 0; i < LPW; ++i) {
+            const int r = wave * 64 + i * 8 + (lane >> 3);
+            const int ch = (lane & 7) ^ ((r >> 1) & 7);
+            int64_t g = m0 + r;
+            if (g > a.M - 1) g = a.M - 1;
+            voffA[i] = (uint32_t)(((g - m0) * ld + ch * 8) * 2);
         }
+    };
+    auto set_B = [&](const void* base, int64_t ld) {
+        sB = static_cast<const char*>(base) + n0 * ld * 2;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            const int r = wave * 64 + i * 8 + (lane >> 3);
+            const int ch = (lane & 7) ^ ((r >> 1) & 7);
+            int64_t n = n0 + r;
+            if (n > a.N - 1) n = a.N - 1;
+            voffB[i] = (uint32_t)(((n - n0) * ld + ch * 8) * 2);
+        }
+    };
+    set_A(a.A1, a.lda1);
+    set_B(a.B1, a.ldb1);
+    int cntA = 0, cntB = 0;                          // slots requested per operand = next stage
+    auto slot_A = [&](int buf, auto checked) {
+        if (checked.value && cntA == KS) set_A(a.A2, a.lda2);      // from x to uhat
+        char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
+#pragma unroll
+        for (int i = 0; i < LPW; ++i) {
+            uint32_t v = voffA[i];
+            asm volatile("" : "+v"(v));   // keeps the zero-extension at the load, which then takes
+                                          // the scalar-base + 32-bit-offset form
+            load_lds_16(sA + v, base + i * 1024);
+        }
+        sA += ROW_BYTES;
         ++cntA;
     };
-    auto pair_B = [&](int buf, int pair, auto checked) {
-        if (checked.value && cntB == 2 * KS) switch_B();
-        char* base = smem + buf * SLOT_BYTES + wave * LOADS * 1024;
+    auto slot_B = [&](int buf, auto checked) {
+        if (checked.value && cntB == KS) set_B(a.B2, a.ldb2);      // from W^T to B^T
+        char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
-        for (int i = 2 * pair; i < 2 * pair + 2; ++i) {
-            load_lds_16(gpB[i], base + i * 1024);
-            gpB[i] += BK;
+        for (int i = 0; i < LPW; ++i) {
+            uint32_t v = voffB[i];
+            asm volatile("" : "+v"(v));
+            load_lds_16(sB + v, base + i * 1024);
         }
+        sB += ROW_BYTES;
         ++cntB;
     };
     constexpr std::true_type kChecked{};
     constexpr std::false_type kUnchecked{};
-    auto issue_A = [&](int buf) { pair_A(buf, 0, kChecked); pair_A(buf, 1, kChecked); };
-    auto issue_B = [&](int buf) { pair_B(buf, 0, kChecked); pair_B(buf, 1, kChecked); };
 
-    // ---- fragment addressing ----
-    const int l32 = lane & 31, h = lane >> 5;
-    const int sw = (l32 >> 1) & 7;
-    int koff[4];
+    // ---- fragment addressing: lane l reads row l % 16 of a block, chunk 4 kk + l / 16 ----
+    const int l16 = lane & 15, g4 = lane >> 4;
+    int koff[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((2 * kk + h) ^ sw) * 16;
-    const int a_base = (wm * TM + l32) * ROW_BYTES;
-    const int b_base = (wn * TN + l32) * ROW_BYTES;
+    for (int kk = 0; kk < 2; ++kk) koff[kk] = ((kk * 4 + g4) ^ (l16 >> 1)) * 16;
+    const int a_base = (wm * TM + l16) * ROW_BYTES;
+    const int b_base = (wn * TN + l16) * ROW_BYTES;
 
-    f32x16 acc[NI][MI];
+    f32x4 acc[NB][MB];
 #pragma unroll
-    for (int ni = 0; ni < NI; ++ni)
+    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[nb][mb][v] = 0.0f;
 
-    bf16x8 af[2][MI], bfr[2][NI];
+    bf16x8 af[2][MB], bfr[2][NB];
     auto read_frags = [&](int bufA, int bufB, int kk, int f) {
-        const char* sa = smem + bufA * SLOT_BYTES;
-        const char* sb = smem + bufB * SLOT_BYTES;
+        const char* sa = smem + bufA * SLOT_BYTES + a_base + koff[kk];
+        const char* sb = smem + bufB * SLOT_BYTES + b_base + koff[kk];
 #pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            af[f][mi] = *reinterpret_cast<const bf16x8*>(sa + a_base + mi * 32 * ROW_BYTES + koff[kk]);
-#pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
-            bfr[f][ni] = *reinterpret_cast<const bf16x8*>(sb + b_base + ni * 32 * ROW_BYTES + koff[kk]);
+        for (int i = 0; i < 8; ++i) {
+            bfr[f][i] = *reinterpret_cast<const bf16x8*>(sb + i * 16 * ROW_BYTES);
+            af[f][i] = *reinterpret_cast<const bf16x8*>(sa + i * 16 * ROW_BYTES);
+        }
     };
+    // the weight fragment is the first operand: a lane ends with 4 consecutive output columns
     auto mfma_step = [&](int f) {
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi)
-                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[f][ni], af[f][mi], acc[ni][mi], 0, 0, 0);
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[f][nb], af[f][mb], acc[nb][mb], 0, 0, 0);
     };
-    // issue order inside a k-step: one MFMA (its operands are already in registers), the LDS reads
-    // of the next k-step, then the remaining MFMAs with the step's two loads spaced out among them
+    // a k-step: 64 MFMAs, the 16 LDS reads of the next k-step among the first eight, the slot's
+    // eight loads one per six MFMAs after that
     auto order_step = [&](bool with_loads) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, MI + NI, 0);
-        if (with_loads) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        } else {
-            __builtin_amdgcn_sched_group_barrier(0x008, MI * NI - 1, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+            if (with_loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto next_buf = [](int v) { return v + 1 == NSLOT ? 0 : v + 1; };
 
     // ---- prologue: slots x0 w0 x1 w1 x2 into buffers 0..4 ----
-    issue_A(0);
-    issue_B(1);
-    if (S > 1) { issue_A(2); issue_B(3); }
-    if (S > 2) { issue_A(4); wait_cnt<3 * LOADS, 15>(); }
+    slot_A(0, kChecked);
+    slot_B(1, kChecked);
+    if (S > 1) { slot_A(2, kChecked); slot_B(3, kChecked); }
+    if (S > 2) { slot_A(4, kChecked); wait_cnt<3 * LPW, 15>(); }
     else wait_cnt<0, 15>();
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     int bA = 0, bB = 1;               // buffers of the stage being computed
-    int pB = 0, pA = 0;               // buffers released at the previous barrier: they take the weight
-                                      // half of stage s+1 (second pair still to request) and the x half of s+2
+    int pA = 0;                       // buffer released at the previous barrier for the x half of stage s+2
     read_frags(bA, bB, 0, 0);
 
-    // Stage s, k-steps 0..2, barrier, k-step 3.  Requests in program order: weights of stage s+1
-    // (second pair), x of stage s+2 (both pairs), barrier, weights of stage s+2 (first pair).  At
-    // the barrier everything but the x half just requested must have landed.
+    // Stage s: k-step 0 (requesting the x half of stage s+2), barrier, k-step 1 (requesting the
+    // weight half of stage s+2).  At the barrier everything but that x half must have landed.
     auto stage_general = [&](int s) {
         const int nA = next_buf(bB), nB = next_buf(nA);
-        const bool pendB = s >= 1 && s + 1 < S, pendA = s >= 1 && s + 2 < S, newB = s + 2 < S;
-        read_frags(bA, bB, 1, 1); if (pendB) pair_B(pB, 1, kChecked); mfma_step(0); order_step(false);
-        read_frags(bA, bB, 2, 0); if (pendA) pair_A(pA, 0, kChecked); mfma_step(1); order_step(false);
-        read_frags(bA, bB, 3, 1); if (pendA) pair_A(pA, 1, kChecked); mfma_step(0); order_step(false);
+        read_frags(bA, bB, 1, 1);
+        if (s >= 1 && s + 2 < S) slot_A(pA, kChecked);
+        mfma_step(0);
+        order_step(false);
         if (s + 1 < S) {
-            if (s + 2 < S) wait_cnt<LOADS, 0>();
+            if (s + 2 < S) wait_cnt<LPW, 0>();
             else wait_cnt<0, 0>();
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
             read_frags(nA, nB, 0, 0);
-            if (newB) pair_B(bA, 0, kChecked);
+            if (s + 2 < S) slot_B(bA, kChecked);
         }
         mfma_step(1);
-        __builtin_amdgcn_sched_barrier(0);
-        pB = bA; pA = bB; bA = nA; bB = nB;
+        order_step(false);
+        pA = bB; bA = nA; bB = nB;
     };
     int s = 0;
     if (S > 0) { stage_general(0); s = 1; }
-    // steady state: no request of this stage starts the second reduction part (that happens in
-    // stage KS-2) and all of them exist, so the body is one branch-free block
+    // steady state: both requests of the stage exist and neither starts the second reduction
+    // part (stage KS-2 does), so the body is one branch-free block
     const int steady_end = (KS - 3 < S - 3) ? KS - 3 : S - 3;      // last steady stage
     for (; s <= steady_end; ++s) {
         const int nA = next_buf(bB), nB = next_buf(nA);
-        read_frags(bA, bB, 1, 1); pair_B(pB, 1, kUnchecked); mfma_step(0); order_step(true);
-        read_frags(bA, bB, 2, 0); pair_A(pA, 0, kUnchecked); mfma_step(1); order_step(true);
-        read_frags(bA, bB, 3, 1); pair_A(pA, 1, kUnchecked); mfma_step(0); order_step(true);
-        wait_cnt<LOADS, 0>();
+        read_frags(bA, bB, 1, 1); slot_A(pA, kUnchecked); mfma_step(0); order_step(true);
+        wait_cnt<LPW, 0>();
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(nA, nB, 0, 0); pair_B(bA, 0, kUnchecked); mfma_step(1); order_step(true);
-        pB = bA; pA = bB; bA = nA; bB = nB;
+        read_frags(nA, nB, 0, 0); slot_B(bA, kUnchecked); mfma_step(1); order_step(true);
+        pA = bB; bA = nA; bB = nB;
     }
     for (; s < S; ++s) stage_general(s);
 
     // ---- epilogue through LDS ----
-    // accumulator register v of block (ni, mi): column n = ni*32 + 8*(v/4) + 4*h + v%4, row
-    // m = mi*32 + l32 (relative to the wave tile).  Image: row r at r*512; 16-byte chunk c (8
-    // columns) is stored at chunk c ^ (r % 16) and its two 8-byte halves are swapped when bit 4
-    // of r is set, which makes the 32-row ds_write_b64 of one (ni, q) hit every bank once.
+    // accumulator register v of block (nb, mb): column nb*16 + 4*(l/16) + v, row mb*16 + l%16
+    // (relative to the wave tile).  Image: row r at r*512; 16-byte chunk c (8 columns) is stored
+    // at chunk c ^ (r % 16) and its two 8-byte halves are swapped when bit 4 of r is set: the
+    // 16 rows x 2 halves written by 32 lanes of one ds_write_b64 hit every bank once.
     wait_cnt<0, 0>();
     __builtin_amdgcn_s_barrier();                    // every wave has finished reading the ring
 #pragma unroll
-    for (int mi = 0; mi < MI; ++mi) {
-        const int r = wm * TM + mi * 32 + l32;
-        char* rowp = smem + r * 512 + ((((r >> 4) & 1) ^ h) << 3);
+    for (int mb = 0; mb < MB; ++mb) {
+        const int r = wm * TM + mb * 16 + l16;
+        char* rowp = smem + r * 512 + ((((r >> 4) & 1) ^ (g4 & 1)) << 3);
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni)
+        for (int nb = 0; nb < NB; ++nb) {
+            const int c = wn * (TN / 8) + nb * 2 + (g4 >> 1);
+            bf16x4 o;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = wn * (TN / 8) + ni * 4 + q;
-                bf16x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[ni][mi][q * 4 + e];
-                *reinterpret_cast<bf16x4*>(rowp + ((c ^ (r & 15)) << 4)) = o;
-            }
+            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[nb][mb][e];
+            *reinterpret_cast<bf16x4*>(rowp + ((c ^ (r & 15)) << 4)) = o;
+        }
     }
     wait_cnt<0, 0>();
     __builtin_amdgcn_s_barrier();
-    // wave w writes rows 32w .. 32w+31, two rows (2 x 512 B) per store instruction
+    // wave w writes rows 64w .. 64w+63, two rows (2 x 512 B) per store instruction
     const int c = lane & 31;
     const int64_t n = n0 + c * 8;                    // N is a multiple of 8: a chunk is in or out whole
 #pragma unroll 4
-    for (int it = 0; it < 16; ++it) {
-        const int r = wave * 32 + it * 2 + (lane >> 5);
+    for (int it = 0; it < 32; ++it) {
+        const int r = wave * 64 + it * 2 + (lane >> 5);
         const int64_t g = m0 + r;
         if (g >= a.M || n >= a.N) continue;
-        const int64_t t = a.perm ? (int64_t)a.perm[g] : g;
         const u32x4 v = *reinterpret_cast<const u32x4*>(smem + r * 512 + ((c ^ (r & 15)) << 4));
         const bool flip = (r >> 4) & 1;
         u32x4 o;
@@ -272,15 +273,17 @@ __global__ void __launch_bounds__(512) main_bf16_kernel(GemmArgs a) {
         o[1] = flip ? v[3] : v[1];
         o[2] = flip ? v[0] : v[2];
         o[3] = flip ? v[1] : v[3];
-        *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + t * a.ldc + n) = o;
+        *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = o;
     }
 }
 
 }  // namespace
 
 cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
+    if (a_in.perm) return launch_main_bf16_general(a_in, st);
     GemmArgs a = a_in;
     if (a.K1 < BK || a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
+    if (a.lda1 > kMaxLd || a.ldb1 > kMaxLd || a.lda2 > kMaxLd || a.ldb2 > kMaxLd) return CWL_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(main_bf16_kernel),
@@ -294,7 +297,7 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     if (n_tiles <= 0) return CWL_OK;
     const int64_t grid = (n_tiles + 7) / 8 * 8;
     if (grid >= (int64_t)1 << 31) return CWL_ERR_UNSUPPORTED;
-    main_bf16_kernel<<<dim3((unsigned)grid), dim3(512), SMEM_BYTES, st>>>(a);
+    main_bf16_kernel<<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }

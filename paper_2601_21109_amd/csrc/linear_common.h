@@ -63,5 +63,6 @@ enum { EPI_STORE = 0, EPI_GATE = 1 };
 cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
+cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st);   // any a.perm
 
 }  // namespace cwl
