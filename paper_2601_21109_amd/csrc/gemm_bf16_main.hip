@@ -29,8 +29,6 @@
 //     effective rank among the tile's rows; uhat is zero beyond a row's own rank.
 // Rows gathered through a permutation (rank grouping) are served by the general kernel in
 // gemm_bf16.hip instead: its loaders keep 64-bit lane addresses.
-#include <type_traits>
-
 #include "mfma_util.h"
 
 namespace cwl {
@@ -51,65 +49,140 @@ constexpr int SMEM_BYTES = NSLOT * SLOT_BYTES;
 constexpr int64_t kMaxLd = (int64_t)1 << 22;        // keeps 256 rows x ld x 2 bytes inside 32 bits
 static_assert(BM * BN * 2 <= SMEM_BYTES, "the output image reuses the ring");
 
-__global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
+// Virtual workgroup v -> (row tile, column tile), the XCD-aware order of mfma::tile_coords with
+// the index passed in: a persistent workgroup b walks v = b, b + gridDim.x, ... and so stays in
+// the band of the XCD it runs on (gridDim.x is a multiple of 8).
+__device__ __forceinline__ bool tile_of(int32_t v, int32_t n_virtual, int32_t tiles_m, int32_t tiles_n,
+                                        int32_t* bm, int32_t* bn) {
+    constexpr int32_t kXcd = 8, GROUP_M = 8;
+    if (v >= n_virtual) return false;
+    const int32_t n_tiles = tiles_m * tiles_n;
+    const int32_t per_xcd = (n_tiles + kXcd - 1) / kXcd;
+    const int32_t tile = (v % kXcd) * per_xcd + v / kXcd;
+    if (tile >= n_tiles) return false;
+    const int32_t band_size = GROUP_M * tiles_n;
+    const int32_t band = tile / band_size, in_band = tile % band_size;
+    const int32_t first_m = band * GROUP_M;
+    const int32_t gm = (tiles_m - first_m < GROUP_M) ? tiles_m - first_m : GROUP_M;
+    *bm = first_m + in_band % gm;
+    *bn = in_band / gm;
+    return true;
+}
+
+__global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_virtual) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-    int bm, bn;
-    if (!tile_coords(a.tiles_m, a.tiles_n, &bm, &bn)) return;
-    const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
+    const int32_t v_step = (int32_t)gridDim.x;
+    const int KS = a.K1 / BK;                        // stages of the first reduction part (>= 1)
 
-    // largest effective rank among the rows of this tile: length of the second reduction part
-    int32_t r_tile = 0;
-    if (a.blk_r) {
-        const int64_t n_blk = (a.M + kRankBlock - 1) / kRankBlock;
+    // stages of a row tile: the first part plus ceil(r_tile / 64), r_tile = largest effective
+    // rank among the tile's rows
+    auto stages_of = [&](int32_t bm) -> int {
+        int32_t r_tile = 0;
+        if (a.blk_r) {
+            const int64_t n_blk = (a.M + kRankBlock - 1) / kRankBlock;
 #pragma unroll
-        for (int i = 0; i < BM / kRankBlock; ++i) {
-            const int64_t blk = m0 / kRankBlock + i;
-            if (blk < n_blk) {
-                const int32_t r = a.blk_r[blk];
-                r_tile = r > r_tile ? r : r_tile;
+            for (int i = 0; i < BM / kRankBlock; ++i) {
+                const int64_t blk = (int64_t)bm * (BM / kRankBlock) + i;
+                if (blk < n_blk) {
+                    const int32_t r = a.blk_r[blk];
+                    r_tile = r > r_tile ? r : r_tile;
+                }
             }
         }
-    }
-    const int KS = a.K1 / BK;                        // stages of the first part (>= 1)
-    const int S = KS + (r_tile + BK - 1) / BK;       // plus those of the second part
+        return KS + (r_tile + BK - 1) / BK;
+    };
 
-    // ---- loaders: wave w fills rows 64w .. 64w+63 of a slot, instruction i rows 64w+8i .. +7 ----
-    // address = scalar (first row of the tile, current k) + lane offset; rows past the end of the
-    // matrix are clamped to its last row (their products are never stored)
+    // ---- loaders ----
+    // Wave w fills rows 64w .. 64w+63 of a slot, instruction i rows 64w+8i .. +7.  Address =
+    // scalar (first row of the tile, current k) + 32-bit lane offset; rows past the end of the
+    // matrix are clamped to its last row (their products are never stored).  The x loader and
+    // the weight loader each walk (tile, stage) on their own, ahead of the MFMAs: the ring does
+    // not drain at a tile boundary.  Every stage requests exactly one x slot and one weight
+    // slot, so the reduction loop has a single branch-free body; what changes between stages
+    // (second reduction part, next tile) is patched into the loader state after the body.  A
+    // loader that has run out of tiles keeps re-requesting its last slot into buffers nobody
+    // reads (stepA / stepB = 0), which only happens in the last two stages of the kernel.
     uint32_t voffA[LPW], voffB[LPW];
-    const char* sA;
-    const char* sB;
+    const char* sA = nullptr;
+    const char* sB = nullptr;
+    int32_t vA = (int32_t)blockIdx.x, vB = (int32_t)blockIdx.x;
+    int cntA = 0, cntB = 0, SA = 0, SB = 0;          // next stage to request, stages of the loader's tile
+    int stepA = ROW_BYTES, stepB = ROW_BYTES;
+    int64_t m0A = 0, n0B = 0;
+    bool validA = false, validB = false;
+    // (the lane index is made opaque where rarely-run code derives addresses from it: otherwise the
+    // compiler computes all of that once, ahead of the tile loop, and the values crowd the register file)
     auto set_A = [&](const void* base, int64_t ld) {
-        sA = static_cast<const char*>(base) + m0 * ld * 2;
+        sA = static_cast<const char*>(base) + m0A * ld * 2;
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int r = wave * 64 + i * 8 + (lane >> 3);
-            const int ch = (lane & 7) ^ ((r >> 1) & 7);
-            int64_t g = m0 + r;
+            const int r = wave * 64 + i * 8 + (ln >> 3);
+            const int ch = (ln & 7) ^ ((r >> 1) & 7);
+            int64_t g = m0A + r;
             if (g > a.M - 1) g = a.M - 1;
-            voffA[i] = (uint32_t)(((g - m0) * ld + ch * 8) * 2);
+            voffA[i] = (uint32_t)(((g - m0A) * ld + ch * 8) * 2);
         }
     };
     auto set_B = [&](const void* base, int64_t ld) {
-        sB = static_cast<const char*>(base) + n0 * ld * 2;
+        sB = static_cast<const char*>(base) + n0B * ld * 2;
+        int ln = lane;
+        asm volatile("" : "+v"(ln));
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            const int r = wave * 64 + i * 8 + (lane >> 3);
-            const int ch = (lane & 7) ^ ((r >> 1) & 7);
-            int64_t n = n0 + r;
+            const int r = wave * 64 + i * 8 + (ln >> 3);
+            const int ch = (ln & 7) ^ ((r >> 1) & 7);
+            int64_t n = n0B + r;
             if (n > a.N - 1) n = a.N - 1;
-            voffB[i] = (uint32_t)(((n - n0) * ld + ch * 8) * 2);
+            voffB[i] = (uint32_t)(((n - n0B) * ld + ch * 8) * 2);
         }
     };
-    set_A(a.A1, a.lda1);
-    set_B(a.B1, a.ldb1);
-    int cntA = 0, cntB = 0;                          // slots requested per operand = next stage
-    auto slot_A = [&](int buf, auto checked) {
-        if (checked.value && cntA == KS) set_A(a.A2, a.lda2);      // from x to uhat
+    auto tile_A = [&]() {
+        int32_t bm = 0, bn = 0;
+        validA = tile_of(vA, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn);
+        if (validA) {
+            m0A = (int64_t)bm * BM;
+            SA = stages_of(bm);
+            cntA = 0;
+            set_A(a.A1, a.lda1);
+        } else {
+            sA -= ROW_BYTES;          // stay on the last slot requested
+            stepA = 0;
+        }
+    };
+    auto tile_B = [&]() {
+        int32_t bm = 0, bn = 0;
+        validB = tile_of(vB, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn);
+        if (validB) {
+            n0B = (int64_t)bn * BN;
+            SB = stages_of(bm);
+            cntB = 0;
+            set_B(a.B1, a.ldb1);
+        } else {
+            sB -= ROW_BYTES;
+            stepB = 0;
+        }
+    };
+    // after a request: move the loader to its next tile, or to the second reduction part
+    auto patch_A = [&]() {
+        if (validA) {
+            if (cntA == SA) { vA += v_step; tile_A(); }
+            else if (cntA == KS) set_A(a.A2, a.lda2);          // from x to uhat
+        }
+    };
+    auto patch_B = [&]() {
+        if (validB) {
+            if (cntB == SB) { vB += v_step; tile_B(); }
+            else if (cntB == KS) set_B(a.B2, a.ldb2);          // from W^T to B^T
+        }
+    };
+    // one slot = 8 load instructions per wave
+    auto slot_A = [&](int buf) {
         char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
@@ -118,11 +191,10 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
                                           // the scalar-base + 32-bit-offset form
             load_lds_16(sA + v, base + i * 1024);
         }
-        sA += ROW_BYTES;
+        sA += stepA;
         ++cntA;
     };
-    auto slot_B = [&](int buf, auto checked) {
-        if (checked.value && cntB == KS) set_B(a.B2, a.ldb2);      // from W^T to B^T
+    auto slot_B = [&](int buf) {
         char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
@@ -130,11 +202,9 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
             asm volatile("" : "+v"(v));
             load_lds_16(sB + v, base + i * 1024);
         }
-        sB += ROW_BYTES;
+        sB += stepB;
         ++cntB;
     };
-    constexpr std::true_type kChecked{};
-    constexpr std::false_type kUnchecked{};
 
     // ---- fragment addressing: lane l reads row l % 16 of a block, chunk 4 kk + l / 16 ----
     const int l16 = lane & 15, g4 = lane >> 4;
@@ -145,13 +215,6 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
     const int b_base = (wn * TN + l16) * ROW_BYTES;
 
     f32x4 acc[NB][MB];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[nb][mb][v] = 0.0f;
-
     bf16x8 af[2][MB], bfr[2][NB];
     auto read_frags = [&](int bufA, int bufB, int kk, int f) {
         const char* sa = smem + bufA * SLOT_BYTES + a_base + koff[kk];
@@ -172,7 +235,7 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
     };
     // a k-step: 64 MFMAs, the 16 LDS reads of the next k-step among the first eight, the slot's
     // eight loads one per six MFMAs after that
-    auto order_step = [&](bool with_loads) {
+    auto order_step = [&]() {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -181,100 +244,148 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
-            if (with_loads) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto next_buf = [](int v) { return v + 1 == NSLOT ? 0 : v + 1; };
-
-    // ---- prologue: slots x0 w0 x1 w1 x2 into buffers 0..4 ----
-    slot_A(0, kChecked);
-    slot_B(1, kChecked);
-    if (S > 1) { slot_A(2, kChecked); slot_B(3, kChecked); }
-    if (S > 2) { slot_A(4, kChecked); wait_cnt<3 * LPW, 15>(); }
-    else wait_cnt<0, 15>();
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    int bA = 0, bB = 1;               // buffers of the stage being computed
-    int pA = 0;                       // buffer released at the previous barrier for the x half of stage s+2
-    read_frags(bA, bB, 0, 0);
-
-    // Stage s: k-step 0 (requesting the x half of stage s+2), barrier, k-step 1 (requesting the
-    // weight half of stage s+2).  At the barrier everything but that x half must have landed.
-    auto stage_general = [&](int s) {
-        const int nA = next_buf(bB), nB = next_buf(nA);
-        read_frags(bA, bB, 1, 1);
-        if (s >= 1 && s + 2 < S) slot_A(pA, kChecked);
-        mfma_step(0);
-        order_step(false);
-        if (s + 1 < S) {
-            if (s + 2 < S) wait_cnt<LPW, 0>();
-            else wait_cnt<0, 0>();
-            __builtin_amdgcn_s_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            read_frags(nA, nB, 0, 0);
-            if (s + 2 < S) slot_B(bA, kChecked);
-        }
-        mfma_step(1);
-        order_step(false);
-        pA = bB; bA = nA; bB = nB;
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[nb][mb][v] = 0.0f;
     };
-    int s = 0;
-    if (S > 0) { stage_general(0); s = 1; }
-    // steady state: both requests of the stage exist and neither starts the second reduction
-    // part (stage KS-2 does), so the body is one branch-free block
-    const int steady_end = (KS - 3 < S - 3) ? KS - 3 : S - 3;      // last steady stage
-    for (; s <= steady_end; ++s) {
-        const int nA = next_buf(bB), nB = next_buf(nA);
-        read_frags(bA, bB, 1, 1); slot_A(pA, kUnchecked); mfma_step(0); order_step(true);
-        wait_cnt<LPW, 0>();
+    auto next_buf = [](int v) { return v + 1 == NSLOT ? 0 : v + 1; };
+    auto sync = [&]() {
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        read_frags(nA, nB, 0, 0); slot_B(bA, kUnchecked); mfma_step(1); order_step(true);
-        pA = bB; bA = nA; bB = nB;
-    }
-    for (; s < S; ++s) stage_general(s);
+    };
 
-    // ---- epilogue through LDS ----
-    // accumulator register v of block (nb, mb): column nb*16 + 4*(l/16) + v, row mb*16 + l%16
-    // (relative to the wave tile).  Image: row r at r*512; 16-byte chunk c (8 columns) is stored
-    // at chunk c ^ (r % 16) and its two 8-byte halves are swapped when bit 4 of r is set: the
-    // 16 rows x 2 halves written by 32 lanes of one ds_write_b64 hit every bank once.
-    wait_cnt<0, 0>();
-    __builtin_amdgcn_s_barrier();                    // every wave has finished reading the ring
+    // ---- this workgroup's first tile; prologue: slots x0 w0 x1 w1 into buffers 0..3 ----
+    int32_t vC = (int32_t)blockIdx.x, bm = 0, bn = 0;
+    if (!tile_of(vC, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn)) return;
+    tile_A();
+    tile_B();
+    slot_A(0); patch_A();
+    slot_B(1); patch_B();
+    slot_A(2); patch_A();
+    slot_B(3); patch_B();
+    wait_cnt<2 * LPW, 15>();          // stage 0 has landed
+    sync();
+    int bA = 0, bB = 1;               // buffers of the stage being computed
+    int pA = 4;                       // buffer that takes the next x slot (two stages ahead)
+    read_frags(bA, bB, 0, 0);
+
+    while (true) {                    // tiles of this workgroup
+        const int S = stages_of(bm);
+        const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
+        zero_acc();
+        // Stage body: k-step 0 (requesting the x slot two stages ahead), barrier, k-step 1
+        // (requesting the weight slot two stages ahead into the x buffer just released).  At the
+        // barrier everything but the x slot just requested has landed: the next stage, which may
+        // be the next tile's first; its first fragments are read during k-step 1.  With one wave per
+        // SIMD whatever follows the last MFMA of a stage is not hidden by anything, so the loader
+        // patches run only after the stages that can need them.
+        auto stage = [&](bool patch) {
+            const int nA = next_buf(bB), nB = next_buf(nA);
+            read_frags(bA, bB, 1, 1); slot_A(pA); mfma_step(0); order_step();
+            wait_cnt<LPW, 0>();
+            sync();
+            read_frags(nA, nB, 0, 0); slot_B(bA); mfma_step(1); order_step();
+            if (patch) {
+                patch_A();
+                patch_B();
+            }
+            pA = bB; bA = nA; bB = nB;
+        };
+        // The first stage is peeled out of the loops: with the cleared accumulators entering a loop
+        // directly, the compiler shuffled them between registers in every iteration.
+        stage(true);
+        int s = 1;
+        // stages whose requests (stage s+2 of this tile) stay inside the first reduction part
+        const int plain_end = (KS < S ? KS : S) - 4;
+        for (; s <= plain_end; ++s) stage(false);
+        for (; s < S; ++s) stage(true);
+
+        // ---- epilogue through LDS, four passes of 64 rows through buffer pA ----
+        // pA (the weight buffer of the stage just finished) is the one free buffer here: the next
+        // request into it comes with the next stage body.  In pass q every wave hands over its
+        // blocks mb = 2q, 2q+1 (32 rows): image rows 0..31 are tile rows 32q .. 32q+31, image rows
+        // 32..63 are tile rows 128+32q .. (the lower wave row).  Accumulator register v of block
+        // (nb, mb): column nb*16 + 4*(l/16) + v, row mb*16 + l%16.  A 16-byte chunk c (8 columns)
+        // of image row r is stored at chunk c ^ (r % 16) with its 8-byte halves swapped when bit 4
+        // of r is set: the 16 rows x 2 halves written by 32 lanes of one ds_write_b64 hit every
+        // bank once.  Then each wave stores 16 image rows, two (2 x 512 B) per instruction.
+        //
+        // The accumulators are read with inline assembly (left to itself the compiler copies all
+        // 256 out of the AGPRs first, which leaves no vector registers for the fragments that
+        // live across the epilogue).  The compiler does not insert the wait states an MFMA result
+        // needs before a vector instruction may read it into inline assembly; the instructions
+        // since the last MFMA already cover them, the explicit ones make that independent of
+        // scheduling.
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_nop 15");
+        asm volatile("s_nop 15");
+        __builtin_amdgcn_sched_barrier(0);
+        char* img = smem + pA * SLOT_BYTES;
+        int le = lane;
+        asm volatile("" : "+v"(le));
+        const int c = le & 31, l16e = le & 15, g4e = le >> 4;
+        const int64_t n = n0 + c * 8;                // N is a multiple of 8: a chunk is in or out whole
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-        const int r = wm * TM + mb * 16 + l16;
-        char* rowp = smem + r * 512 + ((((r >> 4) & 1) ^ (g4 & 1)) << 3);
+        for (int q = 0; q < 4; ++q) {
+            if (q > 0) {
+                wait_cnt<63, 0>();
+                sync();                               // the previous pass has been read out
+            }
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int c = wn * (TN / 8) + nb * 2 + (g4 >> 1);
-            bf16x4 o;
+            for (int m2 = 0; m2 < 2; ++m2) {
+                const int mb = 2 * q + m2;
+                const int r = wm * 32 + m2 * 16 + l16e;
+                char* rowp = img + r * 512 + ((((r >> 4) & 1) ^ (g4e & 1)) << 3);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[nb][mb][e];
-            *reinterpret_cast<bf16x4*>(rowp + ((c ^ (r & 15)) << 4)) = o;
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int ch = wn * (TN / 8) + nb * 2 + (g4e >> 1);
+                    float x0, x1, x2, x3;
+                    asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
+                                 "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
+                                 : "=v"(x0), "=v"(x1), "=v"(x2), "=v"(x3)
+                                 : "a"(acc[nb][mb][0]), "a"(acc[nb][mb][1]), "a"(acc[nb][mb][2]), "a"(acc[nb][mb][3])
+                                 : "memory");
+                    bf16x4 o;
+                    o[0] = (__bf16)x0; o[1] = (__bf16)x1; o[2] = (__bf16)x2; o[3] = (__bf16)x3;
+                    *reinterpret_cast<bf16x4*>(rowp + ((ch ^ (r & 15)) << 4)) = o;
+                }
+            }
+            wait_cnt<63, 0>();
+            sync();
+            u32x4 v[8];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {          // all eight reads in flight before the first store
+                const int r = wave * 16 + it * 2 + (le >> 5);            // image row
+                v[it] = *reinterpret_cast<const u32x4*>(img + r * 512 + ((c ^ (r & 15)) << 4));
+            }
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int r = wave * 16 + it * 2 + (le >> 5);
+                const int64_t g = m0 + (r >> 5) * TM + q * 32 + (r & 31);
+                const bool flip = (r >> 4) & 1;
+                u32x4 o;
+                o[0] = flip ? v[it][2] : v[it][0];
+                o[1] = flip ? v[it][3] : v[it][1];
+                o[2] = flip ? v[it][0] : v[it][2];
+                o[3] = flip ? v[it][1] : v[it][3];
+                if (g < a.M && n < a.N) *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = o;
+            }
         }
+        vC += v_step;
+        if (!tile_of(vC, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn)) break;
+        wait_cnt<63, 0>();
+        sync();                                       // pA may be written by the next request
     }
-    wait_cnt<0, 0>();
-    __builtin_amdgcn_s_barrier();
-    // wave w writes rows 64w .. 64w+63, two rows (2 x 512 B) per store instruction
-    const int c = lane & 31;
-    const int64_t n = n0 + c * 8;                    // N is a multiple of 8: a chunk is in or out whole
-#pragma unroll 4
-    for (int it = 0; it < 32; ++it) {
-        const int r = wave * 64 + it * 2 + (lane >> 5);
-        const int64_t g = m0 + r;
-        if (g >= a.M || n >= a.N) continue;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(smem + r * 512 + ((c ^ (r & 15)) << 4));
-        const bool flip = (r >> 4) & 1;
-        u32x4 o;
-        o[0] = flip ? v[2] : v[0];
-        o[1] = flip ? v[3] : v[1];
-        o[2] = flip ? v[0] : v[2];
-        o[3] = flip ? v[1] : v[3];
-        *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = o;
-    }
+    wait_cnt<0, 0>();                                 // nothing of this wave's is still on its way into LDS
 }
 
 }  // namespace
@@ -295,9 +406,19 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
     const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (n_tiles <= 0) return CWL_OK;
-    const int64_t grid = (n_tiles + 7) / 8 * 8;
-    if (grid >= (int64_t)1 << 31) return CWL_ERR_UNSUPPORTED;
-    main_bf16_kernel<<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a);
+    const int64_t n_virtual = (n_tiles + 7) / 8 * 8;       // workgroup slots, 8 XCDs round-robin
+    if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
+    // persistent: one workgroup per compute unit (160 KiB of LDS each), a multiple of 8 of them
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
+            return CWL_ERR_DEVICE;
+        n_cu = v / 8 * 8;
+    }
+    const int64_t grid = n_virtual < n_cu ? n_virtual : n_cu;
+    main_bf16_kernel<<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a, (int32_t)n_virtual);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }
