@@ -109,18 +109,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    # ---- the timed region: K whole-path steps, per-kernel events on -----------------------------
+    # ---- the timed region: K whole-path steps ---------------------------------------------------
+    # HIP events are recorded on the launch stream around the two kernels whose rooflines are
+    # reported (the main GEMM and score_tokens).  Every event record leaves the stream idle for a
+    # few microseconds, so the other kernels are timed in a second pass of K steps right after.
+    slots = (("score", B.PROF_SCORE), ("partition", B.PROF_PARTITION), ("select", B.PROF_SELECT),
+             ("meta", B.PROF_META), ("shrink", B.PROF_SHRINK), ("main", B.PROF_MAIN))
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.profile_enable(True)
+    B.profile_enable((B.PROF_MAIN, B.PROF_SCORE))
     ms_step, ms_wall = timed(step, args.steps, 0)
-    prof = {name: B.profile_read(slot) for name, slot in
-            (("score", B.PROF_SCORE), ("partition", B.PROF_PARTITION), ("select", B.PROF_SELECT),
-             ("meta", B.PROF_META), ("shrink", B.PROF_SHRINK), ("main", B.PROF_MAIN))}
+    timed_prof = {name: B.profile_read(slot) for name, slot in slots if name in ("main", "score")}
+    B.profile_enable(True)
+    timed(step, args.steps, 0)
+    prof = {name: B.profile_read(slot) for name, slot in slots}
     B.profile_enable(False)
     ms_step = max(ms_step, ms_wall) if ms_step <= 0 else ms_step
     kern_ms = {k: (v[0] / v[1] if v[1] else None) for k, v in prof.items()}
+    breakdown_ms = dict(kern_ms)                      # all six, from the second pass
+    for k, v in timed_prof.items():                   # the roofline kernels: from the timed region
+        if v[1]:
+            kern_ms[k] = v[0] / v[1]
 
     # ---- chunk statistics and algorithmic work --------------------------------------------------
     n_chunks = int(table["chunk_offsets"][-1].item())
@@ -157,6 +167,9 @@ def main():
                    "ladder": wl.ladder, "l_min": wl.l_min, "l_max": wl.l_max, "blend_w": wl.blend_w,
                    "group_rows": args.group_rows, "weights": "prepacked"},
         "kernel_ms": kern_ms,
+        "kernel_ms_note": "main and score: HIP events in the timed region; the rest: a second pass of the same "
+                          "steps with events around every kernel",
+        "kernel_ms_all_events_pass": breakdown_ms,
         "chunks": {"count": n_chunks, "mean_len": float(cl.mean()) if n_chunks else 0.0,
                    "tokens_by_rank": {str(r): int(cl[rk == r].sum()) for r in wl.ladder},
                    "mean_r_eff": float(r_eff.mean())},

@@ -188,9 +188,12 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
 
 /* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel durations from HIP events.
- * cwl_profile_enable(1) creates the events on first use (this is the one place the library
- * creates runtime objects), zeroes the counters and makes every later launch of a tracked kernel
- * record an event pair on its stream; cwl_profile_enable(0) stops that.  cwl_profile_read waits
+ * cwl_profile_enable(slot_mask), bit i standing for slot i, creates the events on first use (this
+ * is the one place the library creates runtime objects), zeroes the counters and makes every
+ * later launch of a kernel whose slot is in the mask record an event pair on its stream (an event
+ * record leaves the stream idle for some microseconds, so enable only what is read);
+ * cwl_profile_enable(0) stops that.  A mask with bits beyond the slots is CWL_ERR_INVALID_ARG.
+ * cwl_profile_read waits
  * for the recorded launches of `slot` (the most recent 256 at most) and returns their summed
  * duration in milliseconds and their count.  Host-side, not thread-safe.
  * ------------------------------------------------------------------------------------------- */
@@ -202,7 +205,7 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
 #define CWL_PROF_MAIN 5       /* main GEMM (x W + uhat B)                                */
 #define CWL_PROF_SLOTS 6
 
-cwl_status cwl_profile_enable(int32_t on);
+cwl_status cwl_profile_enable(int32_t slot_mask);
 cwl_status cwl_profile_read(int32_t slot, double* total_ms /*host*/, int64_t* launches /*host*/);
 
 #ifdef __cplusplus

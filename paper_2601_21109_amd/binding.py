@@ -24,6 +24,7 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
+PROF_SLOTS = 6
 
 
 class ChunkParams(ctypes.Structure):
@@ -293,9 +294,18 @@ def table_from_host(seq_offsets, chunk_offsets, chunk_start, chunk_len, rank_idx
     return up(seq_offsets, np.int32), table, pad(rank_idx, np.int32)
 
 
-def profile_enable(on=True):
-    """Turn per-kernel HIP-event timing on (and reset it) or off."""
-    _check(lib().cwl_profile_enable(1 if on else 0), "cwl_profile_enable")
+def profile_enable(slots=True):
+    """Turn per-kernel HIP-event timing on (and reset it) or off.  ``slots``: True (all), False
+    (off) or an iterable of PROF_* slots to record."""
+    if slots is True:
+        mask = (1 << PROF_SLOTS) - 1
+    elif not slots:
+        mask = 0
+    else:
+        mask = 0
+        for sl in slots:
+            mask |= 1 << int(sl)
+    _check(lib().cwl_profile_enable(mask), "cwl_profile_enable")
 
 
 def profile_read(slot):

@@ -1,5 +1,6 @@
-// Optional per-kernel timing with HIP events, for benchmarks.  Off by default; when on, every
-// launch of a tracked kernel is bracketed by an event pair recorded on the launch stream.
+// Optional per-kernel timing with HIP events, for benchmarks.  Off by default; when a slot is on,
+// every launch of its kernel is bracketed by an event pair recorded on the launch stream.  An event
+// record between two kernels costs idle time on the stream, hence the per-slot mask.
 #include "common.h"
 
 namespace cwl {
@@ -14,18 +15,18 @@ struct Slot {
 };
 
 Slot g_slots[CWL_PROF_SLOTS];
-bool g_on = false;
+uint32_t g_mask = 0;          // bit i: slot i records
 
 }  // namespace
 
 void prof_begin(int slot, hipStream_t st) {
-    if (!g_on) return;
+    if (!(g_mask >> slot & 1u)) return;
     Slot& s = g_slots[slot];
     hipEventRecord(s.start[s.launches % kPairs], st);
 }
 
 void prof_end(int slot, hipStream_t st) {
-    if (!g_on) return;
+    if (!(g_mask >> slot & 1u)) return;
     Slot& s = g_slots[slot];
     hipEventRecord(s.stop[s.launches % kPairs], st);
     s.launches += 1;
@@ -35,21 +36,24 @@ void prof_end(int slot, hipStream_t st) {
 
 using namespace cwl;
 
-extern "C" cwl_status cwl_profile_enable(int32_t on) {
-    if (on) {
+extern "C" cwl_status cwl_profile_enable(int32_t slot_mask) {
+    if (slot_mask < 0 || slot_mask >= (1 << CWL_PROF_SLOTS)) return CWL_ERR_INVALID_ARG;
+    if (slot_mask) {
         for (int i = 0; i < CWL_PROF_SLOTS; ++i) {
             Slot& s = g_slots[i];
             if (!s.made) {
                 for (int p = 0; p < kPairs; ++p) {
-                    if (hipEventCreate(&s.start[p]) != hipSuccess) return CWL_ERR_DEVICE;
-                    if (hipEventCreate(&s.stop[p]) != hipSuccess) return CWL_ERR_DEVICE;
+                    // timing only: without the system-scope fence a recorded event would otherwise
+                    // put between two kernels
+                    if (hipEventCreateWithFlags(&s.start[p], hipEventDisableSystemFence) != hipSuccess) return CWL_ERR_DEVICE;
+                    if (hipEventCreateWithFlags(&s.stop[p], hipEventDisableSystemFence) != hipSuccess) return CWL_ERR_DEVICE;
                 }
                 s.made = true;
             }
             s.launches = 0;
         }
     }
-    g_on = on != 0;
+    g_mask = (uint32_t)slot_mask;
     return CWL_OK;
 }
 
