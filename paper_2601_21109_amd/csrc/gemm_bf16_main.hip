@@ -15,7 +15,7 @@
 //   * Load instructions are never issued as a burst.  The address unit takes one 64-lane
 //     instruction every ~18 cycles and a wave stays in issue until its loads are taken; bursts
 //     after the barrier held the MFMAs back for more than a thousand cycles per stage.  Here
-//     every load sits between MFMAs (one per six), as do the LDS reads (two per MFMA at the
+//     every load sits between MFMAs (one per four), as do the LDS reads (one per MFMA at the
 //     start of a k-step), by way of sched_group_barrier.
 //   * Loads use a scalar base plus a 32-bit lane offset, so the reduction loop advances two
 //     scalar pointers and does no vector address arithmetic.
@@ -233,20 +233,21 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             for (int nb = 0; nb < NB; ++nb)
                 acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[f][nb], af[f][mb], acc[nb][mb], 0, 0, 0);
     };
-    // a k-step: 64 MFMAs, the 16 LDS reads of the next k-step among the first eight, the slot's
-    // eight loads one per six MFMAs after that
+    // a k-step: 64 MFMAs; the 16 LDS reads of the next k-step one per MFMA at the start, then the
+    // slot's eight loads one per four MFMAs (two reads per MFMA measured 5 % slower: with one wave
+    // per SIMD whatever is issued between two MFMAs has to fit into the 16 cycles the first one runs)
     auto order_step = [&]() {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < 16; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 6, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
     auto zero_acc = [&]() {
