@@ -310,15 +310,18 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         for (; s <= plain_end; ++s) stage(false);
         for (; s < S; ++s) stage(true);
 
-        // ---- epilogue through LDS, four passes of 64 rows through buffer pA ----
+        // ---- epilogue through LDS, eight passes of 32 rows through buffer pA ----
         // pA (the weight buffer of the stage just finished) is the one free buffer here: the next
-        // request into it comes with the next stage body.  In pass q every wave hands over its
-        // blocks mb = 2q, 2q+1 (32 rows): image rows 0..31 are tile rows 32q .. 32q+31, image rows
-        // 32..63 are tile rows 128+32q .. (the lower wave row).  Accumulator register v of block
+        // request into it comes with the next stage body.  It is used as two halves of 16 KiB
+        // (32 rows x 512 B) in turn.  In pass q every wave hands over its block row mb = q (16
+        // rows): image rows 0..15 are tile rows 16q .. 16q+15, image rows 16..31 are tile rows
+        // 128+16q .. (the lower wave row); after one barrier each wave stores 8 image rows, two
+        // (2 x 512 B) per instruction, and goes on to write pass q+1 into the other half while
+        // those stores drain.  That barrier also covers the reuse of a half: a wave arrives at it
+        // only after its reads of the pass before have returned.  Accumulator register v of block
         // (nb, mb): column nb*16 + 4*(l/16) + v, row mb*16 + l%16.  A 16-byte chunk c (8 columns)
-        // of image row r is stored at chunk c ^ (r % 16) with its 8-byte halves swapped when bit 4
-        // of r is set: the 16 rows x 2 halves written by 32 lanes of one ds_write_b64 hit every
-        // bank once.  Then each wave stores 16 image rows, two (2 x 512 B) per instruction.
+        // of image row r is stored at chunk c ^ (r % 16): the 16 rows x 2 halves written by 32
+        // lanes of one ds_write_b64 hit every bank once.
         //
         // The accumulators are read with inline assembly (left to itself the compiler copies all
         // 256 out of the AGPRs first, which leaves no vector registers for the fragments that
@@ -336,16 +339,11 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         const int c = le & 31, l16e = le & 15, g4e = le >> 4;
         const int64_t n = n0 + c * 8;                // N is a multiple of 8: a chunk is in or out whole
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (q > 0) {
-                wait_cnt<63, 0>();
-                sync();                               // the previous pass has been read out
-            }
-#pragma unroll
-            for (int m2 = 0; m2 < 2; ++m2) {
-                const int mb = 2 * q + m2;
-                const int r = wm * 32 + m2 * 16 + l16e;
-                char* rowp = img + r * 512 + ((((r >> 4) & 1) ^ (g4e & 1)) << 3);
+        for (int q = 0; q < 8; ++q) {
+            char* half = img + (q & 1) * (SLOT_BYTES / 2);
+            {
+                const int r = wm * 16 + l16e;
+                char* rowp = half + r * 512 + ((g4e & 1) << 3);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     const int ch = wn * (TN / 8) + nb * 2 + (g4e >> 1);
@@ -353,7 +351,7 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
                     asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
                                  "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
                                  : "=v"(x0), "=v"(x1), "=v"(x2), "=v"(x3)
-                                 : "a"(acc[nb][mb][0]), "a"(acc[nb][mb][1]), "a"(acc[nb][mb][2]), "a"(acc[nb][mb][3])
+                                 : "a"(acc[nb][q][0]), "a"(acc[nb][q][1]), "a"(acc[nb][q][2]), "a"(acc[nb][q][3])
                                  : "memory");
                     bf16x4 o;
                     o[0] = (__bf16)x0; o[1] = (__bf16)x1; o[2] = (__bf16)x2; o[3] = (__bf16)x3;
@@ -362,23 +360,17 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             }
             wait_cnt<63, 0>();
             sync();
-            u32x4 v[8];
+            u32x4 v[4];
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {          // all eight reads in flight before the first store
-                const int r = wave * 16 + it * 2 + (le >> 5);            // image row
-                v[it] = *reinterpret_cast<const u32x4*>(img + r * 512 + ((c ^ (r & 15)) << 4));
+            for (int it = 0; it < 4; ++it) {          // all four reads in flight before the first store
+                const int r = wave * 8 + it * 2 + (le >> 5);             // image row
+                v[it] = *reinterpret_cast<const u32x4*>(half + r * 512 + ((c ^ (r & 15)) << 4));
             }
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int r = wave * 16 + it * 2 + (le >> 5);
-                const int64_t g = m0 + (r >> 5) * TM + q * 32 + (r & 31);
-                const bool flip = (r >> 4) & 1;
-                u32x4 o;
-                o[0] = flip ? v[it][2] : v[it][0];
-                o[1] = flip ? v[it][3] : v[it][1];
-                o[2] = flip ? v[it][0] : v[it][2];
-                o[3] = flip ? v[it][1] : v[it][3];
-                if (g < a.M && n < a.N) *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = o;
+            for (int it = 0; it < 4; ++it) {
+                const int r = wave * 8 + it * 2 + (le >> 5);
+                const int64_t g = m0 + (r >> 4) * TM + q * 16 + (r & 15);
+                if (g < a.M && n < a.N) *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = v[it];
             }
         }
         vC += v_step;
