@@ -82,6 +82,18 @@ def test_bf16_shapes(n_seqs, seq_lens, d_in, d_out, ranks, w, group_rows):
     assert rel_err(yh, ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("d_in,ranks", [(64, [8, 16]), (128, [0, 8, 64]), (192, [100]), (320, [8, 16, 32, 64])])
+def test_bf16_more_tiles_than_compute_units(d_in, ranks):
+    """297 output tiles of 256 x 256 (ragged in both directions) with very short reduction loops:
+    persistent workgroups take one or two tiles each and their loaders cross from one tile into the
+    next, and into the rank part, within a few stages."""
+    n, d_out = 2100, 8200
+    rows = np.unique(np.concatenate([np.arange(0, n, 37), np.arange(250, 262), np.arange(n - 70, n)]))
+    yh, ref, _ = run_case(2, [1300, 800], d_in, d_out, ranks, 3, torch.bfloat16, 17, l_min=8, l_max=90,
+                          packed=True, rows=rows)
+    assert rel_err(yh, ref) <= TOL_BF16
+
+
 def test_bf16_grouped_rows_give_identical_output():
     args = (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4, torch.bfloat16, 5)
     _, _, y0 = run_case(*args, group_rows=0, packed=True, l_min=8, l_max=90)
