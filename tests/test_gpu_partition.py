@@ -53,6 +53,10 @@ def run_both(h, seq_lens, l_min, l_max, theta, delta, taus, cap=None):
     ([977] * 300, 16, 40, 32000),
     ([17, 4099, 23], 1, 1, 1024),
     ([4097], 3, 5000, 1024),
+    ([9000, 100, 100, 100], 16, 256, 32000),   # short-sequence path, one sequence beyond its LDS
+    ([20000, 50, 0, 50, 50], 16, 256, 32000),  # long-sequence path with short sequences in the batch
+    ([40000, 300], 64, 2048, 32000),      # longer than the chain walk keeps in LDS
+    ([20000, 9], 16, 15000, 32000),       # reach of a start (l_max) larger than the LDS window
 ])
 def test_partition_matches_oracle(seq_lens, l_min, l_max, vocab):
     lnv = math.log(vocab)
