@@ -8,8 +8,8 @@
 //
 // Data path (gfx950):
 //   * global -> LDS with global_load_lds_dwordx4 (no staging registers) into a ring of NST
-//     stages of BK = 32 (64-byte LDS rows, the 16-byte chunk index XOR-swizzled by (row / 4) % 4
-//     so that ds_read_b128 of 16 consecutive rows touches all 64 banks once).  NST - 1 stages are
+//     stages of BK = 32 or 64 (LDS rows of 64 or 128 bytes, the 16-byte chunk index XOR-swizzled
+//     with the row so that the ds_read_b128 of a fragment touches all 64 banks once).  NST - 1 stages are
 //     in flight while one is consumed: the L2 / fabric latency under load is far longer than one
 //     stage of MFMA work, and a two-stage scheme measured latency-bound.
 //   * LDS -> registers with ds_read_b128, fragments double buffered: the two k-steps of a stage
@@ -26,19 +26,25 @@ namespace {
 
 using namespace mfma;
 
-constexpr int BK = 32;             // elements of K per LDS stage
-constexpr int ROW_BYTES = BK * 2;  // 64
-
-template <int BM, int BN, int WM, int WN, int NST, int EPI>
+// BK = elements of K per LDS stage: 32 (64-byte LDS rows, chunk index XORed with (row / 4) % 4) or
+// 64 (128-byte rows, (row / 2) % 8).  With 64 every load instruction fetches whole 128-byte lines,
+// which is what a kernel that streams its operand once from HBM wants.
+template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) {
+    static_assert(BK == 32 || BK == 64, "stage depth");
+    constexpr int ROW_BYTES = BK * 2;
+    constexpr int CHUNKS = ROW_BYTES / 16;        // 16-byte chunks per LDS row
+    constexpr int RPI = 1024 / ROW_BYTES;         // rows per load instruction
+    constexpr int SW_SHIFT = (BK == 32) ? 2 : 1;  // swizzle = (row >> SW_SHIFT) % CHUNKS
+    constexpr int KSTEPS = BK / 16;               // MFMA k-steps per stage
     constexpr int NW = WM * WN;
     constexpr int TM = BM / WM, TN = BN / WN;     // wave tile
     constexpr int MI = TM / 32, NI = TN / 32;     // 32x32 MFMA blocks per wave tile
     constexpr int ROWS = BM + BN;
-    constexpr int LOADS = ROWS / 16 / NW;         // 1 KiB load instructions per wave per stage
+    constexpr int LOADS = ROWS / RPI / NW;        // 1 KiB load instructions per wave per stage
     constexpr int STAGE_BYTES = ROWS * ROW_BYTES;
     constexpr int N_DS = MI + NI, N_MFMA = MI * NI;
-    static_assert(ROWS % (16 * NW) == 0, "tile rows must split evenly over the waves");
+    static_assert(ROWS % (RPI * NW) == 0 && BM % RPI == 0, "tile rows must split evenly over the waves");
     static_assert(BM % 16 == 0 && BN % 16 == 0 && TM % 32 == 0 && TN % 32 == 0, "tile shape");
     static_assert(BM % kRankBlock == 0, "row tile must cover whole rank blocks");
     static_assert(NST >= 2 && (NST - 1) * LOADS < 64, "ring depth");
@@ -72,7 +78,16 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     for (int ni = 0; ni < NI; ++ni) ni_on[ni] = true;
     int KS = a.K1 / BK;                               // stages of the first part
     if (EPI == EPI_GATE && a.gate_blk_r) {
-        const int32_t r_blk = a.gate_blk_r[m0 / kRankBlock];
+        const int64_t n_blk = (a.M + kRankBlock - 1) / kRankBlock;
+        int32_t r_blk = 0;
+#pragma unroll
+        for (int i = 0; i < BM / kRankBlock; ++i) {
+            const int64_t blk = m0 / kRankBlock + i;
+            if (blk < n_blk) {
+                const int32_t r = a.gate_blk_r[blk];
+                r_blk = r > r_blk ? r : r_blk;
+            }
+        }
 #pragma unroll
         for (int ni = 0; ni < NI; ++ni) ni_on[ni] = (wn * TN + ni * 32) < r_blk;
         if (r_blk == 0) KS = 0;
@@ -81,7 +96,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
                                                       // beyond a row's rank are zero)
     const int S = KS + TS;
 
-    // ---- loader set-up: instruction j of this wave fills rows 16j .. 16j+15 of the stage ----
+    // ---- loader set-up: instruction j of this wave fills rows RPI j .. RPI j + RPI - 1 of the stage ----
     const __bf16* gp[LOADS];          // current global address of this lane's 16 bytes
     int32_t grow[LOADS];              // row in the second operand pair (grouped row / column)
     int lchunk[LOADS];
@@ -89,10 +104,10 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
 #pragma unroll
     for (int i = 0; i < LOADS; ++i) {
         const int j = wave * LOADS + i;
-        const int row_cat = 16 * j + (lane >> 2);
-        is_a[i] = (16 * j) < BM;                      // wave-uniform
+        const int row_cat = RPI * j + lane / CHUNKS;
+        is_a[i] = (RPI * j) < BM;                     // wave-uniform
         const int r = is_a[i] ? row_cat : row_cat - BM;
-        lchunk[i] = (lane & 3) ^ ((r >> 2) & 3);
+        lchunk[i] = (lane % CHUNKS) ^ ((r >> SW_SHIFT) % CHUNKS);
         if (is_a[i]) {
             int64_t g = m0 + r;
             if (g > a.M - 1) g = a.M - 1;
@@ -129,10 +144,10 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
 
     // ---- fragment addressing ----
     const int l32 = lane & 31, h = lane >> 5;
-    const int sw = (l32 >> 2) & 3;
-    int koff[2];
+    const int sw = (l32 >> SW_SHIFT) % CHUNKS;
+    int koff[KSTEPS];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) koff[kk] = ((2 * kk + h) ^ sw) * 16;
+    for (int kk = 0; kk < KSTEPS; ++kk) koff[kk] = ((2 * kk + h) ^ sw) * 16;
     const int a_base = (wm * TM + l32) * ROW_BYTES;
     const int b_base = BM * ROW_BYTES + (wn * TN + l32) * ROW_BYTES;
 
@@ -196,32 +211,41 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     if (S > 0) read_frags(0, 0, 0);
     int buf = 0;
     int s = 0;
+    // A stage is KSTEPS k-steps of 16; fragments alternate between two register sets, the next
+    // k-step's set is fetched while the MFMAs of the current one run.  The stage's one barrier
+    // sits before its last k-step.
     // ---- steady state: stage s releases its buffer to stage s + NST ----
     for (; s + NST < S; ++s) {
         const int nxt = (buf + 1 == NST) ? 0 : buf + 1;
-        read_frags(buf, 1, 1);
-        mfma_step(0);
-        order_first_half();
+#pragma unroll
+        for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
+            read_frags(buf, kk + 1, (kk + 1) & 1);
+            mfma_step(kk & 1);
+            order_first_half();
+        }
         wait_cnt<(NST - 2) * LOADS, 0>();   // my reads of this stage are in registers, my loads of
         stage_barrier();                    // stage s+1 have landed ... and everybody's
         read_frags(nxt, 0, 0);
         issue_next(buf);
-        mfma_step(1);
+        mfma_step((KSTEPS - 1) & 1);
         order_second_half();
         buf = nxt;
     }
     // ---- drain: nothing left to issue ----
     for (; s < S; ++s) {
         const int nxt = (buf + 1 == NST) ? 0 : buf + 1;
-        read_frags(buf, 1, 1);
-        mfma_step(0);
-        order_first_half();
+#pragma unroll
+        for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
+            read_frags(buf, kk + 1, (kk + 1) & 1);
+            mfma_step(kk & 1);
+            order_first_half();
+        }
         if (s + 1 < S) {
             wait_cnt<0, 0>();
             stage_barrier();
             read_frags(nxt, 0, 0);
         }
-        mfma_step(1);
+        mfma_step((KSTEPS - 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
         buf = nxt;
     }
@@ -260,11 +284,12 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NST, int EPI>
+template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
 cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
-    constexpr int smem_bytes = NST * (BM + BN) * ROW_BYTES;
+    constexpr int smem_bytes = NST * (BM + BN) * BK * 2;
     static_assert(smem_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
-    auto kern = gemm_bf16_tn_kernel<BM, BN, WM, WN, NST, EPI>;
+    if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
+    auto kern = gemm_bf16_tn_kernel<BM, BN, WM, WN, NST, EPI, BK>;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -286,13 +311,23 @@ cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
 }  // namespace
 
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
-    // 64-row tiles (one rank block), all padded directions as columns; deep rings because the
-    // shrink streams x once and is bound by memory latency x bytes in flight
+    // 64-row tiles (one rank block), all padded directions as columns.  The shrink streams x once
+    // from HBM: stages of BK = 64 (whole 128-byte lines per load instruction) and rings deep enough
+    // to cover the memory latency with bytes in flight.
+    // Every workgroup re-reads A^T from L2, as many bytes as it reads of x when the tile is 64 x 64;
+    // with enough rows to keep all compute units busy, 128-row tiles halve that.
+    if (a.M >= 128 * 512) {
+        switch (a.N) {
+            case 64: return launch_cfg<128, 64, 2, 2, 5, EPI_GATE, 64>(a, st);
+            case 128: return launch_cfg<128, 128, 2, 2, 4, EPI_GATE, 64>(a, st);
+            default: break;
+        }
+    }
     switch (a.N) {
-        case 64: return launch_cfg<64, 64, 2, 2, 8, EPI_GATE>(a, st);
-        case 128: return launch_cfg<64, 128, 2, 2, 6, EPI_GATE>(a, st);
-        case 192: return launch_cfg<64, 192, 2, 2, 4, EPI_GATE>(a, st);
-        case 256: return launch_cfg<64, 256, 2, 2, 4, EPI_GATE>(a, st);
+        case 64: return launch_cfg<64, 64, 2, 2, 6, EPI_GATE, 64>(a, st);
+        case 128: return launch_cfg<64, 128, 2, 2, 4, EPI_GATE, 64>(a, st);
+        case 192: return launch_cfg<64, 192, 2, 2, 4, EPI_GATE, 64>(a, st);
+        case 256: return launch_cfg<64, 256, 2, 2, 3, EPI_GATE, 64>(a, st);
         default: return CWL_ERR_UNSUPPORTED;
     }
 }
