@@ -384,10 +384,12 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
 }  // namespace
 
 cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
-    if (a_in.perm) return launch_main_bf16_general(a_in, st);
     GemmArgs a = a_in;
+    // gathered rows, and leading dimensions whose 256-row offsets do not fit 32 bits, take the
+    // general kernel (64-bit lane addresses)
+    if (a.perm || a.lda1 > kMaxLd || a.ldb1 > kMaxLd || a.lda2 > kMaxLd || a.ldb2 > kMaxLd)
+        return launch_main_bf16_general(a_in, st);
     if (a.K1 < BK || a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
-    if (a.lda1 > kMaxLd || a.ldb1 > kMaxLd || a.lda2 > kMaxLd || a.ldb2 > kMaxLd) return CWL_ERR_UNSUPPORTED;
     static bool attr_set = false;
     if (!attr_set) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(main_bf16_kernel),
