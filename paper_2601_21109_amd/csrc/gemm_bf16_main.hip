@@ -1,5 +1,5 @@
 // Main bf16 product of cwl_chunkwise_lora_linear: y = [x | uhat] . [W^T | B^T]^T (see
-// linear_common.h for the formulation), one 256 x 256 output tile per workgroup of 4 waves.
+// linear_common.h for the formulation), 256 x 256 output tiles, persistent workgroups of 4 waves.
 //
 // Design (gfx950), with the measurements that led to it:
 //   * Four waves, one per SIMD, each owning a 128 x 128 quarter of the tile: a k-step of 32 needs
@@ -12,6 +12,8 @@
 //     compute unit's LDS): two are being consumed, three are in flight.  After the barrier that
 //     retires stage s the two buffers it held take the weight half of stage s+2 and then the x
 //     half of stage s+3.
+//   * One workgroup per compute unit walks its tiles (XCD-aware order) and the ring keeps running
+//     across tile boundaries: when a tile's epilogue ends, the next tile's first stage is in LDS.
 //   * Load instructions are never issued as a burst.  The address unit takes one 64-lane
 //     instruction every ~18 cycles and a wave stays in issue until its loads are taken; bursts
 //     after the barrier held the MFMAs back for more than a thousand cycles per stage.  Here
@@ -23,8 +25,10 @@
 //     of a fragment (16 rows x 4 chunks) is conflict-free.
 //   * One workgroup barrier per stage, between its two k-steps; fragments are double buffered
 //     in registers across k-steps.
-//   * Epilogue through LDS: the tile is written as bf16 into a 256 x 512 B image and read back
-//     row-wise, so each global store instruction writes two whole 512-byte row segments.
+//   * Epilogue through LDS: the tile goes as bf16 through an image of 512-byte rows and is read back
+//     row-wise, so each global store instruction writes two whole 512-byte row segments (written
+//     straight from the MFMA layout a store covers 8-byte pieces of 16 rows).  The one slot that is
+//     free at a tile boundary is used as two halves in turn, 32 rows per pass.
 //   * The second reduction part (uhat . B^T) walks only ceil(r_tile / 64) stages, r_tile = largest
 //     effective rank among the tile's rows; uhat is zero beyond a row's own rank.
 // Rows gathered through a permutation (rank grouping) are served by the general kernel in
@@ -47,7 +51,6 @@ constexpr int NSLOT = 5;
 constexpr int LPW = 8;                              // load instructions per wave per slot
 constexpr int SMEM_BYTES = NSLOT * SLOT_BYTES;
 constexpr int64_t kMaxLd = (int64_t)1 << 22;        // keeps 256 rows x ld x 2 bytes inside 32 bits
-static_assert(BM * BN * 2 <= SMEM_BYTES, "the output image reuses the ring");
 
 // Virtual workgroup v -> (row tile, column tile), the XCD-aware order of mfma::tile_coords with
 // the index passed in: a persistent workgroup b walks v = b, b + gridDim.x, ... and so stays in
