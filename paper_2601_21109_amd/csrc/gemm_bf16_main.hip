@@ -25,14 +25,17 @@
 //     of a fragment (16 rows x 4 chunks) is conflict-free.
 //   * One workgroup barrier per stage, between its two k-steps; fragments are double buffered
 //     in registers across k-steps.
-//   * Epilogue through LDS: the tile goes as bf16 through an image of 512-byte rows and is read back
-//     row-wise, so each global store instruction writes two whole 512-byte row segments (written
-//     straight from the MFMA layout a store covers 8-byte pieces of 16 rows).  The one slot that is
-//     free at a tile boundary is used as two halves in turn, 32 rows per pass.
+//   * Epilogue through LDS without a barrier: every wave turns its own quarter, 16 rows at a time,
+//     into 256-byte row segments through the 8 KiB of the free slot that it fills itself as a
+//     loader, so each global store writes four whole segments with consecutive lanes on
+//     consecutive addresses (the store unit takes 52 B per cycle that way, 16 B per cycle when the
+//     lanes of a segment are 16 apart as in the MFMA layout), and no 64-bit multiply per store.
 //   * The second reduction part (uhat . B^T) walks only ceil(r_tile / 64) stages, r_tile = largest
 //     effective rank among the tile's rows; uhat is zero beyond a row's own rank.
 // Rows gathered through a permutation (rank grouping) are served by the general kernel in
 // gemm_bf16.hip instead: its loaders keep 64-bit lane addresses.
+#include <type_traits>
+
 #include "mfma_util.h"
 
 namespace cwl {
@@ -313,18 +316,24 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         for (; s <= plain_end; ++s) stage(false);
         for (; s < S; ++s) stage(true);
 
-        // ---- epilogue through LDS, eight passes of 32 rows through buffer pA ----
-        // pA (the weight buffer of the stage just finished) is the one free buffer here: the next
-        // request into it comes with the next stage body.  It is used as two halves of 16 KiB
-        // (32 rows x 512 B) in turn.  In pass q every wave hands over its block row mb = q (16
-        // rows): image rows 0..15 are tile rows 16q .. 16q+15, image rows 16..31 are tile rows
-        // 128+16q .. (the lower wave row); after one barrier each wave stores 8 image rows, two
-        // (2 x 512 B) per instruction, and goes on to write pass q+1 into the other half while
-        // those stores drain.  That barrier also covers the reuse of a half: a wave arrives at it
-        // only after its reads of the pass before have returned.  Accumulator register v of block
-        // (nb, mb): column nb*16 + 4*(l/16) + v, row mb*16 + l%16.  A 16-byte chunk c (8 columns)
-        // of image row r is stored at chunk c ^ (r % 16): the 16 rows x 2 halves written by 32
-        // lanes of one ds_write_b64 hit every bank once.
+        // ---- epilogue: every wave stages its own quarter through its own 8 KiB of buffer pA ----
+        // pA (the weight buffer of the stage just finished) is the one free buffer here: every wave
+        // finished reading it before the barrier of that stage, and the next request into it comes
+        // with the next stage body, where wave w fills bytes [8192 w, 8192 w + 8192) -- the same
+        // 8 KiB it stages through here.  So the epilogue needs no barrier at either end, and the
+        // waves drift apart over it (they meet again at the barrier of the next stage).
+        //
+        // The 8 KiB are two images of 16 rows x 256 B (one block row of the wave's 128 columns as
+        // bf16).  Block row q is written from the MFMA layout (accumulator register v of block
+        // (nb, q): column nb*16 + 4*(l/16) + v, row l%16) with ds_write_b64 and read back row-wise
+        // with ds_read_b128, so a global store covers four whole 256-byte row segments with
+        // consecutive lanes on consecutive addresses (stored straight from the MFMA layout the
+        // lanes of a 64-byte piece are 16 apart and the store unit takes them one lane at a time:
+        // 16 B per cycle against 52).  The LDS unit executes one wave's instructions in order, so
+        // block row q+2 is written into the image block row q was just read from without a wait
+        // between them; only the read data is waited for.  A 16-byte chunk c of image row r sits
+        // at chunk c ^ r: the 16 rows x 2 halves written by 32 lanes of a ds_write_b64 hit every
+        // bank once.
         //
         // The accumulators are read with inline assembly (left to itself the compiler copies all
         // 256 out of the AGPRs first, which leaves no vector registers for the fragments that
@@ -336,20 +345,16 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         asm volatile("s_nop 15");
         asm volatile("s_nop 15");
         __builtin_amdgcn_sched_barrier(0);
-        char* img = smem + pA * SLOT_BYTES;
-        int le = lane;
-        asm volatile("" : "+v"(le));
-        const int c = le & 31, l16e = le & 15, g4e = le >> 4;
-        const int64_t n = n0 + c * 8;                // N is a multiple of 8: a chunk is in or out whole
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            char* half = img + (q & 1) * (SLOT_BYTES / 2);
-            {
-                const int r = wm * 16 + l16e;
-                char* rowp = half + r * 512 + ((g4e & 1) << 3);
+        {
+            int le = lane;
+            asm volatile("" : "+v"(le));
+            const int l16e = le & 15, g4e = le >> 4;
+            char* stg = smem + pA * SLOT_BYTES + wave * 8192;
+            auto put = [&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                char* rowp = stg + (q & 1) * 4096 + l16e * 256 + ((g4e & 1) << 3);
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    const int ch = wn * (TN / 8) + nb * 2 + (g4e >> 1);
                     float x0, x1, x2, x3;
                     asm volatile("v_accvgpr_read_b32 %0, %4\n\tv_accvgpr_read_b32 %1, %5\n\t"
                                  "v_accvgpr_read_b32 %2, %6\n\tv_accvgpr_read_b32 %3, %7"
@@ -358,28 +363,42 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
                                  : "memory");
                     bf16x4 o;
                     o[0] = (__bf16)x0; o[1] = (__bf16)x1; o[2] = (__bf16)x2; o[3] = (__bf16)x3;
-                    *reinterpret_cast<bf16x4*>(rowp + ((ch ^ (r & 15)) << 4)) = o;
+                    *reinterpret_cast<bf16x4*>(rowp + (((nb * 2 + (g4e >> 1)) ^ l16e) << 4)) = o;
                 }
-            }
-            wait_cnt<63, 0>();
-            sync();
-            u32x4 v[4];
+            };
+            // read side: an instruction covers image rows 4 it + l/16, lane l%16 takes chunk l%16
+            const int cch = le & 15, rsub = le >> 4;
+            const int64_t n = n0 + wn * TN + cch * 8;               // N is a multiple of 8: a chunk is in or out whole
+            const int64_t grow0 = m0 + wm * TM + rsub;              // row of (q = 0, it = 0)
+            const int64_t left64 = a.M - grow0;
+            const int rows_left = left64 > BM ? BM : (int)left64;
+            const bool col_ok = n < a.N;
+            char* cp = reinterpret_cast<char*>(static_cast<__bf16*>(a.C) + grow0 * a.ldc + n);
+            const int64_t pitch4 = a.ldc * 8;                       // bytes from row r to row r + 4
+            auto pass = [&](auto qc) {
+                constexpr int q = decltype(qc)::value;
+                u32x4 v[4];
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {          // all four reads in flight before the first store
-                const int r = wave * 8 + it * 2 + (le >> 5);             // image row
-                v[it] = *reinterpret_cast<const u32x4*>(half + r * 512 + ((c ^ (r & 15)) << 4));
-            }
+                for (int it = 0; it < 4; ++it) {
+                    const int r = it * 4 + rsub;
+                    v[it] = *reinterpret_cast<const u32x4*>(stg + (q & 1) * 4096 + r * 256 + ((cch ^ r) << 4));
+                }
+                if constexpr (q + 2 < MB) put(std::integral_constant<int, q + 2>{});
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int r = wave * 8 + it * 2 + (le >> 5);
-                const int64_t g = m0 + (r >> 4) * TM + q * 16 + (r & 15);
-                if (g < a.M && n < a.N) *reinterpret_cast<u32x4*>(static_cast<__bf16*>(a.C) + g * a.ldc + n) = v[it];
-            }
+                for (int it = 0; it < 4; ++it) {
+                    if (col_ok && q * 16 + it * 4 < rows_left) *reinterpret_cast<u32x4*>(cp) = v[it];
+                    cp += pitch4;
+                }
+            };
+            put(std::integral_constant<int, 0>{});
+            put(std::integral_constant<int, 1>{});
+            pass(std::integral_constant<int, 0>{}); pass(std::integral_constant<int, 1>{});
+            pass(std::integral_constant<int, 2>{}); pass(std::integral_constant<int, 3>{});
+            pass(std::integral_constant<int, 4>{}); pass(std::integral_constant<int, 5>{});
+            pass(std::integral_constant<int, 6>{}); pass(std::integral_constant<int, 7>{});
         }
         vC += v_step;
         if (!tile_of(vC, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn)) break;
-        wait_cnt<63, 0>();
-        sync();                                       // pA may be written by the next request
     }
     wait_cnt<0, 0>();                                 // nothing of this wave's is still on its way into LDS
 }
