@@ -20,17 +20,21 @@
 //   * one workgroup barrier per stage, placed between the two k-steps: by then this wave's
 //     fragment reads of the stage are in registers and its loads of the next stage have landed.
 #include "mfma_util.h"
+#include "token_meta.h"
 
 namespace cwl {
 namespace {
 
 using namespace mfma;
 
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
 // BK = elements of K per LDS stage: 32 (64-byte LDS rows, chunk index XORed with (row / 4) % 4) or
 // 64 (128-byte rows, (row / 2) % 8).  With 64 every load instruction fetches whole 128-byte lines,
 // which is what a kernel that streams its operand once from HBM wants.
+// (vid: workgroup index of the GEMM proper; a launch may carry other workgroups in front)
 template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
-__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) {
+__device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int vid) {
     static_assert(BK == 32 || BK == 64, "stage depth");
     constexpr int ROW_BYTES = BK * 2;
     constexpr int CHUNKS = ROW_BYTES / 16;        // 16-byte chunks per LDS row
@@ -52,7 +56,18 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     int bm, bn;
-    if (!tile_coords(a.tiles_m, a.tiles_n, &bm, &bn)) return;
+    int split = 0;
+    if (EPI == EPI_PARTIAL) {
+        // few row tiles, the splits of a tile on consecutive workgroup ids (with 8 splits, split s
+        // always runs on XCD s and the x slice it reads stays in that L2)
+        const int tile = vid / a.splits;
+        split = vid % a.splits;
+        if (tile >= a.tiles_m * a.tiles_n) return;
+        bm = tile % a.tiles_m;
+        bn = tile / a.tiles_m;
+    } else if (!tile_coords(a.tiles_m, a.tiles_n, &bm, &bn)) {
+        return;
+    }
     const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // scalar: stage addresses stay in SGPRs
@@ -92,6 +107,13 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
         for (int ni = 0; ni < NI; ++ni) ni_on[ni] = (wn * TN + ni * 32) < r_blk;
         if (r_blk == 0) KS = 0;
     }
+    int k_first = 0;                                  // first stage of this workgroup's slice
+    if (EPI == EPI_PARTIAL) {
+        k_first = split * a.ks_per_split;
+        int k_end = k_first + a.ks_per_split;
+        if (k_end > KS) k_end = KS;
+        KS = k_end > k_first ? k_end - k_first : 0;
+    }
     const int TS = (r_tile + BK - 1) / BK;            // stages of the second part (uhat columns
                                                       // beyond a row's rank are zero)
     const int S = KS + TS;
@@ -113,12 +135,12 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
             if (g > a.M - 1) g = a.M - 1;
             grow[i] = (int32_t)g;
             const int64_t t = a.perm ? (int64_t)a.perm[g] : g;
-            gp[i] = static_cast<const __bf16*>(a.A1) + t * a.lda1 + lchunk[i] * 8;
+            gp[i] = static_cast<const __bf16*>(a.A1) + t * a.lda1 + lchunk[i] * 8 + (int64_t)k_first * BK;
         } else {
             int64_t n = n0 + r;
             if (n > a.N - 1) n = a.N - 1;
             grow[i] = (int32_t)n;
-            gp[i] = static_cast<const __bf16*>(a.B1) + n * a.ldb1 + lchunk[i] * 8;
+            gp[i] = static_cast<const __bf16*>(a.B1) + n * a.ldb1 + lchunk[i] * 8 + (int64_t)k_first * BK;
         }
     }
     int issued = 0;                   // stages issued so far (wave-uniform)
@@ -257,6 +279,21 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     for (int mi = 0; mi < MI; ++mi) {
         const int64_t g = m0 + wm * TM + mi * 32 + l32;
         if (g >= a.M) continue;
+        if (EPI == EPI_PARTIAL) {
+            float* prow = a.partial + split * a.partial_stride + g * a.ldp;
+#pragma unroll
+            for (int ni = 0; ni < NI; ++ni)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int64_t n = n0 + wn * TN + ni * 32 + q * 8 + h * 4;
+                    if (n >= a.N) continue;
+                    f32x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = acc[ni][mi][q * 4 + e];
+                    *reinterpret_cast<f32x4*>(prow + n) = o;
+                }
+            continue;
+        }
         const int64_t t = a.perm ? (int64_t)a.perm[g] : g;
         TokMeta mt = {0, 0, 0.0f, 0.0f};
         if (EPI == EPI_GATE) mt = a.meta[t];
@@ -282,6 +319,54 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
             }
         }
     }
+}
+
+template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
+__global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) {
+    gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI, BK>(a, (int)blockIdx.x);
+}
+
+// Split-reduction launch for a few rows: workgroup 0 fills the rows' gate table (the chain of
+// dependent lookups takes as long as the products themselves and runs beside them), workgroups
+// 1.. compute the partial products.
+template <int BM, int BN, int WM, int WN, int NST>
+__global__ void __launch_bounds__(WM * WN * 64) partial_bf16_kernel(GemmArgs a, MetaJob job) {
+    if (blockIdx.x == 0) {
+        __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
+        __shared__ float lad_scales[CWL_MAX_LADDER];
+        ladder_to_lds(job.lad, lad_ranks, lad_scales);
+        __syncthreads();
+        for (int64_t t = threadIdx.x; t < a.M; t += WM * WN * 64)
+            job.meta[t] = token_meta_of(t, job.seq_offsets, job.n_seqs, job.chunk_offsets, job.chunk_start,
+                                        job.chunk_len, job.rank_idx, job.chunk_cap, job.lad.K, lad_ranks,
+                                        lad_scales, job.blend_w);
+        return;
+    }
+    gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI_PARTIAL, 64>(a, (int)blockIdx.x - 1);
+}
+
+template <int BM, int BN, int WM, int WN, int NST>
+cwl_status launch_partial_cfg(GemmArgs a, const MetaJob& job, hipStream_t st) {
+    constexpr int BK = 64;
+    constexpr int smem_bytes = NST * (BM + BN) * BK * 2;
+    static_assert(smem_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+    if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
+    if (a.splits < 1 || a.ks_per_split < 1 || !a.partial || !job.meta) return CWL_ERR_INVALID_ARG;
+    auto kern = partial_bf16_kernel<BM, BN, WM, WN, NST>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes) != hipSuccess)
+            return CWL_ERR_DEVICE;
+        attr_set = true;
+    }
+    a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
+    a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
+    const int64_t grid = (int64_t)a.tiles_m * a.tiles_n * a.splits + 1;
+    if (grid >= (int64_t)1 << 31) return CWL_ERR_UNSUPPORTED;
+    kern<<<dim3((unsigned)grid), dim3(WM * WN * 64), smem_bytes, st>>>(a, job);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
 }
 
 template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
@@ -332,9 +417,25 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
     }
 }
 
+// fp32 partial products over slices of the reduction dimension, for a few hundred rows: tiles of 64
+// columns, rings shallow enough for two workgroups per compute unit (the launch is bound by how
+// many bytes of the weight matrix are in flight).
+cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st) {
+    if (a.M <= 64) return launch_partial_cfg<64, 64, 2, 2, 4>(a, job, st);
+    if (a.N_tile == 64) return launch_partial_cfg<128, 64, 2, 2, 3>(a, job, st);
+    return launch_partial_cfg<128, 128, 2, 2, 4>(a, job, st);
+}
+
 // Two-part product with 64-bit lane addresses (rows gathered through a.perm).
 cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st) {
     return launch_cfg<256, 256, 2, 4, 4, EPI_STORE>(a, st);
+}
+
+
+// The same with 128 x 128 tiles, four waves and stages of 64: for products with too few 256 x 256
+// tiles to occupy the compute units.
+cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st) {
+    return launch_cfg<128, 128, 2, 2, 4, EPI_STORE, 64>(a, st);
 }
 
 }  // namespace cwl

@@ -423,6 +423,8 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
     const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;
     if (n_tiles <= 0) return CWL_OK;
+    // with tiles for a quarter of the compute units at most, 128 x 128 tiles fill the chip instead
+    if (n_tiles <= 64) return launch_main_bf16_tile128(a_in, st);
     const int64_t n_virtual = (n_tiles + 7) / 8 * 8;       // workgroup slots, 8 XCDs round-robin
     if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
     // persistent: one workgroup per compute unit (160 KiB of LDS each), a multiple of 8 of them

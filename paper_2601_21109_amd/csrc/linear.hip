@@ -2,6 +2,7 @@
 // grouping, weight re-layout).  The GEMMs themselves are in gemm_f32.hip / gemm_bf16.hip; the
 // formulation is described in linear_common.h.  (Sec. III-C / III-D of arxiv 2601.21109.)
 #include "linear_common.h"
+#include "token_meta.h"
 
 namespace cwl {
 namespace {
@@ -21,8 +22,7 @@ __device__ __forceinline__ int bucket_of(int32_t r_eff, const Ladder& lad) {
 
 
 // ------------------------------------------------------------------------------------------
-// Per-token gate table.  Token t -> its sequence (binary search in seq_offsets) -> its chunk
-// (binary search in that sequence's chunk_start range) -> (r_cur, g_cur, r_prev, g_prev).
+// Per-token gate table (token_meta.h has the lookup).
 // A block of 256 threads covers 4 rank blocks of 64 rows; in token order (no grouping) each
 // wavefront also reduces the largest effective rank of its 64 rows into blk_r.
 // ------------------------------------------------------------------------------------------
@@ -35,60 +35,13 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
     // the ladder is indexed by a per-thread rung: keep a copy in LDS
     __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
     __shared__ float lad_scales[CWL_MAX_LADDER];
-    if (threadIdx.x < CWL_MAX_LADDER) {
-        int32_t r = 0;
-        float sc = 0.0f;
-#pragma unroll
-        for (int k = 0; k < CWL_MAX_LADDER; ++k)
-            if (k == (int)threadIdx.x) { r = lad.ranks[k]; sc = lad.scales[k]; }
-        lad_ranks[threadIdx.x] = r;
-        lad_scales[threadIdx.x] = sc;
-    }
+    ladder_to_lds(lad, lad_ranks, lad_scales);
     __syncthreads();
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     TokMeta m = {0, 0, 0.0f, 0.0f};
-    if (t < n_rows && n_seqs > 0) {
-        // sequence: last b with seq_offsets[b] <= t
-        int32_t lo = 0, hi = n_seqs;           // first index in [0, n_seqs] with offset > t
-        while (lo < hi) {
-            const int32_t mid = lo + (hi - lo) / 2;
-            if ((int64_t)seq_offsets[mid] <= t) lo = mid + 1; else hi = mid;
-        }
-        const int32_t b = lo - 1;
-        if (b >= 0 && t < (int64_t)seq_offsets[b + 1]) {
-            int32_t c0 = chunk_offsets[b], c1 = chunk_offsets[b + 1];
-            if (c1 > chunk_cap) c1 = chunk_cap;
-            int32_t l2 = c0, h2 = c1;          // first chunk in [c0, c1) with start > t
-            while (l2 < h2) {
-                const int32_t mid = l2 + (h2 - l2) / 2;
-                if ((int64_t)chunk_start[mid] <= t) l2 = mid + 1; else h2 = mid;
-            }
-            const int32_t c = l2 - 1;
-            if (c >= c0 && c0 >= 0) {
-                const int64_t j = t - chunk_start[c];
-                if (j < chunk_len[c]) {
-                    const int32_t k = rank_idx[c];
-                    const bool k_ok = k >= 0 && k < lad.K;
-                    const int32_t r_cur = k_ok ? lad_ranks[k] : 0;
-                    const float s_cur = (k_ok && r_cur > 0) ? lad_scales[k] : 0.0f;
-                    if (c == c0 || blend_w == 0 || j >= blend_w) {
-                        m.r_cur = r_cur;
-                        m.g_cur = s_cur;
-                    } else {
-                        const int32_t kp = rank_idx[c - 1];
-                        const bool kp_ok = kp >= 0 && kp < lad.K;
-                        const int32_t r_prev = kp_ok ? lad_ranks[kp] : 0;
-                        const float s_prev = (kp_ok && r_prev > 0) ? lad_scales[kp] : 0.0f;
-                        const float lambda = (float)(j + 1) / (float)(blend_w + 1);
-                        m.r_cur = r_cur;
-                        m.g_cur = lambda * s_cur;
-                        m.r_prev = r_prev;
-                        m.g_prev = (1.0f - lambda) * s_prev;
-                    }
-                }
-            }
-        }
-    }
+    if (t < n_rows)
+        m = token_meta_of(t, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                          chunk_cap, lad.K, lad_ranks, lad_scales, blend_w);
     int32_t r_eff = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
     if (t < n_rows) {
         meta[t] = m;
@@ -329,8 +282,14 @@ PackedLayout packed_layout(const cwl_linear_desc* d) {
 }
 
 struct WsLayout {           // byte offsets into the linear workspace
-    size_t meta, blk_r, r_eff, perm, uhat, total;
+    size_t meta, blk_r, r_eff, perm, uhat, partial, total;
 };
+
+// the few-row path: bf16, token order, and the packed W^T and A^T back to back
+bool small_rows_path(const cwl_linear_desc* d, const PackedLayout& P) {
+    return d->dt == CWL_BF16 && d->group_rows == 0 && d->n_rows >= 1 && d->n_rows <= kSmallRows &&
+           P.at == P.wt + sizeof(uint16_t) * (size_t)d->d_out * (size_t)d->d_in;
+}
 
 WsLayout ws_layout(const cwl_linear_desc* d) {
     WsLayout L;
@@ -343,6 +302,8 @@ WsLayout ws_layout(const cwl_linear_desc* d) {
     L.r_eff = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.perm = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
+    L.partial = off;
+    if (small_rows_path(d, packed_layout(d))) off = align_up(off + small_rows_plan(d).partial_bytes, 256);
     L.total = off;
     return L;
 }
@@ -393,6 +354,11 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
                       int32_t chunk_cap, void* y, char* ws, hipStream_t st) {
     const PackedLayout P = packed_layout(d);
     const WsLayout L = ws_layout(d);
+    if (small_rows_path(d, P))
+        return run_small_rows(d, x, packed + P.wt, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
+                              chunk_start, chunk_len, rank_idx, chunk_cap, y,
+                              reinterpret_cast<float*>(ws + L.partial),
+                              reinterpret_cast<TokMeta*>(ws + L.meta), st);
     TokMeta* meta = reinterpret_cast<TokMeta*>(ws + L.meta);
     int32_t* blk_r = reinterpret_cast<int32_t*>(ws + L.blk_r);
     int32_t* r_eff = reinterpret_cast<int32_t*>(ws + L.r_eff);

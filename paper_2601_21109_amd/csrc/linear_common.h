@@ -55,14 +55,49 @@ struct GemmArgs {
     const TokMeta* meta;
     const int32_t* perm;
     int32_t tiles_m, tiles_n;
+    // EPI_PARTIAL (split reduction): workgroup v computes stages [split * ks_per_split, + ks_per_split)
+    // of the first part for tile v / splits, split = v % splits, and leaves its fp32 tile at
+    // partial[split * partial_stride + m * ldp + n]
+    int32_t splits, ks_per_split;
+    float* partial;
+    int64_t ldp, partial_stride;
+    int32_t N_tile;         // EPI_PARTIAL: column tile the plan was made for (64 or 128)
 };
 
 // EPI_STORE: C = result in the launch's element type.  EPI_GATE: C[g, n] = result * G[perm[g], n].
-enum { EPI_STORE = 0, EPI_GATE = 1 };
+// EPI_PARTIAL: fp32 partial sums of a slice of the reduction dimension (see GemmArgs).
+enum { EPI_STORE = 0, EPI_GATE = 1, EPI_PARTIAL = 2 };
 
 cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
 cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st);   // any a.perm
+cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st);   // 128 x 128 tiles
+// the gate table of rows 0 .. M-1, filled by one workgroup of the split-reduction launch
+struct MetaJob {
+    const int32_t* seq_offsets;
+    const int32_t* chunk_offsets;
+    const int32_t* chunk_start;
+    const int32_t* chunk_len;
+    const int32_t* rank_idx;
+    int32_t n_seqs, chunk_cap, blend_w;
+    Ladder lad;
+    TokMeta* meta;
+};
+cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st);   // EPI_PARTIAL
+
+// ---- few rows (linear_small.hip): bf16, packed weights, token order ----
+constexpr int64_t kSmallRows = 512;
+struct SmallPlan {
+    int32_t splits, ks_per_split, n_tile;
+    int64_t ldp, partial_stride;      // elements
+    size_t partial_bytes;
+};
+SmallPlan small_rows_plan(const cwl_linear_desc* d);
+// wt_at: W^T [d_out, d_in] directly followed by A^T [padded rank, d_in]; bt: B^T [d_out, padded rank]
+cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* wt_at, const void* bt,
+                          const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
+                          const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, hipStream_t st);
 
 }  // namespace cwl

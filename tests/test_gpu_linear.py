@@ -94,6 +94,46 @@ def test_bf16_more_tiles_than_compute_units(d_in, ranks):
     assert rel_err(yh, ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [1], 64, 8, [16], 0),                         # one token, one slice
+    (1, [1], 4096, 4096, [8, 16, 32, 64], 4),         # one decode row at the 7B shape
+    (8, [1] * 8, 1024, 1032, [8, 16, 32, 64], 4),     # eight one-token sequences, ragged columns
+    (3, [9, 1, 7], 512, 72, [0, 4, 70], 3),           # 17 rows, joins inside, padded rank 128, rank-0 rung
+    (1, [64], 2048, 264, [8, 64], 2),                 # exactly one row tile of 64
+    (2, [40, 25], 704, 520, [200], 4),                # 65 rows: the 128-row tile; 11 stages over several slices
+    (4, [32, 32, 32, 32], 4096, 328, [8, 16, 32, 64], 4),   # 128 rows
+    (1, [100], 11008, 136, [8, 16, 32, 64], 4),       # long reduction (172 stages)
+    (1, [300], 1024, 520, [8, 16, 32, 64], 4),        # three row tiles of 128, ragged
+    (3, [200, 12, 300], 512, 264, [0, 24, 100], 3),   # 512 rows: the largest case of this path
+])
+@pytest.mark.parametrize("packed", [True, False])
+def test_bf16_few_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
+    """At most 512 rows: the split-reduction path (partial products + fix-up kernel)."""
+    yh, ref, y = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 23, l_min=4, l_max=12,
+                          packed=packed)
+    assert rel_err(yh, ref) <= TOL_BF16
+    _, _, y2 = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 23, l_min=4, l_max=12,
+                        packed=packed)
+    assert torch.equal(y, y2)                         # slice sums in a fixed order
+
+
+def test_bf16_few_rows_agree_with_the_large_path():
+    """Rows 0..511 of a 513-row call (tiled path) against the same rows as a 512-row call."""
+    d_in, d_out, ranks = 1024, 520, [8, 16, 32, 64]
+    scales = [16.0 / r for r in ranks]
+    x, Wm, A, Bm = operands(513, d_in, d_out, 64, torch.bfloat16, 29)
+    pw = B.prepack_weights(Wm, A, Bm)
+    ys = []
+    for n in (513, 512):
+        so, co, cs, cl, ri = W.random_chunk_table(1, [n], 128, 128, len(ranks), 3)
+        ri[:] = np.arange(len(ri)) % len(ranks)
+        sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+        ys.append(B.chunkwise_lora_linear(x[:n], pw, None, None, ranks, scales, 4, sod, tab, rid)[:512].float())
+    torch.cuda.synchronize()
+    # both round uhat and y to bf16 once; the sums run in different orders
+    assert (ys[0] - ys[1]).abs().max().item() <= 2.0 ** -6 * ys[0].abs().max().item()
+
+
 def test_bf16_grouped_rows_give_identical_output():
     args = (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4, torch.bfloat16, 5)
     _, _, y0 = run_case(*args, group_rows=0, packed=True, l_min=8, l_max=90)
