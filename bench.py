@@ -231,6 +231,38 @@ def main():
             "lora_flop_share_at_r_max": wl.r_max * (d_in + d_out) / (d_in * d_out),
         }
 
+    # ---- the same projection on a few rows (decode steps, short prompts): bound by streaming the
+    #      weights once; the two kernels of that path are timed with their event pairs -----------
+    if not args.no_variants and bf16:
+        few = {}
+        R_pad = (max(wl.r_max, 1) + 63) // 64 * 64
+        w_bytes = 2.0 * d_in * (d_out + R_pad)
+        for rows in (1, 64, 512):
+            tb = W.random_chunk_table(1, [rows], min(wl.l_min, rows), max(min(wl.l_max, rows), 1), K, 11)
+            sod_f, tab_f, rid_f = B.table_from_host(*tb, dev)
+            ws_f = B.linear_workspace((rows, d_in), wl.dtype, d_out, wl.r_max, wl.ladder, wl.scales,
+                                      wl.blend_w, dev)
+            y_f = torch.empty((rows, d_out), dtype=wl.dtype, device=dev)
+            fn = lambda: B.chunkwise_lora_linear(x[:rows], packed, None, None, wl.ladder, wl.scales,
+                                                 wl.blend_w, sod_f, tab_f, rid_f, out=y_f, workspace=ws_f)
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            B.profile_enable((B.PROF_MAIN, B.PROF_META))
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            t_p, n_p = B.profile_read(B.PROF_MAIN)
+            t_f, n_f = B.profile_read(B.PROF_META)
+            B.profile_enable(False)
+            if n_p and n_f:
+                us_p, us_f = t_p / n_p * 1e3, t_f / n_f * 1e3
+                few[str(rows)] = {"partial_products_us": us_p, "fixup_us": us_f,
+                                  "weight_stream_GBps": w_bytes / (us_p * 1e-6) / 1e9,
+                                  "frac_of_hbm_peak": w_bytes / (us_p * 1e-6) / 1e9 / PEAK_HBM_GBS}
+        out["few_rows"] = {"note": "rows <= 512 take the split-reduction path; weight bytes = 2 d_in (d_out + R), "
+                                   "rate over the partial-product kernel alone", "weight_bytes": w_bytes, **few}
+
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------------
     if not args.no_cpu_baseline:
         import oracle as O
