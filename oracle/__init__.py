@@ -12,6 +12,9 @@ from .reference import (  # noqa: F401
     partition,
     select,
     linear,
+    StreamState,
+    stream_step,
+    gated_linear,
     num_threads,
     set_num_threads,
     bf16_round,

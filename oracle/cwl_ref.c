@@ -14,6 +14,9 @@
  *     and an average-complexity threshold                                     -> cwl_ref_partition
  *   - Sec. III-C, Sec. IV-C: chunk mean -> rung of the rank ladder            -> cwl_ref_select
  *   - Sec. III-C (sliced ladder), Sec. III-D (linear cross-fade at joins)     -> cwl_ref_linear
+ *   - Sec. III-A/B (signals and grouping computed step by step while decoding), Sec. III-F
+ *     (scheduler state kept between steps): the same rules one token at a time -> cwl_ref_stream_step
+ *   - the layer for rows that bring their own gate (what a decode step feeds) -> cwl_ref_gated_linear
  *
  * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
  * readings taken are written out step by step in the comments of each function.
@@ -118,8 +121,8 @@ void cwl_ref_quantise_rows(const float* h, int64_t n, int32_t* q, int32_t* nan_f
 }
 
 /* ------------------------------------------------------------------------------------------
- * Adaptive chunker (Sec. III-B, Sec. IV-B).  Reading of "grouped online ... subject to length
- * bounds, an average-complexity threshold": a chunk opened at p is extended one token at a time
+ * Adaptive chunker (Sec. III-B, Sec. IV-B: tokens are grouped as they arrive, under length bounds
+ * and a threshold on the average complexity).  Reading: a chunk opened at p is extended one token at a time
  * and is closed at the first end e (chunk = [p, e)) in [p+L_min, p+L_max] at which
  *      hard :  the chunk's mean score has reached theta           S >= theta_q * n
  *      enter:  the token that would come next is itself hard      q[e] >= theta_q
@@ -192,7 +195,7 @@ int cwl_ref_partition(const int32_t* q, const int32_t* seq_offsets, int32_t n_se
 }
 
 /* ------------------------------------------------------------------------------------------
- * Rung selection (Sec. III-C, Sec. IV-C "rule-based percentile mapping"): the caller's K-1
+ * Rung selection (Sec. III-C, Sec. IV-C: a rule that maps percentiles of the score to rungs): the caller's K-1
  * ascending thresholds are the percentile table; the rung is the number of thresholds the
  * chunk's mean score reaches,  k = #{ j : sum >= tau_q[j] * len }.  A mean exactly on a
  * threshold goes up.
@@ -294,5 +297,123 @@ int cwl_ref_linear(const float* x, int64_t ldx, const float* W, int64_t ldw,
     }
     free(tok_chunk);
     free(tok_first);
+    return CWL_REF_OK;
+}
+
+
+/* ------------------------------------------------------------------------------------------
+ * Decode-step form of the chunker, the selector and the cross-fade (Sec. III-A and III-B have the
+ * estimator and the chunker run while decoding, Sec. III-F keeps the scheduler's state between steps).
+ * One call consumes ONE new token per sequence.  Per sequence the cached state is the open
+ * chunk (tokens n, score sum S), the rung in force at the previous token (k_cur), the rung the
+ * previous chunk ended with (k_prev), the number of chunks closed and of tokens seen.
+ *
+ * Reading (the paper gives no online rule): the new token, with score qe, is tested against the
+ * open chunk exactly as the batch chunker tests an end e = (position of the new token): if the
+ * open chunk has n >= L_min tokens and (n == L_max, or hard, or enter, or dev -- the three tests
+ * of cwl_ref_partition on S, n, qe) the chunk is closed in front of the token and the token opens
+ * the next one; otherwise it joins the open chunk.  The end of the sequence is not known, so the
+ * batch rule that keeps a tail of at least L_min has no counterpart here: both forms place the
+ * same boundaries as long as the chunk starts at least L_min + L_max before the end.
+ * The rung in force for a token is the selector's rule on the open chunk as far as it is known,
+ * k = #{ j : S >= tau_q[j] * n } with the token itself included; at the last token of a chunk that
+ * is the rung the batch form gives the whole chunk.  The first w tokens of a chunk that is not the
+ * first of its sequence cross-fade from the rung the previous chunk ended with:
+ *      lambda = (j + 1) / (w + 1),  j = offset of the token in its chunk,
+ *      gate = (r_cur, lambda * s_cur, r_prev, (1 - lambda) * s_prev);   else (r_cur, s_cur, 0, 0).
+ * closed_len / closed_sum report the chunk this token closed (0 when none).
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_stream_step(const int32_t* q_new, int32_t n_seqs, int32_t l_min, int32_t l_max,
+                        int64_t theta_q, int64_t delta_q, const int64_t* tau_q, int32_t K,
+                        const int32_t* ranks, const float* scales, int32_t blend_w,
+                        int32_t* st_n, int64_t* st_sum, int32_t* st_k_cur, int32_t* st_k_prev,
+                        int32_t* st_chunks, int64_t* st_pos,
+                        int32_t* r_cur, double* g_cur, int32_t* r_prev, double* g_prev,
+                        int32_t* closed_len, int64_t* closed_sum) {
+    if (l_min < 1 || l_max < l_min || K < 1 || blend_w < 0) return CWL_REF_ERR_INVALID;
+    if ((int64_t)l_max < 2 * (int64_t)l_min - 1) return CWL_REF_ERR_INFEASIBLE;
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        const int64_t qe = q_new[b];
+        closed_len[b] = 0;
+        closed_sum[b] = 0;
+        if (st_n[b] >= l_min) {
+            const int64_t n = st_n[b], S = st_sum[b];
+            const int hard = S >= theta_q * n;
+            const int enter = qe >= theta_q;
+            int64_t d = qe * n - S;
+            if (d < 0) d = -d;
+            const int dev = d > delta_q * n;
+            if (n == l_max || hard || enter || dev) {
+                closed_len[b] = (int32_t)n;
+                closed_sum[b] = S;
+                st_k_prev[b] = st_k_cur[b];
+                st_chunks[b] += 1;
+                st_n[b] = 0;
+                st_sum[b] = 0;
+            }
+        }
+        st_n[b] += 1;
+        st_sum[b] += qe;
+        st_pos[b] += 1;
+        int32_t k = 0;
+        for (int32_t j = 0; j < K - 1; ++j)
+            if (st_sum[b] >= tau_q[j] * (int64_t)st_n[b]) ++k;
+        st_k_cur[b] = k;
+        const int32_t rc = ranks[k];
+        const double sc = rc > 0 ? (double)scales[k] : 0.0;
+        const int32_t j_off = st_n[b] - 1;
+        if (st_chunks[b] == 0 || blend_w == 0 || j_off >= blend_w) {
+            r_cur[b] = rc;  g_cur[b] = sc;
+            r_prev[b] = 0;  g_prev[b] = 0.0;
+        } else {
+            const int32_t kp = st_k_prev[b];
+            const int32_t rp = ranks[kp];
+            const double sp = rp > 0 ? (double)scales[kp] : 0.0;
+            const double lambda = (double)(j_off + 1) / (double)(blend_w + 1);
+            r_cur[b] = rc;  g_cur[b] = lambda * sc;
+            r_prev[b] = rp; g_prev[b] = (1.0 - lambda) * sp;
+        }
+    }
+    return CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The layer for rows that bring their own gate (Sec. III-C sliced ladder, Sec. III-D cross-fade,
+ * with the weights already decided):
+ *      y_t = x_t W + g_cur(t) * sum_{i < r_cur(t)} (x_t . A[:, i]) B[i, :]
+ *                  + g_prev(t) * sum_{i < r_prev(t)} (x_t . A[:, i]) B[i, :]
+ * y is [n_rows, d_out] in double, not rounded.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_gated_linear(const float* x, int64_t ldx, const float* W, int64_t ldw,
+                         const float* A, int64_t lda, const float* B, int64_t ldb,
+                         int64_t n_rows, int64_t d_in, int64_t d_out, int32_t r_max,
+                         const int32_t* r_cur, const double* g_cur, const int32_t* r_prev,
+                         const double* g_prev, double* y) {
+    if (r_max < 0) return CWL_REF_ERR_INVALID;
+    for (int64_t t = 0; t < n_rows; ++t)
+        if (r_cur[t] < 0 || r_cur[t] > r_max || r_prev[t] < 0 || r_prev[t] > r_max) return CWL_REF_ERR_INVALID;
+#pragma omp parallel
+    {
+        double* u = (double*)malloc((size_t)(r_max > 0 ? r_max : 1) * sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int64_t t = 0; t < n_rows; ++t) {
+            double* yt = y + t * d_out;
+            const float* xt = x + t * ldx;
+            for (int64_t j = 0; j < d_out; ++j) yt[j] = 0.0;
+            for (int64_t k = 0; k < d_in; ++k) {
+                const double xv = (double)xt[k];
+                const float* wrow = W + k * ldw;
+                for (int64_t j = 0; j < d_out; ++j) yt[j] += xv * (double)wrow[j];
+            }
+            for (int32_t i = 0; i < r_max; ++i) {
+                double a = 0.0;
+                for (int64_t k = 0; k < d_in; ++k) a += (double)xt[k] * (double)A[k * lda + i];
+                u[i] = a;
+            }
+            adapter_term(u, B, ldb, d_out, r_cur[t], 1.0, g_cur[t], yt);
+            adapter_term(u, B, ldb, d_out, r_prev[t], 1.0, g_prev[t], yt);
+        }
+        free(u);
+    }
     return CWL_REF_OK;
 }

@@ -50,6 +50,11 @@ def _load():
     lib.cwl_ref_linear.argtypes = [P, i64, P, i64, P, i64, P, i64, i64, i64, i64, i32,
                                    i32, P, P, i32, P, i32, P, P, P, P, P, i64, i32, P]
     lib.cwl_ref_linear.restype = ctypes.c_int
+    lib.cwl_ref_stream_step.argtypes = [P, i32, i32, i32, i64, i64, P, i32, P, P, i32,
+                                        P, P, P, P, P, P, P, P, P, P, P, P]
+    lib.cwl_ref_stream_step.restype = ctypes.c_int
+    lib.cwl_ref_gated_linear.argtypes = [P, i64, P, i64, P, i64, P, i64, i64, i64, i64, i32, P, P, P, P, P]
+    lib.cwl_ref_gated_linear.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -162,6 +167,59 @@ def linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, chunk_offsets, chunk
                                 _ptr(cl), _ptr(ri), rows_ptr, n_sel, 1 if x_compact else 0, _ptr(y))
     if st != OK:
         raise ValueError(f"cwl_ref_linear: status {st}")
+    return y
+
+
+class StreamState:
+    """Cached scheduler state of the decode-step form, one entry per sequence (all zero at start,
+    k_prev = -1)."""
+
+    def __init__(self, n_seqs):
+        self.n = np.zeros(n_seqs, np.int32)
+        self.sum = np.zeros(n_seqs, np.int64)
+        self.k_cur = np.zeros(n_seqs, np.int32)
+        self.k_prev = np.full(n_seqs, -1, np.int32)
+        self.chunks = np.zeros(n_seqs, np.int32)
+        self.pos = np.zeros(n_seqs, np.int64)
+
+
+def stream_step(state, q_new, l_min, l_max, theta_q, delta_q, tau_q, ranks, scales, blend_w):
+    """One decode step: one new quantised score per sequence.  Updates ``state`` in place and returns
+    (status, dict with r_cur, g_cur, r_prev, g_prev, closed_len, closed_sum)."""
+    qn = _arr(q_new, np.int32).ravel()
+    B = qn.shape[0]
+    assert state.n.shape[0] == B
+    tq = _arr(tau_q, np.int64).ravel()
+    rk = _arr(ranks, np.int32).ravel()
+    sc = _arr(scales, np.float32).ravel()
+    assert rk.shape[0] == tq.shape[0] + 1 == sc.shape[0]
+    out = {"r_cur": np.zeros(B, np.int32), "g_cur": np.zeros(B, np.float64),
+           "r_prev": np.zeros(B, np.int32), "g_prev": np.zeros(B, np.float64),
+           "closed_len": np.zeros(B, np.int32), "closed_sum": np.zeros(B, np.int64)}
+    st = _load().cwl_ref_stream_step(_ptr(qn), B, int(l_min), int(l_max), int(theta_q), int(delta_q),
+                                     _ptr(tq), rk.shape[0], _ptr(rk), _ptr(sc), int(blend_w),
+                                     _ptr(state.n), _ptr(state.sum), _ptr(state.k_cur), _ptr(state.k_prev),
+                                     _ptr(state.chunks), _ptr(state.pos),
+                                     _ptr(out["r_cur"]), _ptr(out["g_cur"]), _ptr(out["r_prev"]),
+                                     _ptr(out["g_prev"]), _ptr(out["closed_len"]), _ptr(out["closed_sum"]))
+    return st, out
+
+
+def gated_linear(x, W, A, B, r_cur, g_cur, r_prev, g_prev):
+    """y = x W + g_cur (x A[:, :r_cur]) B[:r_cur] + g_prev (x A[:, :r_prev]) B[:r_prev], per row, float64."""
+    x, W, A, B = (_arr(a, np.float32) for a in (x, W, A, B))
+    n_rows, d_in = x.shape
+    d_out, r_max = W.shape[1], A.shape[1]
+    assert W.shape[0] == d_in and A.shape[0] == d_in and B.shape == (r_max, d_out)
+    rc, rp = _arr(r_cur, np.int32).ravel(), _arr(r_prev, np.int32).ravel()
+    gc, gp = _arr(g_cur, np.float64).ravel(), _arr(g_prev, np.float64).ravel()
+    assert rc.shape[0] == rp.shape[0] == gc.shape[0] == gp.shape[0] == n_rows
+    y = np.empty((n_rows, d_out), dtype=np.float64)
+    st = _load().cwl_ref_gated_linear(_ptr(x), x.shape[1], _ptr(W), W.shape[1], _ptr(A), A.shape[1],
+                                      _ptr(B), B.shape[1], n_rows, d_in, d_out, r_max,
+                                      _ptr(rc), _ptr(gc), _ptr(rp), _ptr(gp), _ptr(y))
+    if st != OK:
+        raise ValueError(f"cwl_ref_gated_linear: status {st}")
     return y
 
 
