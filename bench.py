@@ -260,6 +260,23 @@ def main():
                 few[str(rows)] = {"partial_products_us": us_p, "fixup_us": us_f,
                                   "weight_stream_GBps": w_bytes / (us_p * 1e-6) / 1e9,
                                   "frac_of_hbm_peak": w_bytes / (us_p * 1e-6) / 1e9 / PEAK_HBM_GBS}
+        # one decode step of the scheduler for 64 sequences (one thread per sequence: launch latency)
+        st_f = B.stream_state(64, dev)
+        h_f = h[:64].contiguous()
+        so_f = None
+        for _ in range(args.warmup):
+            so_f = B.stream_step(h_f, st_f, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), wl.ladder,
+                                 wl.scales, wl.blend_w, out=so_f)
+        torch.cuda.synchronize()
+        B.profile_enable((B.PROF_PARTITION,))
+        for _ in range(args.steps):
+            B.stream_step(h_f, st_f, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), wl.ladder, wl.scales,
+                          wl.blend_w, out=so_f)
+        torch.cuda.synchronize()
+        t_s, n_s = B.profile_read(B.PROF_PARTITION)
+        B.profile_enable(False)
+        if n_s:
+            few["stream_step_us_64_sequences"] = t_s / n_s * 1e3
         out["few_rows"] = {"note": "rows <= 512 take the split-reduction path; weight bytes = 2 d_in (d_out + R), "
                                    "rate over the partial-product kernel alone", "weight_bytes": w_bytes, **few}
 

@@ -107,8 +107,8 @@ cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows, const int3
                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * cwl_select_ranks -- per-chunk rung of the rank ladder (Sec. III-C; Sec. IV-C, the rule-based
- * percentile mapping): rank_idx[c] = #{ j : chunk_sum[c] >= tau_q[j] * chunk_len[c] }, where
+ * cwl_select_ranks -- per-chunk rung of the rank ladder (Sec. III-C; Sec. IV-C, a rule that maps
+ * score percentiles to rungs): rank_idx[c] = #{ j : chunk_sum[c] >= tau_q[j] * chunk_len[c] }, where
  * tau_q[j] is thresholds[j] quantised like the scores.  A mean exactly on a threshold goes up.
  *
  *   chunk_sum, chunk_len, chunk_offsets   as written by cwl_partition_chunks
@@ -187,6 +187,71 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
                                             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_stream_step -- the chunker, the selector and the cross-fade one token at a time (Sec. III-A
+ * and III-B run the estimator and the chunker while decoding; Sec. III-F keeps the scheduler's state
+ * between steps).  One call consumes ONE new token per sequence: its score, quantised as in
+ * cwl_partition_chunks, is tested against the sequence's open chunk (n tokens, score sum S) exactly
+ * as the batch chunker tests an end in front of that token: if n >= l_min and
+ *      n == l_max,  or  S >= theta_q*n,  or  q >= theta_q,  or  |q*n - S| > delta_q*n
+ * the chunk is closed and the token opens the next one, else the token joins the open chunk.  The
+ * end of the sequence is unknown here, so the batch rule that never leaves a tail shorter than
+ * l_min has no counterpart: both forms place the same boundaries for every chunk that starts at
+ * least l_min + l_max tokens before the end.  The rung in force for the token is the selector's
+ * rule on the open chunk with the token included, k = #{ j : S >= tau_q[j]*n }; at the last token
+ * of a chunk that is the rung cwl_select_ranks gives the whole chunk.  Its gate entry is
+ *      (r_cur, s_cur, 0, 0)                                       first chunk of the sequence,
+ *                                                                 blend_w == 0, or offset j >= blend_w
+ *      (r_cur, l*s_cur, r_prev, (1-l)*s_prev),  l = (j+1)/(blend_w+1)    otherwise,
+ * r_prev / s_prev being those of the rung the previous chunk ended with; a rung of rank 0 has
+ * scale 0.  cwl_gated_lora_linear_packed applies such entries.
+ *
+ *   entropy      [n_seqs] fp32: the score of each sequence's new token (e.g. from cwl_score_tokens)
+ *   p, thresholds, K   as for cwl_partition_chunks / cwl_select_ranks (host)
+ *   ranks, scales      host [K], as in cwl_linear_desc
+ *   state        [n_seqs] in/out; all-zero bytes start a sequence
+ *   gate         [n_seqs] written
+ *   closed_len / closed_sum   [n_seqs] written when not NULL: length and score sum of the chunk
+ *                this token closed, 0 when it closed none
+ *   status_word  one int32, OR-ed with CWL_STATUS_NAN_SCORE when a score is NaN (scored as 0);
+ *                the caller clears it
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int64_t sum;        /* score sum of the open chunk                          */
+    int64_t pos;        /* tokens seen                                           */
+    int32_t n;          /* tokens in the open chunk                              */
+    int32_t n_chunks;   /* chunks closed                                         */
+    int32_t k_cur;      /* rung in force at the latest token                     */
+    int32_t k_prev;     /* rung the previous chunk ended with (once one closed)  */
+} cwl_stream_state;
+
+typedef struct {
+    int32_t r_cur, r_prev;
+    float g_cur, g_prev;
+} cwl_token_gate;
+
+cwl_status cwl_stream_step(const float* entropy, int32_t n_seqs, const cwl_chunk_params* p /*host*/,
+                           const float* thresholds /*host*/, int32_t K, const int32_t* ranks /*host*/,
+                           const float* scales /*host*/, int32_t blend_w, cwl_stream_state* state,
+                           cwl_token_gate* gate, int32_t* closed_len, int64_t* closed_sum,
+                           int32_t* status_word, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_gated_lora_linear_packed -- the layer of cwl_chunkwise_lora_linear for rows that bring their
+ * own gate entry (Sec. III-C sliced ladder, Sec. III-D cross-fade, weights already decided), e.g.
+ * the one token per sequence of a decode step:
+ *      y_t = x_t W + g_cur(t) (x_t . A[:, :r_cur(t)]) . B[:r_cur(t), :]
+ *                  + g_prev(t) (x_t . A[:, :r_prev(t)]) . B[:r_prev(t), :]
+ * Ranks outside [0, r_max] are clipped.  `d`, `packed`, the workspace size and the arithmetic are
+ * those of cwl_chunkwise_lora_linear_packed; ranks, scales, K and blend_w of `d` must be valid
+ * but are not used, group_rows must be 0.
+ *
+ *   gate   [n_rows] device
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x, const void* packed,
+                                        const cwl_token_gate* gate, void* y, void* workspace,
+                                        size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel durations from HIP events.
  * cwl_profile_enable(slot_mask), bit i standing for slot i, creates the events on first use (this
  * is the one place the library creates runtime objects), zeroes the counters and makes every
@@ -198,11 +263,13 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
  * duration in milliseconds and their count.  Host-side, not thread-safe.
  * ------------------------------------------------------------------------------------------- */
 #define CWL_PROF_SCORE 0      /* the entropy kernel of cwl_score_tokens                  */
-#define CWL_PROF_PARTITION 1  /* all kernels of cwl_partition_chunks                     */
+#define CWL_PROF_PARTITION 1  /* all kernels of cwl_partition_chunks; cwl_stream_step     */
 #define CWL_PROF_SELECT 2     /* the kernel of cwl_select_ranks                          */
-#define CWL_PROF_META 3       /* gate table / grouping kernels of the linear             */
+#define CWL_PROF_META 3       /* gate table / grouping kernels of the linear; with at     
+                                 most 512 rows: the fix-up kernel                        */
 #define CWL_PROF_SHRINK 4     /* shrink GEMM (x A, gated)                                */
-#define CWL_PROF_MAIN 5       /* main GEMM (x W + uhat B)                                */
+#define CWL_PROF_MAIN 5       /* main GEMM (x W + uhat B); with at most 512 rows: the     
+                                 partial products x [W | A]                              */
 #define CWL_PROF_SLOTS 6
 
 cwl_status cwl_profile_enable(int32_t slot_mask);

@@ -22,7 +22,8 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
-           "cwl_chunkwise_lora_linear_packed", "cwl_profile_enable", "cwl_profile_read"]
+           "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed",
+           "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
 PROF_SLOTS = 6
 
@@ -77,11 +78,15 @@ def lib():
     L.cwl_prepack_weights.argtypes = [dp, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear.argtypes = [dp, P, P, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
+    fp = ctypes.POINTER(ctypes.c_float)
+    L.cwl_stream_step.argtypes = [P, i32, ctypes.POINTER(ChunkParams), fp, i32, ctypes.POINTER(i32), fp,
+                                  i32, P, P, P, P, P, P]
+    L.cwl_gated_lora_linear_packed.argtypes = [dp, P, P, P, P, P, sz, P]
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     for name in ("cwl_profile_enable", "cwl_profile_read", "cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
                  "cwl_prepack_weights", "cwl_chunkwise_lora_linear",
-                 "cwl_chunkwise_lora_linear_packed"):
+                 "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed"):
         getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
@@ -265,6 +270,64 @@ def chunkwise_lora_linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, table
         _check(L.cwl_chunkwise_lora_linear(d.ref(), _ptr(x), _ptr(W), _ptr(A if r_max else None),
                                            _ptr(B if r_max else None), *common),
                "cwl_chunkwise_lora_linear")
+    return out
+
+
+def stream_state(n_seqs, device):
+    """Zeroed cached scheduler state for `n_seqs` sequences: int64 [n_seqs, 4], one cwl_stream_state
+    per row (sum, pos, n | n_chunks << 32, k_cur | k_prev << 32)."""
+    return torch.zeros((n_seqs, 4), dtype=torch.int64, device=device)
+
+
+def stream_state_fields(state):
+    """Host view of a state tensor as a dict of numpy arrays (sum, pos, n, n_chunks, k_cur, k_prev)."""
+    h = state.cpu().numpy()
+    lo = lambda v: (v & 0xffffffff).astype("int64").astype("int32")
+    hi = lambda v: (v >> 32).astype("int32")
+    return {"sum": h[:, 0].copy(), "pos": h[:, 1].copy(), "n": lo(h[:, 2]), "n_chunks": hi(h[:, 2]),
+            "k_cur": lo(h[:, 3]), "k_prev": hi(h[:, 3])}
+
+
+def stream_step(entropy, state, l_min, l_max, theta_hard, delta_dev, thresholds, ranks, scales, blend_w,
+                out=None):
+    """One decode step of the chunker / selector / cross-fade: entropy [B] fp32 (one new token per
+    sequence), state from stream_state (updated in place).  Returns a dict of device tensors: gate
+    (int32 [B, 4]: r_cur, r_prev and the bit patterns of the fp32 g_cur, g_prev), closed_len,
+    closed_sum, status_word (OR-ed into; zeroed when this call allocates it)."""
+    assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
+    assert state.is_cuda and state.dtype == torch.int64 and state.is_contiguous()
+    B, dev, K = entropy.numel(), entropy.device, len(ranks)
+    assert state.shape == (B, 4)
+    if out is None:
+        out = {"gate": torch.empty((B, 4), dtype=torch.int32, device=dev),
+               "closed_len": torch.empty(B, dtype=torch.int32, device=dev),
+               "closed_sum": torch.empty(B, dtype=torch.int64, device=dev),
+               "status_word": torch.zeros(1, dtype=torch.int32, device=dev)}
+    p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
+    th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
+    rk = (ctypes.c_int32 * max(K, 1))(*[int(r) for r in ranks])
+    sc = (ctypes.c_float * max(K, 1))(*[float(v) for v in scales])
+    _check(lib().cwl_stream_step(_ptr(entropy), B, ctypes.byref(p), th, K, rk, sc, int(blend_w),
+                                 _ptr(state), _ptr(out["gate"]), _ptr(out["closed_len"]),
+                                 _ptr(out["closed_sum"]), _ptr(out["status_word"]), _stream()),
+           "cwl_stream_step")
+    return out
+
+
+def gated_lora_linear(x, packed, gate, ranks, scales, out=None, workspace=None):
+    """y = x W + per-row gated adapter terms; `gate` is int32 [n_rows, 4] as written by stream_step,
+    `packed` a PackedWeights.  ranks / scales only fill the descriptor."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(packed, PackedWeights)
+    assert gate.is_cuda and gate.dtype == torch.int32 and gate.is_contiguous() and gate.shape == (x.shape[0], 4)
+    n_rows = x.shape[0]
+    if out is None:
+        out = torch.empty((n_rows, packed.d_out), dtype=x.dtype, device=x.device)
+    d = _desc_for(x, packed.d_out, packed.r_max, ranks, scales, 0, out)
+    need = lib().cwl_linear_packed_workspace_bytes(d.ref()) or 256
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    _check(lib().cwl_gated_lora_linear_packed(d.ref(), _ptr(x), _ptr(packed.blob), _ptr(gate), _ptr(out),
+                                              _ptr(ws), ws.numel(), _stream()),
+           "cwl_gated_lora_linear_packed")
     return out
 
 

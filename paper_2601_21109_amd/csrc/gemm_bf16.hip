@@ -332,6 +332,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
 template <int BM, int BN, int WM, int WN, int NST>
 __global__ void __launch_bounds__(WM * WN * 64) partial_bf16_kernel(GemmArgs a, MetaJob job) {
     if (blockIdx.x == 0) {
+        if (!job.meta) return;                       // the caller brought the gate entries
         __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
         __shared__ float lad_scales[CWL_MAX_LADDER];
         ladder_to_lds(job.lad, lad_ranks, lad_scales);
@@ -351,7 +352,7 @@ cwl_status launch_partial_cfg(GemmArgs a, const MetaJob& job, hipStream_t st) {
     constexpr int smem_bytes = NST * (BM + BN) * BK * 2;
     static_assert(smem_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
     if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
-    if (a.splits < 1 || a.ks_per_split < 1 || !a.partial || !job.meta) return CWL_ERR_INVALID_ARG;
+    if (a.splits < 1 || a.ks_per_split < 1 || !a.partial) return CWL_ERR_INVALID_ARG;
     auto kern = partial_bf16_kernel<BM, BN, WM, WN, NST>;
     static bool attr_set = false;
     if (!attr_set) {

@@ -225,6 +225,27 @@ block_rank_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32
     if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r;
 }
 
+// largest effective rank per block of 64 rows, from gate entries the caller supplies (ranks
+// clipped to [0, r_max]: the table bounds how far the reduction loops walk)
+__global__ void __launch_bounds__(256)
+block_rank_from_gate_kernel(int64_t n_rows, const TokMeta* __restrict__ gate, int32_t r_max,
+                            int32_t* __restrict__ blk_r) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int32_t r = 0;
+    if (t < n_rows) {
+        const TokMeta m = gate[t];
+        r = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
+        r = r < 0 ? 0 : (r > r_max ? r_max : r);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const int32_t o = __shfl_xor(r, off);
+        r = o > r ? o : r;
+    }
+    const int64_t blk = t / kRankBlock;
+    if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r;
+}
+
 // ------------------------------------------------------------------------------------------
 // Weight re-layout: dst[c, r] = src[r, c] (zero where the source has no element), so that every
 // GEMM operand is contiguous along the reduction dimension.
@@ -348,18 +369,20 @@ cwl_status prepack_typed(const cwl_linear_desc* d, const PackedLayout& L, const 
     return transpose_pad<T>(B, d->r_max, d->d_out, d->ldb, packed + L.bt, d->d_out, L.R, st);
 }
 
+// `gate`: per-row gate entries supplied by the caller (then the chunk table is not looked at), or
+// NULL: the entries are derived from the chunk table
 cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packed,
                       const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                       const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
-                      int32_t chunk_cap, void* y, char* ws, hipStream_t st) {
+                      int32_t chunk_cap, const TokMeta* gate, void* y, char* ws, hipStream_t st) {
     const PackedLayout P = packed_layout(d);
     const WsLayout L = ws_layout(d);
     if (small_rows_path(d, P))
         return run_small_rows(d, x, packed + P.wt, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
                               chunk_start, chunk_len, rank_idx, chunk_cap, y,
                               reinterpret_cast<float*>(ws + L.partial),
-                              reinterpret_cast<TokMeta*>(ws + L.meta), st);
-    TokMeta* meta = reinterpret_cast<TokMeta*>(ws + L.meta);
+                              reinterpret_cast<TokMeta*>(ws + L.meta), gate, st);
+    const TokMeta* meta = gate ? gate : reinterpret_cast<TokMeta*>(ws + L.meta);
     int32_t* blk_r = reinterpret_cast<int32_t*>(ws + L.blk_r);
     int32_t* r_eff = reinterpret_cast<int32_t*>(ws + L.r_eff);
     int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
@@ -374,9 +397,13 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     const bool grouped = d->group_rows == 1;
     const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
     prof_begin(CWL_PROF_META, st);
-    token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
-        d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
-        lad, d->blend_w, meta, grouped ? nullptr : blk_r, grouped ? r_eff : nullptr);
+    if (gate)
+        block_rank_from_gate_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, gate, d->r_max, blk_r);
+    else
+        token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
+            d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
+            lad, d->blend_w, reinterpret_cast<TokMeta*>(ws + L.meta), grouped ? nullptr : blk_r,
+            grouped ? r_eff : nullptr);
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (grouped) {
         group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, perm);
@@ -487,8 +514,8 @@ extern "C" cwl_status cwl_chunkwise_lora_linear_packed(
     if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
     if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
     return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
-                      chunk_start, chunk_len, rank_idx, chunk_cap, y, static_cast<char*>(workspace),
-                      static_cast<hipStream_t>(stream));
+                      chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y,
+                      static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 extern "C" cwl_status cwl_chunkwise_lora_linear(
@@ -516,7 +543,27 @@ extern "C" cwl_status cwl_chunkwise_lora_linear(
                          : prepack_typed<uint16_t>(d, L, W, A, B, packed, st);
     if (s != CWL_OK) return s;
     return run_packed(d, x, packed, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len,
-                      rank_idx, chunk_cap, y, ws, st);
+                      rank_idx, chunk_cap, nullptr, y, ws, st);
+}
+
+extern "C" cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x,
+                                                   const void* packed, const cwl_token_gate* gate,
+                                                   void* y, void* workspace, size_t workspace_bytes,
+                                                   void* stream) {
+    static_assert(sizeof(cwl_token_gate) == sizeof(TokMeta), "a gate entry is a TokMeta");
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
+    s = check_call(d, x, nullptr, 0, nullptr, nullptr, nullptr, nullptr, 0, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed || !gate) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(gate) % 16)
+        return CWL_ERR_INVALID_ARG;
+    if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
+    return run_packed(d, x, static_cast<const char*>(packed), nullptr, 0, nullptr, nullptr, nullptr,
+                      nullptr, 0, reinterpret_cast<const TokMeta*>(gate), y,
+                      static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 extern "C" const char* cwl_status_string(cwl_status s) {

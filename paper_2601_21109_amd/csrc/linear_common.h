@@ -82,7 +82,7 @@ struct MetaJob {
     const int32_t* rank_idx;
     int32_t n_seqs, chunk_cap, blend_w;
     Ladder lad;
-    TokMeta* meta;
+    TokMeta* meta;           // NULL: nothing to fill
 };
 cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st);   // EPI_PARTIAL
 
@@ -98,6 +98,7 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d);
 cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* wt_at, const void* bt,
                           const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                           const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
-                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, hipStream_t st);
+                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, const TokMeta* gate,
+                          hipStream_t st);   // gate != NULL: use these entries, leave the chunk table alone
 
 }  // namespace cwl

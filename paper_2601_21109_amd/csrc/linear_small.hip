@@ -171,7 +171,8 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d) {
 cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* wt_at, const void* bt,
                           const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                           const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
-                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, hipStream_t st) {
+                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, const TokMeta* gate,
+                          hipStream_t st) {
     if (d->dt != CWL_BF16 || d->n_rows < 1 || d->n_rows > kSmallRows) return CWL_ERR_UNSUPPORTED;
     const SmallPlan p = small_rows_plan(d);
     const int32_t R = padded_rank(d->r_max);
@@ -201,7 +202,7 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
         job.lad.ranks[k] = d->ranks[k];
         job.lad.scales[k] = d->scales[k];
     }
-    job.meta = meta;
+    job.meta = gate ? nullptr : meta;
     prof_begin(CWL_PROF_MAIN, st);
     cwl_status s = launch_partial_bf16(pa, job, st);
     prof_end(CWL_PROF_MAIN, st);
@@ -209,11 +210,12 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
 
     if (d->d_out < 8) return CWL_ERR_UNSUPPORTED;
     prof_begin(CWL_PROF_META, st);
-    if (p.splits <= 2) s = launch_fixup<2>(d, R, p, partial, bt, meta, y, st);
-    else if (p.splits <= 4) s = launch_fixup<4>(d, R, p, partial, bt, meta, y, st);
-    else if (p.splits <= 8) s = launch_fixup<8>(d, R, p, partial, bt, meta, y, st);
-    else if (p.splits <= 16) s = launch_fixup<16>(d, R, p, partial, bt, meta, y, st);
-    else s = launch_fixup<32>(d, R, p, partial, bt, meta, y, st);
+    const TokMeta* mt = gate ? gate : meta;
+    if (p.splits <= 2) s = launch_fixup<2>(d, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 4) s = launch_fixup<4>(d, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 8) s = launch_fixup<8>(d, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 16) s = launch_fixup<16>(d, R, p, partial, bt, mt, y, st);
+    else s = launch_fixup<32>(d, R, p, partial, bt, mt, y, st);
     prof_end(CWL_PROF_META, st);
     if (s != CWL_OK) return s;
     return CWL_OK;

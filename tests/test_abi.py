@@ -144,6 +144,49 @@ def test_linear_descriptor_errors(L):
     assert L.cwl_linear_packed_workspace_bytes(d.ref()) < L.cwl_linear_workspace_bytes(d.ref())
 
 
+def test_stream_step_and_gated_linear_argument_errors(L):
+    f = L.cwl_stream_step
+    p = B.ChunkParams(4, 9, 1.0, 1.0)
+    th = (ctypes.c_float * 2)(1.0, 2.0)
+    rk = (ctypes.c_int32 * 3)(4, 8, 16)
+    sc = (ctypes.c_float * 3)(4.0, 2.0, 1.0)
+    ok_args = (P(), 5, ctypes.byref(p), th, 3, rk, sc, 2, P(), P(), P(), P(), P(), None)
+
+    def call(**kw):
+        names = ["entropy", "n_seqs", "p", "th", "K", "ranks", "scales", "w", "state", "gate", "cl", "cs",
+                 "status", "stream"]
+        a = dict(zip(names, ok_args))
+        a.update(kw)
+        return f(*[a[n] for n in names])
+
+    assert call(p=None) == B.ERR_NULL
+    assert call(p=ctypes.byref(B.ChunkParams(4, 6, 1.0, 1.0))) == B.ERR_INFEASIBLE
+    assert call(p=ctypes.byref(B.ChunkParams(0, 6, 1.0, 1.0))) == B.ERR_INVALID_ARG
+    assert call(K=0) == B.ERR_INVALID_ARG
+    assert call(K=B.MAX_LADDER + 1) == B.ERR_INVALID_ARG
+    assert call(w=-1) == B.ERR_INVALID_ARG
+    assert call(n_seqs=-1) == B.ERR_INVALID_ARG
+    assert call(th=(ctypes.c_float * 2)(2.0, 1.0)) == B.ERR_INVALID_ARG
+    assert call(ranks=(ctypes.c_int32 * 3)(8, 4, 16)) == B.ERR_INVALID_ARG
+    assert call(ranks=(ctypes.c_int32 * 3)(4, 8, B.MAX_RANK + 1)) == B.ERR_INVALID_ARG
+    assert call(ranks=None) == B.ERR_NULL
+    assert call(state=None) == B.ERR_NULL
+    assert call(gate=None) == B.ERR_NULL
+    assert call(status=None) == B.ERR_NULL
+    assert call(n_seqs=0, entropy=None, state=None, gate=None) == B.OK
+    g = L.cwl_gated_lora_linear_packed
+    d = make_desc()
+    big = 1 << 30
+    assert g(None, P(), P(), P(), P(), P(), big, None) == B.ERR_NULL
+    assert g(d.ref(), P(0x10000), P(0x20000), None, P(0x30000), P(0x40000), big, None) == B.ERR_NULL
+    assert g(d.ref(), P(0x10000), None, P(0x50000), P(0x30000), P(0x40000), big, None) == B.ERR_NULL
+    assert g(d.ref(), P(0x10000), P(0x20000), P(0x50004), P(0x30000), P(0x40000), big, None) == B.ERR_INVALID_ARG
+    assert g(d.ref(), P(0x10000), P(0x20000), P(0x50000), P(0x30000), P(0x40000), 16, None) == B.ERR_CAPACITY
+    assert g(make_desc(group_rows=1).ref(), P(0x10000), P(0x20000), P(0x50000), P(0x30000), P(0x40000), big,
+             None) == B.ERR_UNSUPPORTED
+    assert g(make_desc(n_rows=0).ref(), P(), P(), P(), P(), P(), 0, None) == B.OK
+
+
 def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libcwl.so"))
