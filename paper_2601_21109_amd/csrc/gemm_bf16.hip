@@ -326,24 +326,39 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_bf16_tn_kernel(GemmArgs a) 
     gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI, BK>(a, (int)blockIdx.x);
 }
 
-// Split-reduction launch for a few rows: workgroup 0 fills the rows' gate table (the chain of
-// dependent lookups takes as long as the products themselves and runs beside them), workgroups
-// 1.. compute the partial products.
+// Split-reduction launch: the first job.n_blocks workgroups fill the rows' gate table, 256 tokens
+// each (the chain of dependent lookups takes as long as a short product and runs beside it; each
+// wavefront also reduces the largest effective rank of its 64 rows into job.blk_r), the
+// workgroups after them compute the partial products.
 template <int BM, int BN, int WM, int WN, int NST>
 __global__ void __launch_bounds__(WM * WN * 64) partial_bf16_kernel(GemmArgs a, MetaJob job) {
-    if (blockIdx.x == 0) {
-        if (!job.meta) return;                       // the caller brought the gate entries
+    static_assert(WM * WN * 64 == 256, "a gate-table block is 256 tokens");
+    if ((int)blockIdx.x < job.n_blocks) {
         __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
         __shared__ float lad_scales[CWL_MAX_LADDER];
         ladder_to_lds(job.lad, lad_ranks, lad_scales);
         __syncthreads();
-        for (int64_t t = threadIdx.x; t < a.M; t += WM * WN * 64)
-            job.meta[t] = token_meta_of(t, job.seq_offsets, job.n_seqs, job.chunk_offsets, job.chunk_start,
-                                        job.chunk_len, job.rank_idx, job.chunk_cap, job.lad.K, lad_ranks,
-                                        lad_scales, job.blend_w);
+        const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        TokMeta m = {0, 0, 0.0f, 0.0f};
+        if (t < a.M) {
+            m = token_meta_of(t, job.seq_offsets, job.n_seqs, job.chunk_offsets, job.chunk_start,
+                              job.chunk_len, job.rank_idx, job.chunk_cap, job.lad.K, lad_ranks, lad_scales,
+                              job.blend_w);
+            job.meta[t] = m;
+        }
+        if (job.blk_r) {
+            int32_t r_eff = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const int32_t o = __shfl_xor(r_eff, off);
+                r_eff = o > r_eff ? o : r_eff;
+            }
+            const int64_t blk = t / kRankBlock;
+            if ((threadIdx.x & 63) == 0 && blk * kRankBlock < a.M) job.blk_r[blk] = r_eff;
+        }
         return;
     }
-    gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI_PARTIAL, 64>(a, (int)blockIdx.x - 1);
+    gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI_PARTIAL, 64>(a, (int)blockIdx.x - job.n_blocks);
 }
 
 template <int BM, int BN, int WM, int WN, int NST>
@@ -363,7 +378,8 @@ cwl_status launch_partial_cfg(GemmArgs a, const MetaJob& job, hipStream_t st) {
     }
     a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
-    const int64_t grid = (int64_t)a.tiles_m * a.tiles_n * a.splits + 1;
+    if (job.n_blocks < 0 || (job.n_blocks > 0 && !job.meta)) return CWL_ERR_INVALID_ARG;
+    const int64_t grid = (int64_t)a.tiles_m * a.tiles_n * a.splits + job.n_blocks;
     if (grid >= (int64_t)1 << 31) return CWL_ERR_UNSUPPORTED;
     kern<<<dim3((unsigned)grid), dim3(WM * WN * 64), smem_bytes, st>>>(a, job);
     CWL_RETURN_IF_LAUNCH_FAILED();

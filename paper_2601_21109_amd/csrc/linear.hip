@@ -247,6 +247,81 @@ block_rank_from_gate_kernel(int64_t n_rows, const TokMeta* __restrict__ gate, in
 }
 
 // ------------------------------------------------------------------------------------------
+// Split shrink.  With fewer than ~16k rows the shrink's grid of 64-row tiles leaves most compute
+// units idle while each workgroup walks the whole reduction dimension (21 us at d_in = 4096
+// whatever the row count).  Then x A is computed as fp32 partial products over slices of the
+// reduction dimension (the EPI_PARTIAL launch, which also fills the gate table), and this kernel
+// sums the slices in slice order, applies the gate and rounds to bf16: uhat, as the one-pass
+// shrink writes it.  A thread owns 4 consecutive directions of one row; straight-line code with
+// SP (compile-time bound on the slices) loads in flight.
+// ------------------------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4_t;
+
+template <int SP>
+__global__ void __launch_bounds__(256)
+shrink_fixup_kernel(int64_t n_rows, int32_t R, const float* __restrict__ partial, int32_t splits,
+                    int64_t pstride, const TokMeta* __restrict__ meta, const int32_t* __restrict__ perm,
+                    __bf16* __restrict__ uhat) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;      // over n_rows * R / 4
+    const int per_row = R / 4;
+    int64_t g = idx / per_row;
+    const int i0 = (int)(idx % per_row) * 4;
+    const bool live = g < n_rows;
+    if (!live) g = n_rows - 1;
+    const float* p = partial + g * R + i0;
+    f32x4_t v[SP];
+#pragma unroll
+    for (int s = 0; s < SP; ++s) v[s] = *reinterpret_cast<const f32x4_t*>(p + (s < splits ? s : 0) * pstride);
+    const TokMeta mt = meta[perm ? (int64_t)perm[g] : g];     // partial and uhat: grouped row; meta: token
+    f32x4_t u = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int s = 0; s < SP; ++s)
+        if (s < splits) u += v[s];
+    bf16x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int i = i0 + e;
+        const float gate = (i < mt.r_prev ? mt.g_prev : 0.0f) + (i < mt.r_cur ? mt.g_cur : 0.0f);
+        o[e] = (__bf16)(u[e] * gate);
+    }
+    if (live) *reinterpret_cast<bf16x4_t*>(uhat + g * R + i0) = o;
+}
+
+template <int SP>
+cwl_status launch_shrink_fixup(int64_t n_rows, int32_t R, const float* partial, int32_t splits,
+                               int64_t pstride, const TokMeta* meta, const int32_t* perm, void* uhat,
+                               hipStream_t st) {
+    const int64_t n_thr = n_rows * (R / 4);
+    shrink_fixup_kernel<SP><<<dim3((unsigned)((n_thr + 255) / 256)), dim3(256), 0, st>>>(
+        n_rows, R, partial, splits, pstride, meta, perm, static_cast<__bf16*>(uhat));
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}
+
+// slices of the reduction dimension for the split shrink; splits < 2: keep the one-pass shrink
+// (rows gathered through a permutation are read through it; the gate table is then made first)
+SmallPlan shrink_split_plan(const cwl_linear_desc* d) {
+    SmallPlan p = {};
+    p.splits = 1;
+    if (d->dt != CWL_BF16 || d->n_rows >= 16384) return p;
+    const int64_t R = padded_rank(d->r_max);
+    const int64_t tiles = (d->n_rows + 127) / 128 * (R / 64);
+    const int64_t stages = d->d_in / 64;
+    int64_t s = 512 / tiles;
+    if (s > stages / 4) s = stages / 4;
+    if (s > 32) s = 32;
+    if (s < 2) return p;
+    p.n_tile = 64;
+    p.ks_per_split = (int32_t)((stages + s - 1) / s);
+    p.splits = (int32_t)((stages + p.ks_per_split - 1) / p.ks_per_split);
+    p.ldp = R;
+    p.partial_stride = d->n_rows * R;
+    p.partial_bytes = sizeof(float) * (size_t)p.splits * (size_t)p.partial_stride;
+    return p;
+}
+
+// ------------------------------------------------------------------------------------------
 // Weight re-layout: dst[c, r] = src[r, c] (zero where the source has no element), so that every
 // GEMM operand is contiguous along the reduction dimension.
 // ------------------------------------------------------------------------------------------
@@ -325,6 +400,7 @@ WsLayout ws_layout(const cwl_linear_desc* d) {
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
     L.partial = off;
     if (small_rows_path(d, packed_layout(d))) off = align_up(off + small_rows_plan(d).partial_bytes, 256);
+    else if (shrink_split_plan(d).splits >= 2) off = align_up(off + shrink_split_plan(d).partial_bytes, 256);
     L.total = off;
     return L;
 }
@@ -396,9 +472,12 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     }
     const bool grouped = d->group_rows == 1;
     const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
+    const SmallPlan split = shrink_split_plan(d);      // splits >= 2: split shrink (bf16, token order)
     prof_begin(CWL_PROF_META, st);
     if (gate)
         block_rank_from_gate_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, gate, d->r_max, blk_r);
+    else if (split.splits >= 2 && !grouped)
+        ;                                              // the gate table comes with the partial products
     else
         token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
             d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
@@ -435,7 +514,43 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
 
     cwl_status s;
     prof_begin(CWL_PROF_SHRINK, st);
-    s = d->dt == CWL_F32 ? launch_gemm_f32(sh, EPI_GATE, st) : launch_shrink_bf16(sh, st);
+    if (split.splits >= 2) {
+        float* partial = reinterpret_cast<float*>(ws + L.partial);
+        GemmArgs pa = {};
+        pa.A1 = x;             pa.lda1 = d->ldx;
+        pa.B1 = packed + P.at; pa.ldb1 = d->d_in;
+        pa.K1 = (int32_t)d->d_in;
+        pa.M = d->n_rows;      pa.N = P.R;
+        pa.N_tile = split.n_tile;
+        pa.splits = split.splits;
+        pa.ks_per_split = split.ks_per_split;
+        pa.partial = partial;
+        pa.ldp = split.ldp;
+        pa.partial_stride = split.partial_stride;
+        MetaJob job = {};
+        job.seq_offsets = seq_offsets;
+        job.chunk_offsets = chunk_offsets;
+        job.chunk_start = chunk_start;
+        job.chunk_len = chunk_len;
+        job.rank_idx = rank_idx;
+        job.n_seqs = n_seqs;
+        job.chunk_cap = chunk_cap;
+        job.blend_w = d->blend_w;
+        job.lad = lad;
+        job.meta = reinterpret_cast<TokMeta*>(ws + L.meta);
+        job.blk_r = blk_r;
+        job.n_blocks = (gate || grouped) ? 0 : (int32_t)meta_blocks;
+        pa.perm = grouped ? perm : nullptr;
+        s = launch_partial_bf16(pa, job, st);
+        if (s == CWL_OK) {
+            if (split.splits <= 4) s = launch_shrink_fixup<4>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
+            else if (split.splits <= 8) s = launch_shrink_fixup<8>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
+            else if (split.splits <= 16) s = launch_shrink_fixup<16>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
+            else s = launch_shrink_fixup<32>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
+        }
+    } else {
+        s = d->dt == CWL_F32 ? launch_gemm_f32(sh, EPI_GATE, st) : launch_shrink_bf16(sh, st);
+    }
     prof_end(CWL_PROF_SHRINK, st);
     if (s != CWL_OK) return s;
     prof_begin(CWL_PROF_MAIN, st);

@@ -73,7 +73,7 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = pad
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
 cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st);   // any a.perm
 cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st);   // 128 x 128 tiles
-// the gate table of rows 0 .. M-1, filled by one workgroup of the split-reduction launch
+// the gate table of rows 0 .. M-1, filled by the first workgroups of a split-reduction launch
 struct MetaJob {
     const int32_t* seq_offsets;
     const int32_t* chunk_offsets;
@@ -82,7 +82,9 @@ struct MetaJob {
     const int32_t* rank_idx;
     int32_t n_seqs, chunk_cap, blend_w;
     Ladder lad;
-    TokMeta* meta;           // NULL: nothing to fill
+    TokMeta* meta;           // [M]
+    int32_t* blk_r;          // [ceil(M / 64)] largest effective rank per 64 rows, or NULL
+    int32_t n_blocks;        // ceil(M / 256), or 0: the caller brought the gate entries
 };
 cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st);   // EPI_PARTIAL
 

@@ -6,9 +6,9 @@
 //      P = x . [W | A] is one product with d_out + R output columns.  It is cut into tiles of 64
 //      columns and into slices of the reduction dimension, one workgroup each (several hundred
 //      in all), every one leaving an fp32 tile in the workspace (the matrix-core kernel of
-//      gemm_bf16.hip with the EPI_PARTIAL epilogue).  One more workgroup of the same launch
-//      looks up the rows' gate entries (token_meta.h): a chain of dependent loads that takes as
-//      long as the products.
+//      gemm_bf16.hip with the EPI_PARTIAL epilogue).  One or two more workgroups of the same
+//      launch look up the rows' gate entries (token_meta.h): a chain of dependent loads that
+//      takes as long as the products.
 //   2. Fix-up.  Per 16 rows x 128 columns:
 //      uhat = gate * (sum over slices of the last R columns of P), rounded to bf16 as on the
 //      large path, then y = sum over slices of P + uhat . B with the matrix cores (B^T fragments
@@ -202,7 +202,8 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
         job.lad.ranks[k] = d->ranks[k];
         job.lad.scales[k] = d->scales[k];
     }
-    job.meta = gate ? nullptr : meta;
+    job.meta = meta;
+    job.n_blocks = gate ? 0 : (int32_t)((d->n_rows + 255) / 256);
     prof_begin(CWL_PROF_MAIN, st);
     cwl_status s = launch_partial_bf16(pa, job, st);
     prof_end(CWL_PROF_MAIN, st);
