@@ -455,4 +455,8 @@ cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st) {
     return launch_cfg<128, 128, 2, 2, 4, EPI_STORE, 64>(a, st);
 }
 
+cwl_status launch_main_bf16_tile256x128(const GemmArgs& a, hipStream_t st) {
+    return launch_cfg<256, 128, 2, 2, 3, EPI_STORE, 64>(a, st);
+}
+
 }  // namespace cwl

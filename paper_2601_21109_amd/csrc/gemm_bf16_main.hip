@@ -425,6 +425,8 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     if (n_tiles <= 0) return CWL_OK;
     // with tiles for a quarter of the compute units at most, 128 x 128 tiles fill the chip instead
     if (n_tiles <= 64) return launch_main_bf16_tile128(a_in, st);
+    // up to half of them: 256 x 128 tiles, again twice as many
+    if (n_tiles <= 128) return launch_main_bf16_tile256x128(a_in, st);
     const int64_t n_virtual = (n_tiles + 7) / 8 * 8;       // workgroup slots, 8 XCDs round-robin
     if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
     // persistent: one workgroup per compute unit (160 KiB of LDS each), a multiple of 8 of them

@@ -73,6 +73,7 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = pad
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
 cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st);   // any a.perm
 cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st);   // 128 x 128 tiles
+cwl_status launch_main_bf16_tile256x128(const GemmArgs& a, hipStream_t st);
 // the gate table of rows 0 .. M-1, filled by the first workgroups of a split-reduction launch
 struct MetaJob {
     const int32_t* seq_offsets;

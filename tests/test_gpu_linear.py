@@ -134,6 +134,16 @@ def test_bf16_few_rows_agree_with_the_large_path():
     assert (ys[0] - ys[1]).abs().max().item() <= 2.0 ** -6 * ys[0].abs().max().item()
 
 
+@pytest.mark.parametrize("n,d_out", [(1500, 2504), (2000, 3000)])
+def test_bf16_mid_sized_grids(n, d_out):
+    """60 and 96 tiles of 256 x 256: too few for the persistent kernel, served with 128 x 128 and
+    256 x 128 tiles (ragged in both directions, ranks up to two stages of the rank part)."""
+    rows = np.unique(np.concatenate([np.arange(0, n, 29), np.arange(250, 262), np.arange(n - 40, n)]))
+    yh, ref, _ = run_case(2, [n - 700, 700], 320, d_out, [8, 16, 32, 64, 100], 3, torch.bfloat16, 19, l_min=8,
+                          l_max=90, packed=True, rows=rows)
+    assert rel_err(yh, ref) <= TOL_BF16
+
+
 def test_bf16_grouped_rows_give_identical_output():
     args = (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4, torch.bfloat16, 5)
     _, _, y0 = run_case(*args, group_rows=0, packed=True, l_min=8, l_max=90)
