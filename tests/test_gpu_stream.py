@@ -150,3 +150,67 @@ def test_decode_steps_end_to_end():
                               g_prev.astype(np.float64))
         assert rel_err(host(y), yref) <= TOL_BF16
     assert ost.chunks.sum() > 0
+
+
+def test_decode_step_replays_from_a_hip_graph():
+    """The calls only enqueue kernels on the caller's stream, so a decode step (scores, scheduler step,
+    two projections) can be captured once and replayed.  Every replay, with eager work and
+    synchronisations in between, must equal the eager result for the same inputs and state."""
+    n_seqs, vocab, d_in, d_out, r_max = 8, 1500, 256, 320, 16
+    ranks, scales = [4, 8, 16], [4.0, 2.0, 1.0]
+    lnv = math.log(vocab)
+    args = (2, 4, 0.9 * lnv, 0.3 * lnv, [0.45 * lnv, 0.9 * lnv], ranks, scales, 2)
+    g = torch.Generator(device=DEV).manual_seed(9)
+    mk = lambda *s: (torch.randn(s, generator=g, device=DEV) / math.sqrt(s[0])).to(torch.bfloat16)
+    pw1 = B.prepack_weights(mk(d_in, d_out), mk(d_in, r_max), mk(r_max, d_out))
+    pw2 = B.prepack_weights(mk(d_out, d_in), mk(d_out, r_max), mk(r_max, d_in))
+    logits = torch.empty((n_seqs, vocab), dtype=torch.bfloat16, device=DEV)
+    x = torch.empty((n_seqs, d_in), dtype=torch.bfloat16, device=DEV)
+    h = torch.empty(n_seqs, dtype=torch.float32, device=DEV)
+    state = B.stream_state(n_seqs, DEV)
+    y1 = torch.empty((n_seqs, d_out), dtype=torch.bfloat16, device=DEV)
+    y2 = torch.empty((n_seqs, d_in), dtype=torch.bfloat16, device=DEV)
+    ws1 = B.linear_workspace((n_seqs, d_in), torch.bfloat16, d_out, r_max, ranks, scales, 0, DEV)
+    ws2 = B.linear_workspace((n_seqs, d_out), torch.bfloat16, d_in, r_max, ranks, scales, 0, DEV)
+    out = B.stream_step(h, state, *args)            # allocates the outputs once, outside the graph
+
+    def step():
+        B.score_tokens(logits, out=h)
+        B.stream_step(h, state, *args, out=out)
+        B.gated_lora_linear(x, pw1, out["gate"], ranks, scales, out=y1, workspace=ws1)
+        B.gated_lora_linear(y1, pw2, out["gate"], ranks, scales, out=y2, workspace=ws2)
+
+    def new_inputs(i):
+        gi = torch.Generator(device=DEV).manual_seed(100 + i)
+        sigma = torch.tensor([0.5, 2.0, 6.0], device=DEV)[torch.randint(0, 3, (n_seqs, 1), generator=gi, device=DEV)]
+        logits.copy_((torch.randn((n_seqs, vocab), generator=gi, device=DEV) * sigma).to(torch.bfloat16))
+        x.copy_(torch.randn((n_seqs, d_in), generator=gi, device=DEV).to(torch.bfloat16))
+
+    # eager reference run over 6 steps
+    state.zero_()
+    eager = []
+    for i in range(6):
+        new_inputs(i)
+        step()
+        torch.cuda.synchronize()
+        eager.append((y2.clone(), state.clone(), out["gate"].clone()))
+    # captured run
+    state.zero_()
+    new_inputs(0)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                       # warm-up on the capture stream
+        state.zero_()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for i in range(6):
+        new_inputs(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y2, eager[i][0]), i
+        assert torch.equal(state, eager[i][1]) and torch.equal(out["gate"], eager[i][2]), i
+        _ = (x.float() @ x.float().t()).sum().item()    # unrelated eager work between replays
