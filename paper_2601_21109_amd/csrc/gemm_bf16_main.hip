@@ -192,10 +192,9 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            uint32_t v = voffA[i];
-            asm volatile("" : "+v"(v));   // keeps the zero-extension at the load, which then takes
-                                          // the scalar-base + 32-bit-offset form
-            load_lds_16(sA + v, base + i * 1024);
+            asm volatile("" : "+v"(voffA[i]));   // keeps the zero-extension at the load, which then takes
+                                                 // the scalar-base + 32-bit-offset form (in place: no copy)
+            load_lds_16(sA + voffA[i], base + i * 1024);
         }
         sA += stepA;
         ++cntA;
@@ -204,9 +203,8 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
         char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
-            uint32_t v = voffB[i];
-            asm volatile("" : "+v"(v));
-            load_lds_16(sB + v, base + i * 1024);
+            asm volatile("" : "+v"(voffB[i]));
+            load_lds_16(sB + voffB[i], base + i * 1024);
         }
         sB += stepB;
         ++cntB;
