@@ -149,6 +149,11 @@ cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* chunk_len,
  * CWL_BF16 needs d_in % 64 == 0 and d_out % 8 == 0, 16-byte aligned x / y and ldx % 8 == 0,
  * ldy % 8 == 0 (else CWL_ERR_UNSUPPORTED).
  *
+ * The launch plan depends on the shape (up to 512 rows: the weights are streamed once by several
+ * hundred workgroups, each over a slice of d_in, and a second kernel adds the slices in a fixed
+ * order; otherwise output tiles of 128 x 128 to 256 x 256); the arithmetic stated above does not,
+ * and a call gives the same bits every time.
+ *
  * The static weights can be re-laid out once with cwl_prepack_weights (K-contiguous, padded
  * ladder) and then used through cwl_chunkwise_lora_linear_packed; the plain entry point does
  * the same re-layout into its workspace on every call.
