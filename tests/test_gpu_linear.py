@@ -117,6 +117,26 @@ def test_bf16_few_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
     assert torch.equal(y, y2)                         # slice sums in a fixed order
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_bf16_random_shapes_across_the_launch_plans(seed):
+    """Random shapes around the switch points of the launch plan (512 rows, 64 / 128 tiles of 256 x 256,
+    slice counts), random ladders and joins, against the oracle."""
+    rng = np.random.RandomState(1000 + seed)
+    n = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700, 1100]))
+    d_in = 64 * int(rng.randint(1, 13))
+    d_out = 8 * int(rng.randint(1, 90))
+    K = int(rng.randint(1, 5))
+    ranks = sorted(int(r) for r in rng.choice(np.arange(0, 201), size=K, replace=False))
+    n_seqs = int(rng.randint(1, 4))
+    cuts = np.sort(rng.randint(0, n + 1, size=n_seqs - 1))
+    seq_lens = np.diff(np.concatenate([[0], cuts, [n]])).tolist()
+    w = int(rng.randint(0, 5))
+    rows = None if n * d_out * d_in <= 6e7 else np.unique(rng.randint(0, n, size=120))
+    yh, ref, _ = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 2000 + seed, l_min=5, l_max=37,
+                          packed=bool(seed % 2), rows=rows)
+    assert rel_err(yh, ref) <= TOL_BF16
+
+
 def test_bf16_few_rows_agree_with_the_large_path():
     """Rows 0..511 of a 513-row call (tiled path) against the same rows as a 512-row call."""
     d_in, d_out, ranks = 1024, 520, [8, 16, 32, 64]
