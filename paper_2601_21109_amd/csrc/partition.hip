@@ -220,6 +220,7 @@ partition_scan_kernel(const float* __restrict__ entropy, int64_t n_rows,
 __device__ __forceinline__ int64_t chunk_end(const int32_t* q, const int64_t* Pin, int64_t shift, int64_t p, int64_t T,
                              int32_t l_min, int32_t l_max, int64_t theta_q, int64_t delta_q) {
     const int lane = threadIdx.x & 63;
+    const int32_t theta32 = (int32_t)theta_q, delta32 = (int32_t)delta_q;
     const int64_t e_hi = (p + l_max < T) ? p + l_max : T;
     int64_t e_star = (T - p <= l_max) ? T : ((p + l_max < T - l_min) ? p + l_max : T - l_min);
     const int64_t Pex_p = Pin[p - shift] - q[p - shift];          // sum of the tokens before p
@@ -230,12 +231,13 @@ __device__ __forceinline__ int64_t chunk_end(const int32_t* q, const int64_t* Pi
             if (e == T) {
                 fire = true;
             } else {
-                const int64_t n = e - p;
+                // scores, thresholds (<= 2^21) and lengths fit 32 bits: 32 x 32 -> 64-bit products
+                const int32_t n = (int32_t)(e - p);
                 const int64_t S = Pin[e - 1 - shift] - Pex_p;
-                const int64_t qe = q[e - shift];
-                int64_t d = qe * n - S;
+                const int32_t qe = q[e - shift];
+                int64_t d = (int64_t)qe * n - S;
                 if (d < 0) d = -d;
-                fire = (S >= theta_q * n) || (qe >= theta_q) || (d > delta_q * n);
+                fire = (S >= (int64_t)theta32 * n) || (qe >= theta32) || (d > (int64_t)delta32 * n);
             }
         }
         const unsigned long long mask = __ballot(fire);
