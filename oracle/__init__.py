@@ -15,6 +15,7 @@ from .reference import (  # noqa: F401
     StreamState,
     stream_step,
     gated_linear,
+    compose_scores,
     num_threads,
     set_num_threads,
     bf16_round,

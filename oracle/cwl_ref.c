@@ -17,6 +17,8 @@
  *   - Sec. III-A/B (signals and grouping computed step by step while decoding), Sec. III-F
  *     (scheduler state kept between steps): the same rules one token at a time -> cwl_ref_stream_step
  *   - the layer for rows that bring their own gate (what a decode step feeds) -> cwl_ref_gated_linear
+ *   - Sec. III-A signals (ii) n-gram novelty against the recent context and (iv) positional
+ *     prior, mixed with the entropy into one score                             -> cwl_ref_compose_scores
  *
  * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
  * readings taken are written out step by step in the comments of each function.
@@ -414,6 +416,57 @@ int cwl_ref_gated_linear(const float* x, int64_t ldx, const float* W, int64_t ld
             adapter_term(u, B, ldb, d_out, r_prev[t], 1.0, g_prev[t], yt);
         }
         free(u);
+    }
+    return CWL_REF_OK;
+}
+
+
+/* ------------------------------------------------------------------------------------------
+ * Composite difficulty score (Sec. III-A lists, next to the entropy, an n-gram novelty signal
+ * against the recent context and a small positional prior that favours early steps; the paper
+ * gives neither formula nor weights).  Reading, per token t at position j of its sequence:
+ *   novelty_t = 1 if the n-gram of token ids that ends at j, ids[j-n+1 .. j], ends at none of the
+ *               positions j' with max(n-1, j-window) <= j' < j of the same sequence; tokens with
+ *               j < n-1 (no complete n-gram yet) count as new;  else 0;
+ *   prior_t   = max(0, 1 - j / prior_len)   (0 when prior_len <= 0): a linear ramp down over the
+ *               first prior_len tokens;
+ *   score_t   = w_entropy * H_t + w_novelty * novelty_t + w_prior * prior_t.
+ * A token outside every sequence keeps score_t = w_entropy * H_t and novelty 0.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_compose_scores(const float* entropy, const int32_t* ids, int64_t n_rows,
+                           const int32_t* seq_offsets, int32_t n_seqs, int32_t n, int32_t window,
+                           double w_entropy, double w_novelty, double w_prior, double prior_len,
+                           double* score, int32_t* novelty) {
+    if (n < 1 || window < 0) return CWL_REF_ERR_INVALID;
+    for (int64_t t = 0; t < n_rows; ++t) {
+        score[t] = w_entropy * (double)entropy[t];
+        novelty[t] = 0;
+    }
+    for (int32_t b = 0; b < n_seqs; ++b) {
+        const int64_t base = seq_offsets[b];
+        const int64_t T = (int64_t)seq_offsets[b + 1] - base;
+        if (T < 0 || base < 0 || base + T > n_rows) return CWL_REF_ERR_INVALID;
+        const int32_t* s_ids = ids + base;
+        for (int64_t j = 0; j < T; ++j) {
+            int is_new = 1;
+            if (j >= n - 1) {
+                int64_t lo = j - window;
+                if (lo < n - 1) lo = n - 1;
+                for (int64_t jp = lo; jp < j && is_new; ++jp) {
+                    int same = 1;
+                    for (int32_t i = 0; i < n; ++i)
+                        if (s_ids[jp - i] != s_ids[j - i]) { same = 0; break; }
+                    if (same) is_new = 0;
+                }
+            }
+            double prior = 0.0;
+            if (prior_len > 0.0) {
+                prior = 1.0 - (double)j / prior_len;
+                if (prior < 0.0) prior = 0.0;
+            }
+            novelty[base + j] = is_new;
+            score[base + j] = w_entropy * (double)entropy[base + j] + w_novelty * (double)is_new + w_prior * prior;
+        }
     }
     return CWL_REF_OK;
 }

@@ -55,6 +55,9 @@ def _load():
     lib.cwl_ref_stream_step.restype = ctypes.c_int
     lib.cwl_ref_gated_linear.argtypes = [P, i64, P, i64, P, i64, P, i64, i64, i64, i64, i32, P, P, P, P, P]
     lib.cwl_ref_gated_linear.restype = ctypes.c_int
+    f64 = ctypes.c_double
+    lib.cwl_ref_compose_scores.argtypes = [P, P, i64, P, i32, i32, i32, f64, f64, f64, f64, P, P]
+    lib.cwl_ref_compose_scores.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -221,6 +224,21 @@ def gated_linear(x, W, A, B, r_cur, g_cur, r_prev, g_prev):
     if st != OK:
         raise ValueError(f"cwl_ref_gated_linear: status {st}")
     return y
+
+
+def compose_scores(entropy, token_ids, seq_offsets, n, window, w_entropy, w_novelty, w_prior, prior_len):
+    """Composite score: w_entropy H + w_novelty [n-gram new within `window`] + w_prior max(0, 1 - j / prior_len).
+    Returns (status, score float64[N], novelty int32[N])."""
+    h = _arr(entropy, np.float32).ravel()
+    ids = _arr(token_ids, np.int32).ravel()
+    so = _arr(seq_offsets, np.int32).ravel()
+    assert ids.shape[0] == h.shape[0]
+    score = np.zeros(h.shape[0], np.float64)
+    nov = np.zeros(h.shape[0], np.int32)
+    st = _load().cwl_ref_compose_scores(_ptr(h), _ptr(ids), h.shape[0], _ptr(so), so.shape[0] - 1, int(n),
+                                        int(window), float(w_entropy), float(w_novelty), float(w_prior),
+                                        float(prior_len), _ptr(score), _ptr(nov))
+    return st, score, nov
 
 
 def bf16_round(y):
