@@ -67,6 +67,36 @@ cwl_status cwl_score_tokens(const void* logits, cwl_dtype dt, int64_t n_rows, in
                             int64_t row_stride, float* entropy, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_compose_scores -- composite difficulty score (Sec. III-A names, next to the entropy, an
+ * n-gram novelty signal against the recent context and a small positional prior that favours
+ * early steps; no formula or weight is given, this is the reading taken).  For token t at position
+ * j of its sequence:
+ *      novelty_t = 1 if the n-gram of token ids ending at j ends at none of the positions j' with
+ *                  max(n-1, j-window) <= j' < j of the same sequence (tokens with j < n-1 count
+ *                  as new), else 0
+ *      prior_t   = max(0, 1 - j / prior_len)         (0 when prior_len <= 0)
+ *      score_t   = w_entropy * entropy_t + w_novelty * novelty_t + w_prior * prior_t     (fp32)
+ * A row outside every sequence gets w_entropy * entropy_t and novelty 0.  The result is a score in
+ * the units of its weights; with the weights in nats it can be handed to cwl_partition_chunks in
+ * place of the entropy.
+ *
+ *   entropy     [n_rows] fp32        token_ids   [n_rows] int32
+ *   seq_offsets [n_seqs+1]           m           host; 1 <= n <= 8, 0 <= window <= 4096 (else
+ *                                                CWL_ERR_UNSUPPORTED)
+ *   score       [n_rows] fp32, written (may alias entropy)
+ *   novelty     [n_rows] int32, written when not NULL
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int32_t n, window;
+    float w_entropy, w_novelty, w_prior;
+    float prior_len;
+} cwl_score_mix;
+
+cwl_status cwl_compose_scores(const float* entropy, const int32_t* token_ids, int64_t n_rows,
+                              const int32_t* seq_offsets, int32_t n_seqs, const cwl_score_mix* m /*host*/,
+                              float* score, int32_t* novelty, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * cwl_partition_chunks -- adaptive chunker (Sec. III-B, Sec. IV-B).
  *
  * Scores are first turned into Q10 fixed-point integers q = floor(h*1024 + 0.5) (fp32; NaN and
@@ -267,7 +297,7 @@ cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x,
  * for the recorded launches of `slot` (the most recent 256 at most) and returns their summed
  * duration in milliseconds and their count.  Host-side, not thread-safe.
  * ------------------------------------------------------------------------------------------- */
-#define CWL_PROF_SCORE 0      /* the entropy kernel of cwl_score_tokens                  */
+#define CWL_PROF_SCORE 0      /* the entropy kernel of cwl_score_tokens; cwl_compose_scores */
 #define CWL_PROF_PARTITION 1  /* all kernels of cwl_partition_chunks; cwl_stream_step     */
 #define CWL_PROF_SELECT 2     /* the kernel of cwl_select_ranks                          */
 #define CWL_PROF_META 3       /* gate table / grouping kernels of the linear; with at     

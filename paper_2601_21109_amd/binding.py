@@ -18,7 +18,7 @@ F32, BF16 = 0, 1
 STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS = 1, 2, 4
 MAX_LADDER, MAX_RANK = 16, 256
 
-EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens",
+EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_compose_scores",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
@@ -31,6 +31,11 @@ PROF_SLOTS = 6
 class ChunkParams(ctypes.Structure):
     _fields_ = [("l_min", ctypes.c_int32), ("l_max", ctypes.c_int32),
                 ("theta_hard", ctypes.c_float), ("delta_dev", ctypes.c_float)]
+
+
+class ScoreMix(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_int32), ("window", ctypes.c_int32), ("w_entropy", ctypes.c_float),
+                ("w_novelty", ctypes.c_float), ("w_prior", ctypes.c_float), ("prior_len", ctypes.c_float)]
 
 
 class LinearDesc(ctypes.Structure):
@@ -65,6 +70,8 @@ def lib():
     L.cwl_status_string.restype = ctypes.c_char_p
     L.cwl_abi_version.restype = i32
     L.cwl_score_tokens.argtypes = [P, ctypes.c_int, i64, i64, i64, P, P]
+    L.cwl_compose_scores.argtypes = [P, P, i64, P, i32, ctypes.POINTER(ScoreMix), P, P, P]
+    L.cwl_compose_scores.restype = ctypes.c_int
     L.cwl_partition_workspace_bytes.argtypes = [i64, i32, ctypes.POINTER(ChunkParams)]
     L.cwl_partition_workspace_bytes.restype = sz
     L.cwl_partition_chunks.argtypes = [P, i64, P, i32, ctypes.POINTER(ChunkParams), P, P, P, P,
@@ -132,6 +139,24 @@ def score_tokens(logits, out=None):
     _check(lib().cwl_score_tokens(_ptr(logits), _dt(logits), n, v, logits.stride(0) if n > 1 else v,
                                   _ptr(out), _stream()), "cwl_score_tokens")
     return out
+
+
+def compose_scores(entropy, token_ids, seq_offsets, n, window, w_entropy=1.0, w_novelty=0.0, w_prior=0.0,
+                   prior_len=0.0, out=None, novelty=None):
+    """Composite difficulty score (entropy, n-gram novelty within `window`, positional prior).  Returns
+    (score fp32 [N], novelty int32 [N])."""
+    assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
+    assert token_ids.is_cuda and token_ids.dtype == torch.int32 and token_ids.is_contiguous()
+    assert token_ids.numel() == entropy.numel()
+    n_rows, n_seqs = entropy.numel(), seq_offsets.numel() - 1
+    if out is None:
+        out = torch.empty_like(entropy)
+    if novelty is None:
+        novelty = torch.empty(n_rows, dtype=torch.int32, device=entropy.device)
+    m = ScoreMix(int(n), int(window), float(w_entropy), float(w_novelty), float(w_prior), float(prior_len))
+    _check(lib().cwl_compose_scores(_ptr(entropy), _ptr(token_ids), n_rows, _ptr(seq_offsets), n_seqs,
+                                    ctypes.byref(m), _ptr(out), _ptr(novelty), _stream()), "cwl_compose_scores")
+    return out, novelty
 
 
 def partition_chunks(entropy, seq_offsets, l_min, l_max, theta_hard=math.inf, delta_dev=math.inf,

@@ -1,0 +1,93 @@
+// cwl_compose_scores: the composite difficulty score (gfx950 only).  Sec. III-A of arxiv 2601.21109
+// lists, next to the entropy, an n-gram novelty signal against the recent context and a small
+// positional prior; include/cwl.h states the reading taken.  One thread per token; a block of 256
+// tokens first copies the token ids it can look back at (its own 256 plus window + n - 1 before
+// them) into LDS, so the look-back costs LDS reads only: for window = 256, n = 3 about 350 per
+// token, a few microseconds for 16384 tokens.
+#include "common.h"
+
+namespace cwl {
+namespace {
+
+constexpr int kCompThreads = 256;
+constexpr int kMaxWindow = 4096;
+constexpr int kMaxN = 8;
+
+__global__ void __launch_bounds__(kCompThreads)
+compose_scores_kernel(const float* __restrict__ entropy, const int32_t* __restrict__ ids, int64_t n_rows,
+                      const int32_t* __restrict__ seq_offsets, int32_t n_seqs, int32_t n, int32_t window,
+                      float w_entropy, float w_novelty, float w_prior, float prior_len,
+                      float* __restrict__ score, int32_t* __restrict__ novelty) {
+    extern __shared__ int32_t ids_lds[];                     // ids[origin .. t0 + 255]
+    const int64_t t0 = (int64_t)blockIdx.x * kCompThreads;
+    int64_t origin = t0 - window - (n - 1);
+    if (origin < 0) origin = 0;
+    int64_t last = t0 + kCompThreads;
+    if (last > n_rows) last = n_rows;
+    for (int64_t i = origin + threadIdx.x; i < last; i += kCompThreads) ids_lds[i - origin] = ids[i];
+    __syncthreads();
+    const int64_t t = t0 + threadIdx.x;
+    if (t >= n_rows) return;
+    const float h = entropy[t];
+    float s = w_entropy * h;
+    int32_t is_new = 0;
+    // sequence: last b with seq_offsets[b] <= t
+    int32_t lo = 0, hi = n_seqs;
+    while (lo < hi) {
+        const int32_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)seq_offsets[mid] <= t) lo = mid + 1; else hi = mid;
+    }
+    const int32_t b = lo - 1;
+    if (b >= 0 && t < (int64_t)seq_offsets[b + 1]) {
+        const int64_t base = seq_offsets[b];
+        const int64_t j = t - base;
+        is_new = 1;
+        if (j >= n - 1) {
+            int64_t jlo = j - window;
+            if (jlo < n - 1) jlo = n - 1;
+            const int32_t* cur = ids_lds + (t - origin);     // cur[-i] = id at position j - i
+            for (int64_t jp = jlo; jp < j && is_new; ++jp) {
+                const int32_t* cand = ids_lds + (base + jp - origin);
+                bool same = true;
+                for (int32_t i = 0; i < n; ++i)
+                    if (cand[-i] != cur[-i]) { same = false; break; }
+                if (same) is_new = 0;
+            }
+        }
+        float prior = 0.0f;
+        if (prior_len > 0.0f) prior = fmaxf(1.0f - (float)j / prior_len, 0.0f);
+        s = fmaf(w_prior, prior, fmaf(w_novelty, (float)is_new, s));
+    }
+    score[t] = s;
+    if (novelty) novelty[t] = is_new;
+}
+
+}  // namespace
+}  // namespace cwl
+
+using namespace cwl;
+
+extern "C" cwl_status cwl_compose_scores(const float* entropy, const int32_t* token_ids, int64_t n_rows,
+                                         const int32_t* seq_offsets, int32_t n_seqs, const cwl_score_mix* m,
+                                         float* score, int32_t* novelty, void* stream) {
+    if (!m) return CWL_ERR_NULL;
+    if (n_rows < 0 || n_rows >= (int64_t)1 << 31 || n_seqs < 0) return CWL_ERR_INVALID_ARG;
+    if (m->n < 1 || m->window < 0) return CWL_ERR_INVALID_ARG;
+    if (m->n > kMaxN || m->window > kMaxWindow) return CWL_ERR_UNSUPPORTED;
+    if (m->w_entropy != m->w_entropy || m->w_novelty != m->w_novelty || m->w_prior != m->w_prior ||
+        m->prior_len != m->prior_len)
+        return CWL_ERR_INVALID_ARG;
+    if (n_rows == 0) return CWL_OK;
+    if (!entropy || !token_ids || !score) return CWL_ERR_NULL;
+    if (n_seqs > 0 && !seq_offsets) return CWL_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const unsigned blocks = (unsigned)((n_rows + kCompThreads - 1) / kCompThreads);
+    const size_t lds = sizeof(int32_t) * (size_t)(kCompThreads + m->window + m->n - 1);
+    prof_begin(CWL_PROF_SCORE, st);
+    compose_scores_kernel<<<dim3(blocks), dim3(kCompThreads), lds, st>>>(
+        entropy, token_ids, n_rows, seq_offsets, n_seqs, m->n, m->window, m->w_entropy, m->w_novelty,
+        m->w_prior, m->prior_len, score, novelty);
+    prof_end(CWL_PROF_SCORE, st);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}

@@ -187,6 +187,25 @@ def test_stream_step_and_gated_linear_argument_errors(L):
     assert g(make_desc(n_rows=0).ref(), P(), P(), P(), P(), P(), 0, None) == B.OK
 
 
+def test_compose_scores_argument_errors(L):
+    f = L.cwl_compose_scores
+    mix = lambda **kw: ctypes.byref(B.ScoreMix(**{**dict(n=3, window=64, w_entropy=1.0, w_novelty=0.5, w_prior=0.25,
+                                                          prior_len=100.0), **kw}))
+    assert f(P(), P(), 10, P(), 1, None, P(), P(), None) == B.ERR_NULL
+    assert f(P(), P(), -1, P(), 1, mix(), P(), P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), 10, P(), -1, mix(), P(), P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), 10, P(), 1, mix(n=0), P(), P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), 10, P(), 1, mix(window=-1), P(), P(), None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), 10, P(), 1, mix(n=9), P(), P(), None) == B.ERR_UNSUPPORTED
+    assert f(P(), P(), 10, P(), 1, mix(window=5000), P(), P(), None) == B.ERR_UNSUPPORTED
+    assert f(P(), P(), 10, P(), 1, mix(w_prior=math.nan), P(), P(), None) == B.ERR_INVALID_ARG
+    assert f(None, P(), 10, P(), 1, mix(), P(), P(), None) == B.ERR_NULL
+    assert f(P(), None, 10, P(), 1, mix(), P(), P(), None) == B.ERR_NULL
+    assert f(P(), P(), 10, P(), 1, mix(), None, P(), None) == B.ERR_NULL
+    assert f(P(), P(), 10, None, 1, mix(), P(), P(), None) == B.ERR_NULL
+    assert f(None, None, 0, None, 0, mix(), None, None, None) == B.OK
+
+
 def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libcwl.so"))
