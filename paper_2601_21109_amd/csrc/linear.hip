@@ -473,12 +473,12 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     const bool grouped = d->group_rows == 1;
     const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
     const SmallPlan split = shrink_split_plan(d);      // splits >= 2: split shrink (bf16, token order)
+    // with the split shrink in token order the gate table comes with the partial products
+    const bool table_with_products = !gate && split.splits >= 2 && !grouped;
     prof_begin(CWL_PROF_META, st);
     if (gate)
         block_rank_from_gate_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, gate, d->r_max, blk_r);
-    else if (split.splits >= 2 && !grouped)
-        ;                                              // the gate table comes with the partial products
-    else
+    else if (!table_with_products)
         token_meta_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(
             d->n_rows, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
             lad, d->blend_w, reinterpret_cast<TokMeta*>(ws + L.meta), grouped ? nullptr : blk_r,
@@ -539,7 +539,7 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
         job.lad = lad;
         job.meta = reinterpret_cast<TokMeta*>(ws + L.meta);
         job.blk_r = blk_r;
-        job.n_blocks = (gate || grouped) ? 0 : (int32_t)meta_blocks;
+        job.n_blocks = table_with_products ? (int32_t)meta_blocks : 0;
         pa.perm = grouped ? perm : nullptr;
         s = launch_partial_bf16(pa, job, st);
         if (s == CWL_OK) {
