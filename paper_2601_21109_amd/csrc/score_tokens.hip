@@ -183,7 +183,11 @@ cwl_status launch(const void* logits, int64_t n_rows, int64_t vocab, int64_t row
     cwl::prof_begin(CWL_PROF_SCORE, st);
     // threads per row: enough 16-byte loads per thread to amortise the state merge, enough
     // blocks per CU to keep HBM busy (measured best on 64 KB rows: 2 wavefronts per row)
-    if (row_bytes <= 16 * 1024) {
+    if (n_rows <= 128 && row_bytes > 16 * 1024) {
+        // a decode step's handful of rows: one workgroup per row is all the parallelism there is,
+        // so give every row sixteen wavefronts
+        score_tokens_kernel<T, 16><<<dim3((unsigned)n_rows), dim3(1024), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
+    } else if (row_bytes <= 16 * 1024) {
         const int64_t blocks = (n_rows + 3) / 4;
         score_tokens_kernel<T, 1><<<dim3((unsigned)blocks), dim3(256), 0, st>>>(lp, n_rows, vocab, row_stride, entropy);
     } else if (row_bytes <= 128 * 1024) {

@@ -38,6 +38,18 @@ def test_vocab_sizes_and_ragged_tails(oracle, dtype, V):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [4099, 9000, 32000, 70001])
+def test_more_rows_than_the_few_row_launch(oracle, dtype, V):
+    """130 rows: past the launch used for a decode step's handful of rows, so the two- and four-wavefront
+    kernels run (up to 128 rows with long rows get sixteen wavefronts each)."""
+    g = torch.Generator(device=DEV).manual_seed(V + 1)
+    n = 130
+    sig = torch.tensor([0.5, 2.0, 6.0], device=DEV)[torch.arange(n, device=DEV) % 3].unsqueeze(1)
+    z = (torch.randn((n, V), generator=g, device=DEV) * sig).to(dtype)
+    check(z, oracle)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_large_vocab_path(oracle, dtype):
     g = torch.Generator(device=DEV).manual_seed(5)
     z = (torch.randn((9, 128000), generator=g, device=DEV) * 3.0).to(dtype)
