@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--group-rows", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true")
+    ap.add_argument("--all-projections", action="store_true",
+                    help="also time the linear of every projection of the workload (own x, W, A, B; the same "
+                         "chunk table) and report the sum")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings against)")
@@ -330,6 +333,28 @@ def main():
         out["few_rows"] = {"note": "rows <= 512: partial products + fix-up kernel; weight bytes = 2 d_in (d_out + R), "
                                    "rate over both event-timed kernels (a few microseconds of launch gap included)",
                            "weight_bytes": w_bytes, **few}
+
+    # ---- every projection of the workload with the same chunk table -------------------------------
+    if args.all_projections:
+        per = {}
+        for p_i, (p_name, p_in, p_out) in enumerate(wl.projections):
+            xp, Wp, Ap, Bp = W.linear_operands(wl, p_i, dev)
+            pk = B.prepack_weights(Wp, Ap, Bp)
+            del Wp, Ap, Bp
+            yp = torch.empty((N, p_out), dtype=wl.dtype, device=dev)
+            wsp = B.linear_workspace((N, p_in), wl.dtype, p_out, wl.r_max, wl.ladder, wl.scales, wl.blend_w, dev)
+            fn = lambda: B.chunkwise_lora_linear(xp, pk, None, None, wl.ladder, wl.scales, wl.blend_w, sod, table,
+                                                 ri, out=yp, workspace=wsp)
+            ms_p, _ = timed(fn, max(args.steps // 2, 1), 2)
+            fl = 2.0 * N * p_in * p_out + 2.0 * float(r_eff.sum()) * (p_in + p_out)
+            per[f"{p_i}:{p_name}"] = {"d_in": p_in, "d_out": p_out, "ms": ms_p, "effective_tflops": fl / ms_p / 1e9}
+            del xp, pk, yp, wsp
+            torch.cuda.empty_cache()
+        tot = sum(v["ms"] for v in per.values())
+        out["all_projections"] = {"linear_ms_sum": tot, "linear_tokens_per_s": N / (tot * 1e-3),
+                                  "whole_path_tokens_per_s": N / ((tot + sum((kern_ms[k] or 0.0) for k in
+                                                                   ("score", "partition", "select"))) * 1e-3),
+                                  "per_projection": per}
 
     # ---- the CPU oracle on a bounded sample of the same workload ---------------------------------
     if not args.no_cpu_baseline:
