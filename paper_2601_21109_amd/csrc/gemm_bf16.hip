@@ -417,11 +417,11 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
     // from HBM: stages of BK = 64 (whole 128-byte lines per load instruction) and rings deep enough
     // to cover the memory latency with bytes in flight.
     // Every workgroup re-reads A^T from L2, as many bytes as it reads of x when the tile is 64 x 64;
-    // with enough rows to keep all compute units busy, 128-row tiles halve that.
+    // with enough rows to keep all compute units busy, 256-row tiles quarter that.
     if (a.M >= 128 * 512) {
         switch (a.N) {
-            case 64: return launch_cfg<128, 64, 2, 2, 5, EPI_GATE, 64>(a, st);
-            case 128: return launch_cfg<128, 128, 2, 2, 4, EPI_GATE, 64>(a, st);
+            case 64: return launch_cfg<256, 64, 2, 2, 4, EPI_GATE, 64>(a, st);
+            case 128: return launch_cfg<256, 128, 2, 2, 3, EPI_GATE, 64>(a, st);
             default: break;
         }
     }
