@@ -217,15 +217,18 @@ partition_scan_kernel(const float* __restrict__ entropy, int64_t n_rows,
 // or that token deviates from the chunk mean by more than delta; else the longest admissible
 // end.  q and Pin are indexed by local position (pointers already at the sequence, or at an LDS
 // copy of a window of it shifted by `shift`).  One wavefront, 64 candidates per step.
-__device__ __forceinline__ int64_t chunk_end(const int32_t* q, const int64_t* Pin, int64_t shift, int64_t p, int64_t T,
+// (IT: int64_t, or int32_t where positions are known to fit -- half the integer instructions in the
+// chain walk, whose latency is the run time of the short-sequence kernel)
+template <typename IT>
+__device__ __forceinline__ IT chunk_end(const int32_t* q, const int64_t* Pin, IT shift, IT p, IT T,
                              int32_t l_min, int32_t l_max, int64_t theta_q, int64_t delta_q) {
     const int lane = threadIdx.x & 63;
     const int32_t theta32 = (int32_t)theta_q, delta32 = (int32_t)delta_q;
-    const int64_t e_hi = (p + l_max < T) ? p + l_max : T;
-    int64_t e_star = (T - p <= l_max) ? T : ((p + l_max < T - l_min) ? p + l_max : T - l_min);
+    const IT e_hi = (p + l_max < T) ? p + l_max : T;
+    IT e_star = (T - p <= l_max) ? T : ((p + l_max < T - l_min) ? p + l_max : T - l_min);
     const int64_t Pex_p = Pin[p - shift] - q[p - shift];          // sum of the tokens before p
-    for (int64_t e0 = p + l_min; e0 <= e_hi; e0 += 64) {
-        const int64_t e = e0 + lane;
+    for (IT e0 = p + l_min; e0 <= e_hi; e0 += 64) {
+        const IT e = e0 + lane;
         bool fire = false;
         if (e <= e_hi && (e <= T - l_min || e == T)) {
             if (e == T) {
@@ -290,15 +293,15 @@ partition_next_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, i
         seq_extent(seq_offsets, b, n_rows, &base, &T, &bad);
         if (bad || t < base || t >= base + T) continue;
         int64_t e;
-        if (in_lds) e = chunk_end(ql, Pl, g0 - base, t - base, T, l_min, l_max, theta_q, delta_q);
-        else e = chunk_end(ws.q + base, ws.Pin + base, 0, t - base, T, l_min, l_max, theta_q, delta_q);
+        if (in_lds) e = chunk_end<int64_t>(ql, Pl, g0 - base, t - base, T, l_min, l_max, theta_q, delta_q);
+        else e = chunk_end<int64_t>(ws.q + base, ws.Pin + base, (int64_t)0, t - base, T, l_min, l_max, theta_q, delta_q);
         if ((tid & 63) == 0) ws.next[t] = (int32_t)(base + e);
     }
 }
 
 // ---- short sequences: scan and chain walk in one kernel ----
 constexpr int kLdsTokens = 8192;   // sequences up to this length keep q and Pin in LDS
-constexpr size_t kSeqLdsBytes = (sizeof(int64_t) + sizeof(int32_t)) * kLdsTokens;
+constexpr size_t kSeqLdsBytes = (sizeof(int64_t) + 2 * sizeof(int32_t)) * kLdsTokens;   // Pin, q, chunk starts
 
 __global__ void __launch_bounds__(kThreads)
 partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
@@ -307,6 +310,7 @@ partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     __shared__ int64_t red[kThreads / 64];
     __shared__ int64_t wave_tot[kThreads / 64];
+    __shared__ int32_t n_sh;
     const int tid = threadIdx.x, wave = tid >> 6;
     const int32_t b = blockIdx.x;
     bool bad = false, saw_nan = false;
@@ -327,28 +331,58 @@ partition_seq_kernel(const float* __restrict__ entropy, int64_t n_rows,
     // look-ups, so their latency is the run time), else in the workspace.  Two instantiations, so
     // that the LDS one is compiled to LDS instructions rather than to generic-address ones.
     int32_t n_chunks = 0;
-    auto run = [&](int32_t* q, int64_t* Pin) {
+    // `starts`: LDS array for the chunk starts (then the chunk records are written by all threads after
+    // the walk, and the walk itself issues no global stores), or NULL: lane 0 writes every record as it goes
+    auto run = [&](auto it_tag, int32_t* q, int64_t* Pin, int32_t* starts) {
+        using IT = decltype(it_tag);                        // position type of the walk
         quantise_and_scan(entropy + base, T, q, Pin, wave_tot, &saw_nan);
         __syncthreads();       // q and Pin of the sequence are visible to the whole workgroup
         if (wave == 0) {
-            int64_t p = 0;
-            while (p < T) {
-                const int64_t e = chunk_end(q, Pin, 0, p, T, l_min, l_max, theta_q, delta_q);
-                const int64_t slot = stage_off + n_chunks;
-                if ((tid & 63) == 0 && slot < ws.stage_cap) {
-                    ws.st_start[slot] = (int32_t)(base + p);
-                    ws.st_len[slot] = (int32_t)(e - p);
-                    ws.st_sum[slot] = Pin[e - 1] - Pin[p] + q[p];
+            const IT Tw = (IT)T;
+            // a chunk cannot be longer than the sequence: with l_max cut to T the 32-bit sums below cannot overflow
+            const int32_t l_max_w = (int64_t)l_max > T ? (int32_t)T : l_max;
+            IT p = 0;
+            while (p < Tw) {
+                const IT e = chunk_end<IT>(q, Pin, (IT)0, p, Tw, l_min, l_max_w, theta_q, delta_q);
+                if ((tid & 63) == 0) {
+                    if (starts) {
+                        starts[n_chunks] = (int32_t)p;
+                    } else {
+                        const int64_t slot = stage_off + n_chunks;
+                        if (slot < ws.stage_cap) {
+                            ws.st_start[slot] = (int32_t)(base + p);
+                            ws.st_len[slot] = (int32_t)(e - p);
+                            ws.st_sum[slot] = Pin[e - 1] - Pin[p] + q[p];
+                        }
+                    }
                 }
                 ++n_chunks;
                 p = e;
             }
+            if (starts && (tid & 63) == 0) n_sh = n_chunks;
+        }
+        if (starts) {
+            __syncthreads();
+            const int32_t n = n_sh;
+            for (int32_t c = tid; c < n; c += kThreads) {
+                const int32_t p0 = starts[c];
+                const int32_t e0 = (c + 1 < n) ? starts[c + 1] : (int32_t)T;
+                const int64_t slot = stage_off + c;
+                if (slot < ws.stage_cap) {
+                    ws.st_start[slot] = (int32_t)(base + p0);
+                    ws.st_len[slot] = e0 - p0;
+                    ws.st_sum[slot] = Pin[e0 - 1] - Pin[p0] + q[p0];
+                }
+            }
+            n_chunks = n;
         }
     };
     if (T <= kLdsTokens)
-        run(reinterpret_cast<int32_t*>(lds_raw + sizeof(int64_t) * kLdsTokens), reinterpret_cast<int64_t*>(lds_raw));
+        run(int32_t{0}, reinterpret_cast<int32_t*>(lds_raw + sizeof(int64_t) * kLdsTokens),
+            reinterpret_cast<int64_t*>(lds_raw),
+            reinterpret_cast<int32_t*>(lds_raw + (sizeof(int64_t) + sizeof(int32_t)) * kLdsTokens));
     else
-        run(ws.q + base, ws.Pin + base);
+        run(int64_t{0}, ws.q + base, ws.Pin + base, nullptr);
     const int32_t nan_any = __syncthreads_or(saw_nan ? 1 : 0);
     const int32_t bad_any = __syncthreads_or(bad ? 1 : 0);
     if (tid == 0) {
