@@ -16,6 +16,9 @@ from .reference import (  # noqa: F401
     stream_step,
     gated_linear,
     compose_scores,
+    limit_high,
+    bucket_sequences,
+    partition_aligned,
     num_threads,
     set_num_threads,
     bf16_round,

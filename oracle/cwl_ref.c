@@ -19,6 +19,10 @@
  *   - the layer for rows that bring their own gate (what a decode step feeds) -> cwl_ref_gated_linear
  *   - Sec. III-A signals (ii) n-gram novelty against the recent context and (iv) positional
  *     prior, mixed with the entropy into one score                             -> cwl_ref_compose_scores
+ *   - Sec. III-B budget of high-capacity regions per sequence                   -> cwl_ref_limit_high
+ *   - Sec. III-G buckets of sequences by complexity percentile, Sec. IV-D
+ *     complexity-balanced micro-batches                                        -> cwl_ref_bucket_sequences
+ *   - Sec. III-G chunk boundaries aligned inside a bucket                       -> cwl_ref_partition_aligned
  *
  * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
  * readings taken are written out step by step in the comments of each function.
@@ -469,4 +473,158 @@ int cwl_ref_compose_scores(const float* entropy, const int32_t* ids, int64_t n_r
         }
     }
     return CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Budget of high-capacity regions per sequence (Sec. III-B lists the budget among the chunker's
+ * constraints; the paper gives no rule).  Reading: a chunk asks for high capacity when the rung
+ * the selector gives it is at least k_high.  Chunks are met in sequence order, as the online
+ * chunker meets them; the first `budget` chunks of a sequence that ask keep their rung, every
+ * later one that asks is set to rung k_high - 1, the highest one that is not high capacity.
+ * n_asked[s] (when not NULL) reports how many chunks of sequence s asked.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_limit_high(int32_t* rank_idx, const int32_t* chunk_offsets, int32_t n_seqs,
+                       int32_t k_high, int32_t budget, int32_t* n_asked) {
+    if (k_high < 1 || budget < 0) return CWL_REF_ERR_INVALID;
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        int32_t asked = 0;
+        for (int32_t c = chunk_offsets[s]; c < chunk_offsets[s + 1]; ++c) {
+            if (rank_idx[c] >= k_high) {
+                if (asked >= budget) rank_idx[c] = k_high - 1;
+                ++asked;
+            }
+        }
+        if (n_asked) n_asked[s] = asked;
+    }
+    return CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Buckets of sequences by complexity percentile, and complexity-balanced micro-batches
+ * (Sec. III-G: sequences of a batch are bucketed by complexity percentiles so that their chunk
+ * boundaries can be aligned; Sec. IV-D: a batch controller keeps micro-batches balanced in
+ * complexity).  Reading: the complexity of a sequence is the mean of its quantised scores,
+ * m_s = floor(sum_s / T_s) (0 for an empty sequence).  Sequences are ranked by (m_s, s) ascending,
+ * rho_s being the rank; order[rho_s] = s.  With n_buckets equal-count percentile bins,
+ *      bucket_s = floor(rho_s * n_buckets / n_seqs),
+ * so bucket 0 holds the sequences below the (100 / n_buckets)-th percentile, and so on.
+ * Micro-batches (when asked for) are dealt from the ranked order in alternating direction, round
+ * by round:  round = floor(rho / n_micro), j = rho mod n_micro,
+ *      micro_s = j for even rounds, n_micro - 1 - j for odd rounds,
+ * which gives every micro-batch the same number of sequences (within one) and total complexities
+ * that differ by no more than the spread of m over the batch.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_bucket_sequences(const int32_t* q, const int32_t* seq_offsets, int32_t n_seqs,
+                             int32_t n_buckets, int32_t n_micro, int64_t* seq_sum,
+                             int32_t* order, int32_t* bucket, int32_t* micro) {
+    if (n_buckets < 1 || n_micro < 0) return CWL_REF_ERR_INVALID;
+    int64_t* mean = (int64_t*)malloc((size_t)(n_seqs + 1) * sizeof(int64_t));
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        const int64_t T = (int64_t)seq_offsets[s + 1] - seq_offsets[s];
+        if (T < 0) { free(mean); return CWL_REF_ERR_INVALID; }
+        int64_t sum = 0;
+        for (int64_t t = 0; t < T; ++t) sum += q[seq_offsets[s] + t];
+        seq_sum[s] = sum;
+        mean[s] = T > 0 ? sum / T : 0;
+    }
+    /* rank by counting: rho_s = number of sequences that come before s in (mean, index) order */
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        int32_t rho = 0;
+        for (int32_t u = 0; u < n_seqs; ++u)
+            if (mean[u] < mean[s] || (mean[u] == mean[s] && u < s)) ++rho;
+        order[rho] = s;
+        bucket[s] = (int32_t)(((int64_t)rho * n_buckets) / n_seqs);
+        if (micro && n_micro > 0) {
+            const int32_t round = rho / n_micro, j = rho % n_micro;
+            micro[s] = (round % 2 == 0) ? j : n_micro - 1 - j;
+        }
+    }
+    free(mean);
+    return CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Chunker with boundaries aligned inside each bucket (Sec. III-G: chunk boundaries of the
+ * sequences of a bucket are aligned, while every sequence keeps its own rank choices).
+ * Reading: the sequences of a bucket share one set of boundaries, those the chunker of
+ * cwl_ref_partition places on the bucket's mean score series
+ *      m_b[t] = floor( sum over members s with T_s > t of q_s[t]  /  number of such members ),
+ * t < max T_s over the members.  A member takes every boundary that falls inside it: its chunks
+ * are [e_i, min(e_{i+1}, T_s)) for the bucket's chunk starts e_i < T_s, so only its last chunk
+ * can be shorter than the bucket's (and shorter than L_min).  Chunk sums are the member's own
+ * scores, so the selector still decides per sequence.  With one sequence per bucket this is
+ * cwl_ref_partition.
+ * ------------------------------------------------------------------------------------------ */
+int cwl_ref_partition_aligned(const int32_t* q, const int32_t* seq_offsets, int32_t n_seqs,
+                              const int32_t* bucket, int32_t n_buckets,
+                              int32_t l_min, int32_t l_max, int64_t theta_q, int64_t delta_q,
+                              int32_t* chunk_offsets, int32_t* chunk_start, int32_t* chunk_len,
+                              int64_t* chunk_sum, int32_t cap) {
+    if (n_buckets < 1) return CWL_REF_ERR_INVALID;
+    if (l_min < 1 || l_max < l_min) return CWL_REF_ERR_INVALID;
+    if ((int64_t)l_max < 2 * (int64_t)l_min - 1) return CWL_REF_ERR_INFEASIBLE;
+    int64_t n_rows = 0;
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        if (bucket[s] < 0 || bucket[s] >= n_buckets) return CWL_REF_ERR_INVALID;
+        if (seq_offsets[s + 1] < seq_offsets[s]) return CWL_REF_ERR_INVALID;
+        if (seq_offsets[s + 1] > n_rows) n_rows = seq_offsets[s + 1];
+    }
+    /* boundaries of every bucket: bstart[b] points at the bucket's ascending chunk starts */
+    int32_t** bstart = (int32_t**)calloc((size_t)n_buckets, sizeof(int32_t*));
+    int32_t* bcount = (int32_t*)calloc((size_t)n_buckets, sizeof(int32_t));
+    int32_t* bend = (int32_t*)calloc((size_t)n_buckets, sizeof(int32_t));   /* bucket's longest member */
+    int32_t* m = (int32_t*)malloc((size_t)(n_rows + 1) * sizeof(int32_t));
+    for (int32_t b = 0; b < n_buckets; ++b) {
+        int64_t Tmax = 0;
+        for (int32_t s = 0; s < n_seqs; ++s)
+            if (bucket[s] == b && (int64_t)seq_offsets[s + 1] - seq_offsets[s] > Tmax)
+                Tmax = (int64_t)seq_offsets[s + 1] - seq_offsets[s];
+        bend[b] = (int32_t)Tmax;
+        for (int64_t t = 0; t < Tmax; ++t) {
+            int64_t sum = 0, alive = 0;
+            for (int32_t s = 0; s < n_seqs; ++s)
+                if (bucket[s] == b && (int64_t)seq_offsets[s + 1] - seq_offsets[s] > t) {
+                    sum += q[seq_offsets[s] + t];
+                    ++alive;
+                }
+            m[t] = (int32_t)(sum / alive);
+        }
+        const int32_t vcap = (int32_t)Tmax + 1;
+        int32_t voff[2] = {0, (int32_t)Tmax};
+        int32_t vco[2];
+        int32_t* vstart = (int32_t*)malloc((size_t)vcap * sizeof(int32_t));
+        int32_t* vlen = (int32_t*)malloc((size_t)vcap * sizeof(int32_t));
+        int64_t* vsum = (int64_t*)malloc((size_t)vcap * sizeof(int64_t));
+        const int st = cwl_ref_partition(m, voff, 1, l_min, l_max, theta_q, delta_q, vco, vstart, vlen, vsum, vcap);
+        free(vlen);
+        free(vsum);
+        if (st != CWL_REF_OK) { free(vstart); free(m); free(bstart); free(bcount); free(bend); return st; }
+        bstart[b] = vstart;
+        bcount[b] = vco[1];
+    }
+    int64_t n_chunks = 0;
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        chunk_offsets[s] = (int32_t)n_chunks;
+        const int64_t base = seq_offsets[s];
+        const int64_t T = (int64_t)seq_offsets[s + 1] - base;
+        const int32_t b = bucket[s];
+        for (int32_t i = 0; i < bcount[b]; ++i) {
+            const int64_t e0 = bstart[b][i];
+            if (e0 >= T) break;
+            int64_t e1 = (i + 1 < bcount[b]) ? bstart[b][i + 1] : bend[b];
+            if (e1 > T) e1 = T;
+            if (n_chunks < cap) {
+                int64_t sum = 0;
+                for (int64_t t = e0; t < e1; ++t) sum += q[base + t];
+                chunk_start[n_chunks] = (int32_t)(base + e0);
+                chunk_len[n_chunks] = (int32_t)(e1 - e0);
+                chunk_sum[n_chunks] = sum;
+            }
+            ++n_chunks;
+        }
+    }
+    chunk_offsets[n_seqs] = (int32_t)n_chunks;
+    for (int32_t b = 0; b < n_buckets; ++b) free(bstart[b]);
+    free(bstart); free(bcount); free(bend); free(m);
+    return n_chunks > cap ? CWL_REF_ERR_CAPACITY : CWL_REF_OK;
 }

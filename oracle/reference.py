@@ -58,6 +58,12 @@ def _load():
     f64 = ctypes.c_double
     lib.cwl_ref_compose_scores.argtypes = [P, P, i64, P, i32, i32, i32, f64, f64, f64, f64, P, P]
     lib.cwl_ref_compose_scores.restype = ctypes.c_int
+    lib.cwl_ref_limit_high.argtypes = [P, P, i32, i32, i32, P]
+    lib.cwl_ref_limit_high.restype = ctypes.c_int
+    lib.cwl_ref_bucket_sequences.argtypes = [P, P, i32, i32, i32, P, P, P, P]
+    lib.cwl_ref_bucket_sequences.restype = ctypes.c_int
+    lib.cwl_ref_partition_aligned.argtypes = [P, P, i32, P, i32, i32, i32, i64, i64, P, P, P, P, i32]
+    lib.cwl_ref_partition_aligned.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -239,6 +245,50 @@ def compose_scores(entropy, token_ids, seq_offsets, n, window, w_entropy, w_nove
                                         int(window), float(w_entropy), float(w_novelty), float(w_prior),
                                         float(prior_len), _ptr(score), _ptr(nov))
     return st, score, nov
+
+
+def limit_high(rank_idx, chunk_offsets, k_high, budget):
+    """Budget of high-capacity chunks per sequence.  Returns (status, limited rank_idx, n_asked[n_seqs])."""
+    ri = _arr(rank_idx, np.int32).ravel().copy()
+    co = _arr(chunk_offsets, np.int32).ravel()
+    assert ri.shape[0] >= co[-1]
+    asked = np.zeros(co.shape[0] - 1, np.int32)
+    st = _load().cwl_ref_limit_high(_ptr(ri), _ptr(co), co.shape[0] - 1, int(k_high), int(budget), _ptr(asked))
+    return st, ri, asked
+
+
+def bucket_sequences(q, seq_offsets, n_buckets, n_micro=0):
+    """Percentile buckets and micro-batches of the sequences of a batch.
+    Returns (status, dict with seq_sum, order, bucket, micro)."""
+    q = _arr(q, np.int32).ravel()
+    so = _arr(seq_offsets, np.int32).ravel()
+    n = so.shape[0] - 1
+    out = {"seq_sum": np.zeros(n, np.int64), "order": np.zeros(n, np.int32),
+           "bucket": np.zeros(n, np.int32), "micro": np.zeros(n, np.int32)}
+    st = _load().cwl_ref_bucket_sequences(_ptr(q), _ptr(so), n, int(n_buckets), int(n_micro), _ptr(out["seq_sum"]),
+                                          _ptr(out["order"]), _ptr(out["bucket"]), _ptr(out["micro"]))
+    return st, out
+
+
+def partition_aligned(q, seq_offsets, bucket, n_buckets, l_min, l_max, theta_q, delta_q, cap=None):
+    """Chunk table with the boundaries shared inside each bucket.  Returns (status, dict of arrays)."""
+    q = _arr(q, np.int32).ravel()
+    so = _arr(seq_offsets, np.int32).ravel()
+    bk = _arr(bucket, np.int32).ravel()
+    n_seqs = so.shape[0] - 1
+    assert bk.shape[0] == n_seqs
+    if cap is None:
+        cap = int(q.shape[0]) + n_seqs + 1
+    off = np.zeros(n_seqs + 1, dtype=np.int32)
+    start = np.zeros(max(cap, 1), dtype=np.int32)
+    length = np.zeros(max(cap, 1), dtype=np.int32)
+    csum = np.zeros(max(cap, 1), dtype=np.int64)
+    st = _load().cwl_ref_partition_aligned(_ptr(q), _ptr(so), n_seqs, _ptr(bk), int(n_buckets), int(l_min),
+                                           int(l_max), int(theta_q), int(delta_q), _ptr(off), _ptr(start),
+                                           _ptr(length), _ptr(csum), int(cap))
+    n = min(int(off[-1]), cap) if st in (OK, ERR_CAPACITY) else 0
+    return st, {"chunk_offsets": off, "chunk_start": start[:n].copy(),
+                "chunk_len": length[:n].copy(), "chunk_sum": csum[:n].copy()}
 
 
 def bf16_round(y):

@@ -1,0 +1,229 @@
+"""Pins for the oracle's budget of high-capacity chunks (Sec. III-B), its percentile buckets and
+micro-batches (Sec. III-G, IV-D) and its chunker with boundaries aligned inside a bucket
+(Sec. III-G): hand-worked cases, reductions to the plain chunker, invariants, and independent
+restatements with numpy's sort and Python integers."""
+import numpy as np
+import pytest
+
+from test_oracle_partition import restated_partition
+
+INF_Q = 1 << 21
+
+
+def ragged(rng, n_seqs, t_lo, t_hi, levels=(300, 1500, 4000)):
+    lens = rng.integers(t_lo, t_hi + 1, n_seqs)
+    so = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    q = np.empty(so[-1], np.int32)
+    for s in range(n_seqs):
+        # spans of one difficulty level each, like the workloads' score series
+        t, T = 0, lens[s]
+        while t < T:
+            n = int(rng.integers(3, 40))
+            lvl = levels[int(rng.integers(0, len(levels)))] * (0.5 + s / n_seqs)
+            q[so[s] + t: so[s] + min(t + n, T)] = np.clip(rng.normal(lvl, 100, min(n, T - t)), 0, 1 << 20)
+            t += n
+    return q, so
+
+
+# ---------------------------------------------------------------- budget of high-capacity chunks
+
+def test_budget_hand_worked(oracle):
+    # two sequences; rungs asked for, k_high = 2, budget 2: the third and later askers drop to rung 1
+    ranks = [2, 0, 3, 1, 2, 3,   3, 1, 0]
+    st, out, asked = oracle.limit_high(ranks, [0, 6, 9], 2, 2)
+    assert st == 0
+    assert out.tolist() == [2, 0, 3, 1, 1, 1,   3, 1, 0]
+    assert asked.tolist() == [4, 1]
+
+
+def test_budget_limits(oracle):
+    rng = np.random.default_rng(5)
+    ranks = rng.integers(0, 4, 200).astype(np.int32)
+    co = np.array([0, 50, 50, 120, 200], np.int32)
+    # a budget no sequence exhausts changes nothing
+    st, out, asked = oracle.limit_high(ranks, co, 3, 1000)
+    assert st == 0 and out.tolist() == ranks.tolist()
+    assert asked.tolist() == [int((ranks[a:b] >= 3).sum()) for a, b in zip(co[:-1], co[1:])]
+    # budget 0: every rung is capped below k_high
+    st, out, _ = oracle.limit_high(ranks, co, 2, 0)
+    assert out.tolist() == np.minimum(ranks, 1).tolist()
+    # k_high above the ladder: nothing asks
+    st, out, asked = oracle.limit_high(ranks, co, 4, 0)
+    assert out.tolist() == ranks.tolist() and asked.tolist() == [0, 0, 0, 0]
+    assert oracle.limit_high(ranks, co, 0, 1)[0] != 0
+    assert oracle.limit_high(ranks, co, 1, -1)[0] != 0
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_budget_against_restatement(oracle, seed):
+    """Restated with prefix counts: a chunk is lowered iff it asks and at least `budget` earlier
+    chunks of its sequence asked."""
+    rng = np.random.default_rng(seed)
+    K = int(rng.integers(2, 6))
+    k_high = int(rng.integers(1, K))
+    budget = int(rng.integers(0, 5))
+    lens = rng.integers(0, 30, 7)
+    co = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    ranks = rng.integers(0, K, co[-1]).astype(np.int32)
+    st, out, asked = oracle.limit_high(ranks, co, k_high, budget)
+    assert st == 0
+    for a, b in zip(co[:-1], co[1:]):
+        seg = ranks[a:b]
+        asks = seg >= k_high
+        before = np.cumsum(asks) - asks
+        want = np.where(asks & (before >= budget), k_high - 1, seg)
+        assert out[a:b].tolist() == want.tolist()
+        assert int((out[a:b] >= k_high).sum()) == min(budget, int(asks.sum()))
+
+
+# ---------------------------------------------------------------- percentile buckets, micro-batches
+
+def test_buckets_hand_worked(oracle):
+    # means 10, 40, 20, 30 (lengths 1, 2, 1, 3) and an empty sequence (mean 0)
+    so = [0, 1, 3, 4, 7, 7]
+    q = [10, 40, 41, 20, 30, 30, 32]
+    st, o = oracle.bucket_sequences(q, so, 2, 2)
+    assert st == 0
+    assert o["seq_sum"].tolist() == [10, 81, 20, 92, 0]
+    # ranked: empty(0) < s0(10) < s2(20) < s3(30) < s1(40)
+    assert o["order"].tolist() == [4, 0, 2, 3, 1]
+    # ranks 0,1,2 | 3,4 with 5 sequences in 2 buckets: floor(rho*2/5)
+    assert o["bucket"].tolist() == [0, 1, 0, 1, 0]
+    # dealt 4,0 | 3,2 (reversed) | 1
+    assert o["micro"].tolist() == [1, 0, 1, 0, 0]
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_buckets_against_numpy_sort(oracle, seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(1, 40))
+    q, so = ragged(rng, n, 0, 60)
+    nb = int(rng.integers(1, 7))
+    nm = int(rng.integers(1, 6))
+    st, o = oracle.bucket_sequences(q, so, nb, nm)
+    assert st == 0
+    sums = np.array([int(q[a:b].astype(np.int64).sum()) for a, b in zip(so[:-1], so[1:])])
+    lens = np.diff(so)
+    means = np.where(lens > 0, sums // np.maximum(lens, 1), 0)
+    assert o["seq_sum"].tolist() == sums.tolist()
+    order = np.argsort(means, kind="stable")
+    assert o["order"].tolist() == order.tolist()
+    rho = np.empty(n, np.int64)
+    rho[order] = np.arange(n)
+    # percentile bins: bucket b holds the ranks in [ceil(b n / nb), ceil((b+1) n / nb))
+    for s in range(n):
+        b = int(o["bucket"][s])
+        assert -(-b * n // nb) <= rho[s] < -(-(b + 1) * n // nb)
+    assert np.all(np.diff(o["bucket"][order]) >= 0)
+    counts = np.bincount(o["bucket"], minlength=nb)
+    assert counts.max() - counts.min() <= 1
+    # micro-batches: equal counts within one, total complexity within the spread of the means
+    mcount = np.bincount(o["micro"], minlength=nm)
+    assert mcount.max() - mcount.min() <= 1
+    full_rounds = n // nm * nm
+    tot = np.bincount(o["micro"][order[:full_rounds]], weights=means[order[:full_rounds]], minlength=nm)
+    assert tot.max() - tot.min() <= means.max() - means.min()
+
+
+def test_buckets_ties_go_by_index(oracle):
+    so = np.arange(0, 7) * 3
+    q = np.full(18, 500, np.int32)
+    st, o = oracle.bucket_sequences(q, so, 3, 0)
+    assert o["order"].tolist() == [0, 1, 2, 3, 4, 5]
+    assert o["bucket"].tolist() == [0, 0, 1, 1, 2, 2]
+
+
+# ---------------------------------------------------------------- aligned chunker
+
+def table(res):
+    return (res["chunk_offsets"].tolist(), res["chunk_start"].tolist(), res["chunk_len"].tolist(),
+            res["chunk_sum"].tolist())
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_one_sequence_per_bucket_is_the_plain_chunker(oracle, seed):
+    rng = np.random.default_rng(seed)
+    q, so = ragged(rng, 6, 0, 200)
+    st0, plain = oracle.partition(q, so, 4, 24, 3000, 700)
+    perm = rng.permutation(6)
+    st1, al = oracle.partition_aligned(q, so, perm, 6, 4, 24, 3000, 700)
+    assert st0 == 0 and st1 == 0
+    assert table(al) == table(plain)
+
+
+def test_identical_sequences_keep_their_boundaries(oracle):
+    rng = np.random.default_rng(9)
+    q1, _ = ragged(rng, 1, 150, 150)
+    q = np.tile(q1, 4)
+    so = np.arange(5) * 150
+    st0, plain = oracle.partition(q, so, 4, 24, 3000, 700)
+    st1, al = oracle.partition_aligned(q, so, [0, 1, 0, 1], 2, 4, 24, 3000, 700)
+    assert st0 == 0 and st1 == 0 and table(al) == table(plain)
+
+
+def test_aligned_hand_worked(oracle):
+    # one bucket, two sequences of 8 and 5 tokens; L = (2, 4), theta = 100, no deviation test.
+    # mean series: floor((a+b)/2) while both run, then a alone
+    a = [10, 10, 300, 10, 10, 10, 10, 10]
+    b = [11, 20, 100, 10, 10]
+    m = [10, 15, 200, 10, 10, 10, 10, 10]
+    # chunker on m: [0,2) closes because m[2] >= theta; [2,4): mean 105 >= theta closes at once;
+    # [4,8): nothing fires, runs to the end (4 tokens)
+    assert restated_partition(m, 2, 4, 100, INF_Q) == [(0, 2, 25), (2, 2, 210), (4, 4, 40)]
+    st, al = oracle.partition_aligned(a + b, [0, 8, 13], [0, 0], 1, 2, 4, 100, INF_Q)
+    assert st == 0
+    assert al["chunk_offsets"].tolist() == [0, 3, 6]
+    assert al["chunk_start"].tolist() == [0, 2, 4, 8, 10, 12]
+    assert al["chunk_len"].tolist() == [2, 2, 4, 2, 2, 1]          # the short member's last chunk is cut
+    assert al["chunk_sum"].tolist() == [20, 310, 40, 31, 110, 10]  # each member's own scores
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_aligned_against_restatement(oracle, seed):
+    """Bucket mean series with Python integers, boundaries from the independent restatement of the
+    chunk rule, members cut at their own length."""
+    rng = np.random.default_rng(40 + seed)
+    n = int(rng.integers(2, 9))
+    q, so = ragged(rng, n, 0, 90)
+    nb = int(rng.integers(1, 4))
+    bucket = rng.integers(0, nb, n)
+    l_min, l_max = 3, 11
+    theta, delta = 2500, 600
+    st, al = oracle.partition_aligned(q, so, bucket, nb, l_min, l_max, theta, delta)
+    assert st == 0
+    lens = np.diff(so)
+    want_off, want = [0], []
+    bounds = {}
+    for b in range(nb):
+        mem = [s for s in range(n) if bucket[s] == b]
+        tmax = max([lens[s] for s in mem], default=0)
+        m = []
+        for t in range(tmax):
+            vals = [int(q[so[s] + t]) for s in mem if lens[s] > t]
+            m.append(sum(vals) // len(vals))
+        bounds[b] = [c[0] for c in restated_partition(m, l_min, l_max, theta, delta)] + [tmax]
+    for s in range(n):
+        e = bounds[int(bucket[s])]
+        for i in range(len(e) - 1):
+            if e[i] >= lens[s]:
+                break
+            hi = min(e[i + 1], lens[s])
+            want.append((so[s] + e[i], hi - e[i], int(q[so[s] + e[i]: so[s] + hi].astype(np.int64).sum())))
+        want_off.append(len(want))
+    assert al["chunk_offsets"].tolist() == want_off
+    assert list(zip(al["chunk_start"].tolist(), al["chunk_len"].tolist(), al["chunk_sum"].tolist())) == want
+    # every sequence is tiled exactly, and members of a bucket share their boundaries
+    for s in range(n):
+        a_, b_ = al["chunk_offsets"][s], al["chunk_offsets"][s + 1]
+        starts, ls = al["chunk_start"][a_:b_], al["chunk_len"][a_:b_]
+        assert ls.sum() == lens[s]
+        if b_ > a_:
+            assert starts[0] == so[s] and np.all(starts[1:] == starts[:-1] + ls[:-1])
+
+
+def test_aligned_errors(oracle):
+    q = np.arange(20, dtype=np.int32)
+    assert oracle.partition_aligned(q, [0, 10, 20], [0, 2], 2, 2, 4, 100, 100)[0] != 0     # bucket out of range
+    assert oracle.partition_aligned(q, [0, 10, 20], [0, 1], 2, 3, 4, 100, 100)[0] == 3     # infeasible bounds
+    st, al = oracle.partition_aligned(q, [0, 10, 20], [0, 1], 2, 2, 4, 100, 100, cap=3)
+    assert st == 4                                                                        # capacity
