@@ -41,10 +41,11 @@ typedef enum {
 
 typedef enum { CWL_F32 = 0, CWL_BF16 = 1 } cwl_dtype;
 
-/* Bits of the device status word written by cwl_partition_chunks. */
+/* Bits of the device status word written by cwl_partition_chunks(_aligned). */
 #define CWL_STATUS_CAPACITY 1u     /* more chunks than `cap`; only the first cap were written  */
 #define CWL_STATUS_NAN_SCORE 2u    /* a NaN score was met and scored as 0                      */
 #define CWL_STATUS_BAD_OFFSETS 4u  /* seq_offsets not non-decreasing within [0, n_rows]        */
+#define CWL_STATUS_BAD_BUCKET 8u   /* a bucket index outside [0, n_buckets) (taken as the nearest) */
 
 #define CWL_MAX_LADDER 16          /* largest K (rungs of the rank ladder)                     */
 #define CWL_MAX_RANK 256           /* largest r_max                                            */
@@ -151,6 +152,68 @@ cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* chunk_len,
                             const int32_t* chunk_offsets, int32_t n_seqs, int32_t cap,
                             const float* thresholds /*host*/, int32_t K, int32_t* rank_idx,
                             void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_select_ranks_budget -- cwl_select_ranks under a budget of high-capacity regions per sequence
+ * (Sec. III-B lists such a budget among the chunker's constraints).  A chunk asks for high capacity
+ * when the rung cwl_select_ranks gives it is >= k_high.  The chunks of a sequence are taken in
+ * order, as the online chunker meets them: the first `budget` that ask keep their rung, every later
+ * one that asks gets rung k_high - 1.
+ *
+ *   k_high   >= 1 (k_high >= K: no chunk asks)        budget   >= 0
+ *   n_asked  [n_seqs] written when not NULL: chunks of each sequence that asked
+ *   the other arguments as for cwl_select_ranks
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_select_ranks_budget(const int64_t* chunk_sum, const int32_t* chunk_len,
+                                   const int32_t* chunk_offsets, int32_t n_seqs, int32_t cap,
+                                   const float* thresholds /*host*/, int32_t K, int32_t k_high,
+                                   int32_t budget, int32_t* rank_idx, int32_t* n_asked, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_bucket_sequences -- buckets of the sequences of a batch by complexity percentile (Sec. III-G)
+ * and complexity-balanced micro-batches (Sec. IV-D).  The complexity of a sequence is the mean of
+ * its scores, quantised as in cwl_partition_chunks: m_s = floor(seq_sum[s] / T_s), 0 when empty.
+ * Sequences are ranked by (m_s, s) ascending, order[rho] = the sequence of rank rho, and
+ *      bucket[s] = floor(rho_s * n_buckets / n_seqs)          equal-count percentile bins,
+ *      micro[s]  = j in even rounds, n_micro-1-j in odd ones,   round = rho_s / n_micro, j = rho_s % n_micro
+ * (the ranked order dealt out in alternating direction: micro-batches of equal size within one
+ * whose total complexities differ by no more than the spread of m over the batch).
+ *
+ *   score [n_rows] fp32     seq_offsets [n_seqs+1]     n_seqs <= 4096 (else CWL_ERR_UNSUPPORTED)
+ *   n_buckets >= 1          n_micro >= 1 when micro is not NULL
+ *   seq_sum [n_seqs] int64, order / bucket [n_seqs] int32: written;  micro [n_seqs] written when not NULL
+ * A malformed seq_offsets entry counts as an empty sequence.
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_bucket_sequences(const float* score, int64_t n_rows, const int32_t* seq_offsets,
+                                int32_t n_seqs, int32_t n_buckets, int32_t n_micro, int64_t* seq_sum,
+                                int32_t* order, int32_t* bucket, int32_t* micro, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * cwl_partition_chunks_aligned -- the chunker with boundaries aligned inside each bucket
+ * (Sec. III-G: boundaries are aligned by bucketing the sequences, each sequence keeps its own
+ * rank choices).  The sequences of a bucket share the boundaries that the rule of
+ * cwl_partition_chunks places on the bucket's mean series
+ *      m_b[t] = floor( sum of q_s[t] over the members s with T_s > t  /  their number ),
+ * t < the longest member.  A member takes every boundary inside it, its chunks are
+ * [e_i, min(e_{i+1}, T_s)) for the bucket's chunk starts e_i < T_s, so only its last chunk can be
+ * shorter than the bucket's (and than l_min); chunk_sum holds the member's own scores.  With one
+ * sequence per bucket the result is that of cwl_partition_chunks.
+ *
+ *   bucket   [n_seqs] device, values in [0, n_buckets) (e.g. from cwl_bucket_sequences); a value
+ *            outside is taken as the nearest bucket and sets CWL_STATUS_BAD_BUCKET
+ *   n_seqs, n_buckets <= 4096 (else CWL_ERR_UNSUPPORTED)
+ *   workspace >= cwl_aligned_workspace_bytes(n_rows, n_seqs, n_buckets, p) bytes
+ *   the other arguments, the outputs and the status word as for cwl_partition_chunks
+ * ------------------------------------------------------------------------------------------- */
+size_t cwl_aligned_workspace_bytes(int64_t n_rows, int32_t n_seqs, int32_t n_buckets,
+                                   const cwl_chunk_params* p);
+
+cwl_status cwl_partition_chunks_aligned(const float* score, int64_t n_rows, const int32_t* seq_offsets,
+                                        int32_t n_seqs, const int32_t* bucket, int32_t n_buckets,
+                                        const cwl_chunk_params* p /*host*/, int32_t* chunk_offsets,
+                                        int32_t* chunk_start, int32_t* chunk_len, int64_t* chunk_sum,
+                                        int32_t cap, int32_t* status_word, void* workspace,
+                                        size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * cwl_chunkwise_lora_linear -- the chunk-segmented, variable-rank LoRA projection with the

@@ -15,11 +15,13 @@ LIB_PATH = os.environ.get("CWL_LIB_PATH", os.path.join(_HERE, "libcwl.so"))   # 
 
 OK, ERR_NULL, ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = range(7)
 F32, BF16 = 0, 1
-STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS = 1, 2, 4
+STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS, STATUS_BAD_BUCKET = 1, 2, 4, 8
 MAX_LADDER, MAX_RANK = 16, 256
 
 EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_compose_scores",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
+           "cwl_select_ranks_budget", "cwl_bucket_sequences", "cwl_aligned_workspace_bytes",
+           "cwl_partition_chunks_aligned",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed",
@@ -77,6 +79,12 @@ def lib():
     L.cwl_partition_chunks.argtypes = [P, i64, P, i32, ctypes.POINTER(ChunkParams), P, P, P, P,
                                        i32, P, P, sz, P]
     L.cwl_select_ranks.argtypes = [P, P, P, i32, i32, ctypes.POINTER(ctypes.c_float), i32, P, P]
+    L.cwl_select_ranks_budget.argtypes = [P, P, P, i32, i32, ctypes.POINTER(ctypes.c_float), i32, i32, i32, P, P, P]
+    L.cwl_bucket_sequences.argtypes = [P, i64, P, i32, i32, i32, P, P, P, P, P]
+    L.cwl_aligned_workspace_bytes.argtypes = [i64, i32, i32, ctypes.POINTER(ChunkParams)]
+    L.cwl_aligned_workspace_bytes.restype = sz
+    L.cwl_partition_chunks_aligned.argtypes = [P, i64, P, i32, P, i32, ctypes.POINTER(ChunkParams), P, P, P, P,
+                                               i32, P, P, sz, P]
     dp = ctypes.POINTER(LinearDesc)
     for name in ("cwl_packed_weights_bytes", "cwl_linear_workspace_bytes",
                  "cwl_linear_packed_workspace_bytes"):
@@ -92,6 +100,8 @@ def lib():
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
     for name in ("cwl_profile_enable", "cwl_profile_read", "cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
+           "cwl_select_ranks_budget", "cwl_bucket_sequences", "cwl_aligned_workspace_bytes",
+           "cwl_partition_chunks_aligned",
                  "cwl_prepack_weights", "cwl_chunkwise_lora_linear",
                  "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed"):
         getattr(L, name).restype = ctypes.c_int
@@ -203,6 +213,73 @@ def select_ranks(table, thresholds, K, out=None):
                                   _ptr(table["chunk_offsets"]), n_seqs, cap, th, int(K),
                                   _ptr(rank_idx), _stream()), "cwl_select_ranks")
     return rank_idx
+
+
+def select_ranks_budget(table, thresholds, K, k_high, budget, out=None, n_asked=None):
+    """select_ranks with at most `budget` chunks per sequence on a rung >= k_high.  Returns
+    (rank_idx, n_asked), both int32 on the device."""
+    dev = table["chunk_len"].device
+    n_seqs = table["chunk_offsets"].numel() - 1
+    cap = table["cap"]
+    rank_idx = out if out is not None else torch.zeros(max(cap, 1), dtype=torch.int32, device=dev)
+    n_asked = n_asked if n_asked is not None else torch.zeros(max(n_seqs, 1), dtype=torch.int32, device=dev)
+    th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
+    _check(lib().cwl_select_ranks_budget(_ptr(table["chunk_sum"]), _ptr(table["chunk_len"]),
+                                         _ptr(table["chunk_offsets"]), n_seqs, cap, th, int(K), int(k_high),
+                                         int(budget), _ptr(rank_idx), _ptr(n_asked), _stream()),
+           "cwl_select_ranks_budget")
+    return rank_idx, n_asked
+
+
+def bucket_sequences(score, seq_offsets, n_buckets, n_micro=0, out=None):
+    """Percentile buckets (and micro-batches when n_micro > 0) of the sequences of a batch.  Returns a
+    dict of device tensors: seq_sum (int64), order, bucket, micro (int32; micro absent when n_micro == 0)."""
+    assert score.is_cuda and score.dtype == torch.float32 and score.is_contiguous()
+    assert seq_offsets.is_cuda and seq_offsets.dtype == torch.int32
+    dev = score.device
+    n_rows, n_seqs = score.numel(), seq_offsets.numel() - 1
+    if out is None:
+        out = {"seq_sum": torch.zeros(max(n_seqs, 1), dtype=torch.int64, device=dev),
+               "order": torch.zeros(max(n_seqs, 1), dtype=torch.int32, device=dev),
+               "bucket": torch.zeros(max(n_seqs, 1), dtype=torch.int32, device=dev)}
+        if n_micro > 0:
+            out["micro"] = torch.zeros(max(n_seqs, 1), dtype=torch.int32, device=dev)
+    _check(lib().cwl_bucket_sequences(_ptr(score), n_rows, _ptr(seq_offsets), n_seqs, int(n_buckets),
+                                      int(n_micro), _ptr(out["seq_sum"]), _ptr(out["order"]), _ptr(out["bucket"]),
+                                      _ptr(out.get("micro")), _stream()), "cwl_bucket_sequences")
+    return out
+
+
+def partition_chunks_aligned(score, seq_offsets, bucket, n_buckets, l_min, l_max, theta_hard=math.inf,
+                             delta_dev=math.inf, cap=None, out=None):
+    """Chunk table with the boundaries shared inside each bucket; same result layout as partition_chunks."""
+    assert score.is_cuda and score.dtype == torch.float32 and score.is_contiguous()
+    assert seq_offsets.is_cuda and seq_offsets.dtype == torch.int32
+    assert bucket.is_cuda and bucket.dtype == torch.int32
+    dev = score.device
+    n_rows, n_seqs = score.numel(), seq_offsets.numel() - 1
+    p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
+    if out is not None:
+        cap = out["cap"]
+    elif cap is None:
+        cap = n_rows // max(int(l_min), 1) + n_seqs + 1
+    nbytes = lib().cwl_aligned_workspace_bytes(n_rows, n_seqs, int(n_buckets), ctypes.byref(p))
+    out = out if out is not None else {
+        "chunk_offsets": torch.empty(n_seqs + 1, dtype=torch.int32, device=dev),
+        "chunk_start": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_len": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_sum": torch.empty(max(cap, 1), dtype=torch.int64, device=dev),
+        "status_word": torch.empty(1, dtype=torch.int32, device=dev),
+        "cap": int(cap),
+        "_workspace": _ws(nbytes, dev),
+    }
+    ws = out["_workspace"]
+    _check(lib().cwl_partition_chunks_aligned(_ptr(score), n_rows, _ptr(seq_offsets), n_seqs, _ptr(bucket),
+                                              int(n_buckets), ctypes.byref(p), _ptr(out["chunk_offsets"]),
+                                              _ptr(out["chunk_start"]), _ptr(out["chunk_len"]),
+                                              _ptr(out["chunk_sum"]), int(cap), _ptr(out["status_word"]),
+                                              _ptr(ws), ws.numel(), _stream()), "cwl_partition_chunks_aligned")
+    return out
 
 
 class _Desc:

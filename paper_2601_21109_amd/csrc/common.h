@@ -39,6 +39,20 @@ inline int64_t quantise_threshold(float h) {
     return (int64_t)f;
 }
 
+// sequence b: validated (first row, length); a malformed entry yields length 0
+__device__ __forceinline__ void seq_extent(const int32_t* seq_offsets, int32_t b, int64_t n_rows,
+                                           int64_t* base, int64_t* T, bool* bad) {
+    const int64_t s = seq_offsets[b], e = seq_offsets[b + 1];
+    if (s < 0 || e < s || e > n_rows) {
+        *bad = true;
+        *base = 0;
+        *T = 0;
+    } else {
+        *base = s;
+        *T = e - s;
+    }
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
     return __uint_as_float(bits16 << 16);
 }
@@ -46,5 +60,12 @@ __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
 // optional event timing around tracked kernels (profile.hip); no-ops unless enabled
 void prof_begin(int slot, hipStream_t st);
 void prof_end(int slot, hipStream_t st);
+
+// cwl_partition_chunks with the path chosen from a caller-supplied average sequence length
+cwl_status partition_chunks_avg_len(const float* entropy, int64_t n_rows, const int32_t* seq_offsets,
+                                    int32_t n_seqs, const cwl_chunk_params* p, int32_t* chunk_offsets,
+                                    int32_t* chunk_start, int32_t* chunk_len, int64_t* chunk_sum, int32_t cap,
+                                    int32_t* status_word, void* workspace, size_t workspace_bytes, void* stream,
+                                    int64_t avg_len);
 
 }  // namespace cwl

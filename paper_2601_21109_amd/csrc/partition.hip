@@ -32,6 +32,7 @@
 namespace {
 
 using cwl::quantise_score;
+using cwl::seq_extent;
 
 constexpr int kThreads = 256;    // compact and next kernels
 constexpr int kBig = 1024;       // scan and walk kernels: one workgroup per sequence, so a wide one
@@ -107,20 +108,6 @@ __device__ int64_t block_sum_i64(int64_t v, int64_t* smem /*[waves]*/) {
     int64_t tot = 0;
     for (unsigned w = 0; w < blockDim.x / 64; ++w) tot += smem[w];
     return tot;
-}
-
-// sequence b: validated (first row, length); a malformed entry yields length 0
-__device__ __forceinline__ void seq_extent(const int32_t* seq_offsets, int32_t b, int64_t n_rows,
-                                           int64_t* base, int64_t* T, bool* bad) {
-    const int64_t s = seq_offsets[b], e = seq_offsets[b + 1];
-    if (s < 0 || e < s || e > n_rows) {
-        *bad = true;
-        *base = 0;
-        *T = 0;
-    } else {
-        *base = s;
-        *T = e - s;
-    }
 }
 
 __device__ __forceinline__ int64_t chunk_bound(int64_t T, int32_t l_min) {
@@ -530,12 +517,14 @@ extern "C" size_t cwl_partition_workspace_bytes(int64_t n_rows, int32_t n_seqs,
     return part_ws_layout(n_rows, n_seqs, p->l_min, nullptr, nullptr, nullptr);
 }
 
-extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
-                                           const int32_t* seq_offsets, int32_t n_seqs,
-                                           const cwl_chunk_params* p, int32_t* chunk_offsets,
-                                           int32_t* chunk_start, int32_t* chunk_len,
-                                           int64_t* chunk_sum, int32_t cap, int32_t* status_word,
-                                           void* workspace, size_t workspace_bytes, void* stream) {
+// avg_len: what the host knows of the sequence lengths (their average); it picks the path
+cwl_status cwl::partition_chunks_avg_len(const float* entropy, int64_t n_rows,
+                                         const int32_t* seq_offsets, int32_t n_seqs,
+                                         const cwl_chunk_params* p, int32_t* chunk_offsets,
+                                         int32_t* chunk_start, int32_t* chunk_len,
+                                         int64_t* chunk_sum, int32_t cap, int32_t* status_word,
+                                         void* workspace, size_t workspace_bytes, void* stream,
+                                         int64_t avg_len) {
     cwl_status st = check_params(p);
     if (st != CWL_OK) return st;
     if (n_rows < 0 || n_rows >= (int64_t)1 << 31 || n_seqs < 0 || cap < 0) return CWL_ERR_INVALID_ARG;
@@ -581,7 +570,7 @@ extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
         seq_attr_set = true;
     }
     // which path: the host knows only the batch average of the sequence lengths
-    const bool long_sequences = n_rows / n_seqs > 4096;
+    const bool long_sequences = avg_len > 4096;
     cwl::prof_begin(CWL_PROF_PARTITION, s);
     if (!long_sequences) {
         partition_seq_kernel<<<dim3((unsigned)n_seqs), dim3(kThreads), kSeqLdsBytes, s>>>(
@@ -603,6 +592,17 @@ extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
     cwl::prof_end(CWL_PROF_PARTITION, s);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
+}
+
+extern "C" cwl_status cwl_partition_chunks(const float* entropy, int64_t n_rows,
+                                           const int32_t* seq_offsets, int32_t n_seqs,
+                                           const cwl_chunk_params* p, int32_t* chunk_offsets,
+                                           int32_t* chunk_start, int32_t* chunk_len,
+                                           int64_t* chunk_sum, int32_t cap, int32_t* status_word,
+                                           void* workspace, size_t workspace_bytes, void* stream) {
+    return cwl::partition_chunks_avg_len(entropy, n_rows, seq_offsets, n_seqs, p, chunk_offsets, chunk_start,
+                                         chunk_len, chunk_sum, cap, status_word, workspace, workspace_bytes,
+                                         stream, n_seqs > 0 ? n_rows / n_seqs : 0);
 }
 
 extern "C" cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* chunk_len,

@@ -211,3 +211,49 @@ def test_missing_library_is_an_error(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libcwl.so"))
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         B.lib()
+
+
+def test_budget_bucket_aligned_argument_errors(L):
+    th = (ctypes.c_float * 3)(1.0, 2.0, 3.0)
+    f = L.cwl_select_ranks_budget
+    assert f(P(), P(), P(), 1, 8, th, 4, 0, 1, P(), None, None) == B.ERR_INVALID_ARG      # k_high < 1
+    assert f(P(), P(), P(), 1, 8, th, 4, 2, -1, P(), None, None) == B.ERR_INVALID_ARG     # budget < 0
+    assert f(P(), P(), P(), 1, 8, th, 0, 2, 1, P(), None, None) == B.ERR_INVALID_ARG
+    assert f(P(), P(), P(), 1, 8, None, 4, 2, 1, P(), None, None) == B.ERR_NULL
+    assert f(P(), P(), None, 1, 8, th, 4, 2, 1, P(), None, None) == B.ERR_NULL
+    assert f(P(), P(), P(), 1, 8, th, 4, 2, 1, None, None, None) == B.ERR_NULL
+    assert f(P(), P(), P(), 0, 8, th, 4, 2, 1, P(), None, None) == B.OK
+
+    g = L.cwl_bucket_sequences
+    assert g(P(), 64, P(), 2, 0, 0, P(), P(), P(), None, None) == B.ERR_INVALID_ARG        # no buckets
+    assert g(P(), -1, P(), 2, 2, 0, P(), P(), P(), None, None) == B.ERR_INVALID_ARG
+    assert g(P(), 64, P(), 2, 2, 0, P(), P(), P(), P(), None) == B.ERR_INVALID_ARG         # micro without n_micro
+    assert g(P(), 64, P(), 4097, 2, 0, P(), P(), P(), None, None) == B.ERR_UNSUPPORTED
+    assert g(P(), 64, None, 2, 2, 0, P(), P(), P(), None, None) == B.ERR_NULL
+    assert g(None, 64, P(), 2, 2, 0, P(), P(), P(), None, None) == B.ERR_NULL
+    assert g(P(), 64, P(), 2, 2, 0, None, P(), P(), None, None) == B.ERR_NULL
+    assert g(P(), 64, P(), 0, 2, 0, None, None, None, None, None) == B.OK
+
+    h = L.cwl_partition_chunks_aligned
+
+    def call(l_min=4, l_max=8, n_rows=64, n_seqs=2, n_buckets=2, cap=32, ws=P(0x10000), ws_bytes=1 << 20,
+             sc=P(), so=P(), bk=P(), status=P()):
+        p = B.ChunkParams(l_min, l_max, math.inf, math.inf)
+        return h(sc, n_rows, so, n_seqs, bk, n_buckets, ctypes.byref(p), P(), P(), P(), P(), cap, status, ws,
+                 ws_bytes, None)
+
+    assert call(l_min=0) == B.ERR_INVALID_ARG
+    assert call(l_min=4, l_max=6) == B.ERR_INFEASIBLE
+    assert call(n_buckets=0) == B.ERR_INVALID_ARG
+    assert call(n_seqs=4097) == B.ERR_UNSUPPORTED
+    assert call(n_buckets=4097) == B.ERR_UNSUPPORTED
+    assert call(bk=None) == B.ERR_NULL
+    assert call(so=None) == B.ERR_NULL
+    assert call(sc=None) == B.ERR_NULL
+    assert call(status=None) == B.ERR_NULL
+    assert call(ws=None) == B.ERR_NULL
+    assert call(ws=P(0x10010)) == B.ERR_INVALID_ARG
+    assert call(ws_bytes=64) == B.ERR_CAPACITY
+    p = B.ChunkParams(4, 8, 1.0, 1.0)
+    assert L.cwl_aligned_workspace_bytes(1000, 8, 2, ctypes.byref(p)) > L.cwl_partition_workspace_bytes(1000, 2, ctypes.byref(p))
+    assert L.cwl_aligned_workspace_bytes(1000, 8, 0, ctypes.byref(p)) == 0
