@@ -334,6 +334,30 @@ def main():
                                    "rate over both event-timed kernels (a few microseconds of launch gap included)",
                            "weight_bytes": w_bytes, **few}
 
+    # ---- scheduler variants: budget of high-capacity chunks, percentile buckets, aligned chunker ---
+    if not args.no_variants:
+        n_b = max(1, min(4, wl.n_seqs // 2))
+        bk = B.bucket_sequences(h, sod, n_b, 2)
+        tab_a = B.partition_chunks_aligned(h, sod, bk["bucket"], n_b, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+        ri_b, asked = B.select_ranks_budget(table, wl.taus(), K, K - 1, 4)
+        torch.cuda.synchronize()
+        reps = max(args.steps, 10)
+        us = lambda fn: timed(fn, reps, 3)[0] * 1e3
+        out["scheduler_variants"] = {
+            "note": "event-timed back-to-back launches of one call each, microseconds; integer work, launch-bound",
+            "n_buckets": n_b,
+            "partition_chunks_us": us(lambda: B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(),
+                                                                out=table)),
+            "bucket_sequences_us": us(lambda: B.bucket_sequences(h, sod, n_b, 2, out=bk)),
+            "partition_chunks_aligned_us": us(lambda: B.partition_chunks_aligned(
+                h, sod, bk["bucket"], n_b, wl.l_min, wl.l_max, wl.theta(), wl.delta(), out=tab_a)),
+            "select_ranks_us": us(lambda: B.select_ranks(table, wl.taus(), K, out=ri)),
+            "select_ranks_budget_us": us(lambda: B.select_ranks_budget(table, wl.taus(), K, K - 1, 4, out=ri_b,
+                                                                       n_asked=asked)),
+            "chunks_plain": int(table["chunk_offsets"][-1].item()),
+            "chunks_aligned": int(tab_a["chunk_offsets"][-1].item()),
+        }
+
     # ---- every projection of the workload with the same chunk table -------------------------------
     if args.all_projections:
         per = {}

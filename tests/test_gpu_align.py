@@ -40,6 +40,9 @@ CASES = [
     ([977] * 300, 16, 40, 32000),
     ([9000, 100, 100, 100], 16, 256, 32000),
     ([20000, 50, 0, 50, 50], 16, 256, 32000),
+    ([4096] * 16, 32, 512, 32000),          # the shapes of the larger workloads, whole
+    ([2048] * 32, 32, 512, 32000),
+    ([32768], 64, 2048, 128000),
 ]
 
 
