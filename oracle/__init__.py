@@ -19,6 +19,8 @@ from .reference import (  # noqa: F401
     limit_high,
     bucket_sequences,
     partition_aligned,
+    BucketState,
+    stream_step_aligned,
     num_threads,
     set_num_threads,
     bf16_round,

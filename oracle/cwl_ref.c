@@ -23,6 +23,7 @@
  *   - Sec. III-G buckets of sequences by complexity percentile, Sec. IV-D
  *     complexity-balanced micro-batches                                        -> cwl_ref_bucket_sequences
  *   - Sec. III-G chunk boundaries aligned inside a bucket                       -> cwl_ref_partition_aligned
+ *   - the two above one token at a time, for a batch that is being decoded      -> cwl_ref_stream_step_aligned
  *
  * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
  * readings taken are written out step by step in the comments of each function.
@@ -627,4 +628,109 @@ int cwl_ref_partition_aligned(const int32_t* q, const int32_t* seq_offsets, int3
     for (int32_t b = 0; b < n_buckets; ++b) free(bstart[b]);
     free(bstart); free(bcount); free(bend); free(m);
     return n_chunks > cap ? CWL_REF_ERR_CAPACITY : CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Decode step of a batch under the batch controller: boundaries aligned inside each bucket
+ * (Sec. III-G speaks of batched decoding) and the budget of high-capacity chunks (Sec. III-B),
+ * one new token per sequence.  It is cwl_ref_stream_step with two changes.
+ *   Alignment (bucket != NULL): every bucket keeps one open chunk of its own on the bucket's mean
+ * series, state (bn, bsum).  The mean of the step is qm = floor(sum of the members' new scores /
+ * number of members in the call).  The close test of cwl_ref_stream_step is taken once per bucket
+ * on (bn, bsum, qm); when it fires, every member closes its own open chunk (if it has one) in front
+ * of its new token.  The bucket's chunk then takes qm as the members' chunks take their own score.
+ * A bucket without members in the call keeps its state.  With bucket == NULL every sequence decides
+ * on its own open chunk as in cwl_ref_stream_step.
+ *   Budget (n_high != NULL): n_high[s] counts the closed chunks of sequence s whose last token had
+ * a rung of at least k_high before any lowering, which is the chunk's rung in the batch form.  The
+ * rung in force for a token is the selector's rule on the open chunk, lowered to k_high - 1 when it
+ * is at least k_high and n_high[s] >= budget.  k_prev, the outgoing rung of the cross-fade, is the
+ * rung in force at the previous chunk's last token, lowered or not.
+ * Fed token by token to sequences of equal length, this places the boundaries of
+ * cwl_ref_partition_aligned (where the end cannot matter) and ends every chunk on the rung that
+ * cwl_ref_select followed by cwl_ref_limit_high gives it.
+ * ------------------------------------------------------------------------------------------ */
+static int32_t rung_of(int64_t S, int64_t n, const int64_t* tau_q, int32_t K) {
+    int32_t k = 0;
+    for (int32_t j = 0; j < K - 1; ++j)
+        if (S >= tau_q[j] * n) ++k;
+    return k;
+}
+
+static int close_test(int64_t n, int64_t S, int64_t qe, int32_t l_min, int32_t l_max,
+                      int64_t theta_q, int64_t delta_q) {
+    if (n < l_min) return 0;
+    int64_t d = qe * n - S;
+    if (d < 0) d = -d;
+    return n == l_max || S >= theta_q * n || qe >= theta_q || d > delta_q * n;
+}
+
+int cwl_ref_stream_step_aligned(const int32_t* q_new, int32_t n_seqs, int32_t l_min, int32_t l_max,
+                                int64_t theta_q, int64_t delta_q, const int64_t* tau_q, int32_t K,
+                                const int32_t* ranks, const float* scales, int32_t blend_w,
+                                const int32_t* bucket, int32_t n_buckets, int32_t* bk_n, int64_t* bk_sum,
+                                int32_t k_high, int32_t budget, int32_t* n_high,
+                                int32_t* st_n, int64_t* st_sum, int32_t* st_k_cur, int32_t* st_k_prev,
+                                int32_t* st_chunks, int64_t* st_pos,
+                                int32_t* r_cur, double* g_cur, int32_t* r_prev, double* g_prev,
+                                int32_t* closed_len, int64_t* closed_sum) {
+    if (l_min < 1 || l_max < l_min || K < 1 || blend_w < 0) return CWL_REF_ERR_INVALID;
+    if ((int64_t)l_max < 2 * (int64_t)l_min - 1) return CWL_REF_ERR_INFEASIBLE;
+    if (n_high && (k_high < 1 || budget < 0)) return CWL_REF_ERR_INVALID;
+    int* bclose = NULL;
+    if (bucket) {
+        if (n_buckets < 1) return CWL_REF_ERR_INVALID;
+        for (int32_t s = 0; s < n_seqs; ++s)
+            if (bucket[s] < 0 || bucket[s] >= n_buckets) return CWL_REF_ERR_INVALID;
+        bclose = (int*)calloc((size_t)n_buckets, sizeof(int));
+        for (int32_t b = 0; b < n_buckets; ++b) {
+            int64_t tot = 0, members = 0;
+            for (int32_t s = 0; s < n_seqs; ++s)
+                if (bucket[s] == b) { tot += q_new[s]; ++members; }
+            if (members == 0) continue;
+            const int64_t qm = tot / members;
+            bclose[b] = close_test(bk_n[b], bk_sum[b], qm, l_min, l_max, theta_q, delta_q);
+            if (bclose[b]) { bk_n[b] = 0; bk_sum[b] = 0; }
+            bk_n[b] += 1;
+            bk_sum[b] += qm;
+        }
+    }
+    for (int32_t s = 0; s < n_seqs; ++s) {
+        const int64_t qe = q_new[s];
+        closed_len[s] = 0;
+        closed_sum[s] = 0;
+        const int closes = bucket ? bclose[bucket[s]]
+                                  : close_test(st_n[s], st_sum[s], qe, l_min, l_max, theta_q, delta_q);
+        if (closes && st_n[s] > 0) {
+            if (n_high && rung_of(st_sum[s], st_n[s], tau_q, K) >= k_high) n_high[s] += 1;
+            closed_len[s] = st_n[s];
+            closed_sum[s] = st_sum[s];
+            st_k_prev[s] = st_k_cur[s];
+            st_chunks[s] += 1;
+            st_n[s] = 0;
+            st_sum[s] = 0;
+        }
+        st_n[s] += 1;
+        st_sum[s] += qe;
+        st_pos[s] += 1;
+        int32_t k = rung_of(st_sum[s], st_n[s], tau_q, K);
+        if (n_high && k >= k_high && n_high[s] >= budget) k = k_high - 1;
+        st_k_cur[s] = k;
+        const int32_t rc = ranks[k];
+        const double sc = rc > 0 ? (double)scales[k] : 0.0;
+        const int32_t j_off = st_n[s] - 1;
+        if (st_chunks[s] == 0 || blend_w == 0 || j_off >= blend_w) {
+            r_cur[s] = rc;  g_cur[s] = sc;
+            r_prev[s] = 0;  g_prev[s] = 0.0;
+        } else {
+            const int32_t kp = st_k_prev[s];
+            const int32_t rp = ranks[kp];
+            const double sp = rp > 0 ? (double)scales[kp] : 0.0;
+            const double lambda = (double)(j_off + 1) / (double)(blend_w + 1);
+            r_cur[s] = rc;  g_cur[s] = lambda * sc;
+            r_prev[s] = rp; g_prev[s] = (1.0 - lambda) * sp;
+        }
+    }
+    free(bclose);
+    return CWL_REF_OK;
 }

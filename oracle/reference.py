@@ -64,6 +64,10 @@ def _load():
     lib.cwl_ref_bucket_sequences.restype = ctypes.c_int
     lib.cwl_ref_partition_aligned.argtypes = [P, P, i32, P, i32, i32, i32, i64, i64, P, P, P, P, i32]
     lib.cwl_ref_partition_aligned.restype = ctypes.c_int
+    lib.cwl_ref_stream_step_aligned.argtypes = [P, i32, i32, i32, i64, i64, P, i32, P, P, i32,
+                                                P, i32, P, P, i32, i32, P,
+                                                P, P, P, P, P, P, P, P, P, P, P, P]
+    lib.cwl_ref_stream_step_aligned.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -211,6 +215,48 @@ def stream_step(state, q_new, l_min, l_max, theta_q, delta_q, tau_q, ranks, scal
                                      _ptr(state.chunks), _ptr(state.pos),
                                      _ptr(out["r_cur"]), _ptr(out["g_cur"]), _ptr(out["r_prev"]),
                                      _ptr(out["g_prev"]), _ptr(out["closed_len"]), _ptr(out["closed_sum"]))
+    return st, out
+
+
+class BucketState:
+    """Open chunk of every bucket's mean series (all zero at start)."""
+
+    def __init__(self, n_buckets):
+        self.n = np.zeros(n_buckets, np.int32)
+        self.sum = np.zeros(n_buckets, np.int64)
+
+
+def stream_step_aligned(state, q_new, l_min, l_max, theta_q, delta_q, tau_q, ranks, scales, blend_w,
+                        bucket=None, bucket_state=None, k_high=1, budget=0, n_high=None):
+    """One decode step of a batch with boundaries shared inside each bucket (``bucket`` + ``bucket_state``,
+    both or neither) and a budget of high-capacity chunks (``n_high``: int32 counters, updated in place,
+    or None for no budget).  Returns (status, dict) like stream_step."""
+    qn = _arr(q_new, np.int32).ravel()
+    B = qn.shape[0]
+    assert state.n.shape[0] == B
+    tq = _arr(tau_q, np.int64).ravel()
+    rk = _arr(ranks, np.int32).ravel()
+    sc = _arr(scales, np.float32).ravel()
+    assert rk.shape[0] == tq.shape[0] + 1 == sc.shape[0]
+    assert (bucket is None) == (bucket_state is None)
+    null = ctypes.c_void_p(0)
+    if bucket is not None:
+        bk = _arr(bucket, np.int32).ravel()
+        assert bk.shape[0] == B
+        bk_args = (_ptr(bk), bucket_state.n.shape[0], _ptr(bucket_state.n), _ptr(bucket_state.sum))
+    else:
+        bk_args = (null, 0, null, null)
+    if n_high is not None:
+        assert n_high.dtype == np.int32 and n_high.shape[0] == B
+    out = {"r_cur": np.zeros(B, np.int32), "g_cur": np.zeros(B, np.float64),
+           "r_prev": np.zeros(B, np.int32), "g_prev": np.zeros(B, np.float64),
+           "closed_len": np.zeros(B, np.int32), "closed_sum": np.zeros(B, np.int64)}
+    st = _load().cwl_ref_stream_step_aligned(
+        _ptr(qn), B, int(l_min), int(l_max), int(theta_q), int(delta_q), _ptr(tq), rk.shape[0], _ptr(rk), _ptr(sc),
+        int(blend_w), *bk_args, int(k_high), int(budget), null if n_high is None else _ptr(n_high),
+        _ptr(state.n), _ptr(state.sum), _ptr(state.k_cur), _ptr(state.k_prev), _ptr(state.chunks), _ptr(state.pos),
+        _ptr(out["r_cur"]), _ptr(out["g_cur"]), _ptr(out["r_prev"]), _ptr(out["g_prev"]),
+        _ptr(out["closed_len"]), _ptr(out["closed_sum"]))
     return st, out
 
 

@@ -227,3 +227,143 @@ def test_aligned_errors(oracle):
     assert oracle.partition_aligned(q, [0, 10, 20], [0, 1], 2, 3, 4, 100, 100)[0] == 3     # infeasible bounds
     st, al = oracle.partition_aligned(q, [0, 10, 20], [0, 1], 2, 2, 4, 100, 100, cap=3)
     assert st == 4                                                                        # capacity
+
+
+# ---------------------------------------------------------------- decode step of a batch: aligned, budgeted
+
+LADDER = ([0, 4, 8, 16], [0.0, 4.0, 2.0, 1.0])
+TAUS = [1000, 2500, 4200]
+
+
+def level_scores(rng, n_seqs, T):
+    """Equal-length sequences made of spans of one difficulty level each, scaled per sequence."""
+    q = np.empty((n_seqs, T), np.int32)
+    for s in range(n_seqs):
+        row = np.concatenate([rng.choice([600, 2000, 5000]) + rng.randint(-300, 300, size=rng.randint(5, 50))
+                              for _ in range(T // 5 + 1)])[:T]
+        q[s] = np.clip(row * (0.6 + 0.1 * s), 0, 1 << 20)
+    return q
+
+
+def feed(oracle, q, l_min, l_max, theta, delta, w, bucket=None, n_buckets=0, k_high=1, budget=0, use_budget=False):
+    """Feed a batch token by token.  Returns per sequence: closed chunks (start, len, sum), rung in force
+    at every token, gates."""
+    n_seqs, T = q.shape
+    st = oracle.StreamState(n_seqs)
+    bst = oracle.BucketState(n_buckets) if bucket is not None else None
+    n_high = np.zeros(n_seqs, np.int32) if use_budget else None
+    chunks = [[] for _ in range(n_seqs)]
+    rungs = np.zeros((n_seqs, T), np.int32)
+    gates = []
+    for t in range(T):
+        code, out = oracle.stream_step_aligned(st, q[:, t], l_min, l_max, theta, delta, TAUS, *LADDER, w,
+                                               bucket=bucket, bucket_state=bst, k_high=k_high, budget=budget,
+                                               n_high=n_high)
+        assert code == 0
+        for s in range(n_seqs):
+            n = int(out["closed_len"][s])
+            if n:
+                chunks[s].append((t - n, n, int(out["closed_sum"][s])))
+        rungs[:, t] = st.k_cur
+        gates.append({k: v.copy() for k, v in out.items()})
+    return chunks, rungs, gates, st, n_high
+
+
+def test_step_without_buckets_and_budget_is_the_plain_step(oracle):
+    rng = np.random.RandomState(1)
+    q = level_scores(rng, 4, 300)
+    st0 = oracle.StreamState(4)
+    st1 = oracle.StreamState(4)
+    for t in range(300):
+        c0, o0 = oracle.stream_step(st0, q[:, t], 5, 24, 4000, 1200, TAUS, *LADDER, 3)
+        c1, o1 = oracle.stream_step_aligned(st1, q[:, t], 5, 24, 4000, 1200, TAUS, *LADDER, 3)
+        assert c0 == 0 and c1 == 0
+        for k in o0:
+            assert o0[k].tolist() == o1[k].tolist(), (t, k)
+    for f in ("n", "sum", "k_cur", "k_prev", "chunks", "pos"):
+        assert getattr(st0, f).tolist() == getattr(st1, f).tolist()
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_aligned_budgeted_step_reproduces_the_batch_forms(oracle, seed):
+    """Token by token on equal-length sequences: the boundaries of the aligned batch chunker wherever the
+    end cannot matter, and at every chunk's last token the rung of select followed by the budget."""
+    rng = np.random.RandomState(10 + seed)
+    n_seqs, T = 6, 500
+    l_min, l_max = [(4, 9), (8, 40), (3, 5), (6, 30)][seed]
+    theta, delta, k_high, budget = 4500, 1300, 2, [0, 1, 3, 5][seed]
+    q = level_scores(rng, n_seqs, T)
+    bucket = np.array([0, 1, 0, 2, 1, 0], np.int32)
+    so = np.arange(n_seqs + 1) * T
+    code, tab = oracle.partition_aligned(q.ravel(), so, bucket, 3, l_min, l_max, theta, delta)
+    assert code == 0
+    ranks = oracle.select(tab["chunk_sum"], tab["chunk_len"], TAUS)
+    code, limited, _ = oracle.limit_high(ranks, tab["chunk_offsets"], k_high, budget)
+    assert code == 0
+    chunks, rungs, _, _, n_high = feed(oracle, q, l_min, l_max, theta, delta, 2, bucket, 3, k_high, budget, True)
+    lowered = 0
+    for s in range(n_seqs):
+        a, b = tab["chunk_offsets"][s], tab["chunk_offsets"][s + 1]
+        batch = [(int(tab["chunk_start"][c]) - s * T, int(tab["chunk_len"][c]), int(tab["chunk_sum"][c]), int(limited[c]),
+                  int(ranks[c])) for c in range(a, b)]
+        safe = [c for c in batch if c[0] + l_max <= T - l_min]
+        assert len(safe) > 5
+        assert chunks[s][:len(safe)] == [c[:3] for c in safe]
+        assert [int(rungs[s, c[0] + c[1] - 1]) for c in safe] == [c[3] for c in safe]
+        lowered += sum(1 for c in safe if c[3] != c[4])
+        assert n_high[s] >= sum(1 for c in safe if c[4] >= k_high)
+    if budget < 5:
+        assert lowered > 0          # the budget did bite somewhere
+
+
+def test_members_of_a_bucket_close_together(oracle):
+    rng = np.random.RandomState(5)
+    q = level_scores(rng, 5, 200)
+    bucket = np.array([1, 0, 1, 1, 0], np.int32)
+    chunks, _, _, _, _ = feed(oracle, q, 4, 16, 4500, 1300, 0, bucket, 2)
+    for members in ([0, 2, 3], [1, 4]):
+        first = [(c[0], c[1]) for c in chunks[members[0]]]
+        for s in members[1:]:
+            assert [(c[0], c[1]) for c in chunks[s]] == first
+    assert [(c[0], c[1]) for c in chunks[0]] != [(c[0], c[1]) for c in chunks[1]]
+
+
+def test_aligned_step_hand_worked(oracle):
+    # one bucket of two sequences, L = (2, 4), theta = 100, no deviation test, rungs at means 50 / 150 / 250,
+    # k_high = 2 with a budget of one chunk
+    a = [10, 10, 300, 10, 10, 10]
+    b = [11, 20, 300, 300, 10, 10]
+    # means 10, 15, 300, 155, 10, 10: [0,2) closes in front of t=2 (its mean token is hard); [2,4): bucket mean
+    # (300 + 155) / 2 >= 100 closes in front of t=4
+    st = oracle.StreamState(2)
+    bst = oracle.BucketState(1)
+    n_high = np.zeros(2, np.int32)
+    closed, rung = [], []
+    for t in range(6):
+        code, out = oracle.stream_step_aligned(st, [a[t], b[t]], 2, 4, 100, INF_Q, [50, 150, 250], *LADDER, 0,
+                                               bucket=[0, 0], bucket_state=bst, k_high=2, budget=1, n_high=n_high)
+        assert code == 0
+        closed.append(out["closed_len"].tolist())
+        rung.append(st.k_cur.tolist())
+    assert closed == [[0, 0], [0, 0], [2, 2], [0, 0], [2, 2], [0, 0]]
+    # sequence a: chunk [2,4) has means 300, 155 -> rungs 3, 2 (first asker, kept); chunk [4,6): mean 10 -> 0
+    # sequence b: chunk [2,4) means 300, 300 -> 3, 3 (kept, it is the first asker)
+    assert [r[0] for r in rung] == [0, 0, 3, 2, 0, 0]
+    assert [r[1] for r in rung] == [0, 0, 3, 3, 0, 0]
+    assert n_high.tolist() == [1, 1]
+    # a further hard chunk is now over budget in both sequences: lowered to rung 1
+    for t in range(2):
+        code, out = oracle.stream_step_aligned(st, [400, 400], 2, 4, 100, INF_Q, [50, 150, 250], *LADDER, 0,
+                                               bucket=[0, 0], bucket_state=bst, k_high=2, budget=1, n_high=n_high)
+        assert st.k_cur.tolist() == [1, 1]
+        assert out["r_cur"].tolist() == [4, 4] and out["g_cur"].tolist() == [4.0, 4.0]
+
+
+def test_aligned_step_errors(oracle):
+    st = oracle.StreamState(2)
+    bst = oracle.BucketState(2)
+    assert oracle.stream_step_aligned(st, [1, 2], 2, 4, 100, 100, TAUS, *LADDER, 0, bucket=[0, 2],
+                                      bucket_state=bst)[0] != 0
+    assert oracle.stream_step_aligned(st, [1, 2], 2, 4, 100, 100, TAUS, *LADDER, 0, k_high=0, budget=1,
+                                      n_high=np.zeros(2, np.int32))[0] != 0
+    assert oracle.stream_step_aligned(st, [1, 2], 3, 4, 100, 100, TAUS, *LADDER, 0)[0] == 3
