@@ -334,6 +334,43 @@ cwl_status cwl_stream_step(const float* entropy, int32_t n_seqs, const cwl_chunk
                            int32_t* status_word, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_stream_step_aligned -- cwl_stream_step for a batch under the batch controller: boundaries
+ * aligned inside each bucket (Sec. III-G, which speaks of batched decoding) and the budget of
+ * high-capacity chunks (Sec. III-B).  Two changes to cwl_stream_step:
+ *   bucket != NULL: every bucket keeps an open chunk of its own on the bucket's mean series
+ * (bucket_state: n tokens, sum).  With qm = floor(sum of the members' new quantised scores / number
+ * of members in the call), the close test of cwl_stream_step is taken once per bucket on
+ * (n, sum, qm); when it fires every member closes its own open chunk, if it has one, in front of
+ * its new token; the bucket's chunk then takes qm.  A bucket with no member in the call keeps its
+ * state.  Sequences of equal length fed token by token get the boundaries of
+ * cwl_partition_chunks_aligned wherever the end cannot matter.
+ *   n_high != NULL: n_high[s] counts the closed chunks of sequence s whose last token had a rung
+ * >= k_high before any lowering (the chunk's rung in the batch form).  The rung in force for a
+ * token is lowered to k_high - 1 when it is >= k_high and n_high[s] >= budget, so every chunk ends
+ * on the rung cwl_select_ranks_budget gives it.
+ * With bucket == NULL and n_high == NULL this is cwl_stream_step.
+ *
+ *   bucket        [n_seqs] device or NULL; values in [0, n_buckets), else the nearest bucket and
+ *                 CWL_STATUS_BAD_BUCKET; needs n_seqs, n_buckets <= 4096 (else CWL_ERR_UNSUPPORTED)
+ *   bucket_state  [n_buckets] in/out, all-zero bytes at the start
+ *   k_high >= 1, budget >= 0 (read when n_high != NULL)     n_high  [n_seqs] in/out, zero at the start
+ *   the other arguments as for cwl_stream_step
+ * ------------------------------------------------------------------------------------------- */
+typedef struct {
+    int64_t sum;        /* sum of the mean series over the bucket's open chunk */
+    int32_t n;          /* tokens in it                                        */
+    int32_t reserved;
+} cwl_bucket_state;
+
+cwl_status cwl_stream_step_aligned(const float* entropy, int32_t n_seqs, const cwl_chunk_params* p /*host*/,
+                                   const float* thresholds /*host*/, int32_t K, const int32_t* ranks /*host*/,
+                                   const float* scales /*host*/, int32_t blend_w, const int32_t* bucket,
+                                   int32_t n_buckets, cwl_bucket_state* bucket_state, int32_t k_high,
+                                   int32_t budget, int32_t* n_high, cwl_stream_state* state,
+                                   cwl_token_gate* gate, int32_t* closed_len, int64_t* closed_sum,
+                                   int32_t* status_word, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * cwl_gated_lora_linear_packed -- the layer of cwl_chunkwise_lora_linear for rows that bring their
  * own gate entry (Sec. III-C sliced ladder, Sec. III-D cross-fade, weights already decided), e.g.
  * the one token per sequence of a decode step:

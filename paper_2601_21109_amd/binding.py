@@ -24,7 +24,8 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_partition_chunks_aligned",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
-           "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed",
+           "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_stream_step_aligned",
+           "cwl_gated_lora_linear_packed",
            "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
 PROF_SLOTS = 6
@@ -96,6 +97,9 @@ def lib():
     fp = ctypes.POINTER(ctypes.c_float)
     L.cwl_stream_step.argtypes = [P, i32, ctypes.POINTER(ChunkParams), fp, i32, ctypes.POINTER(i32), fp,
                                   i32, P, P, P, P, P, P]
+    L.cwl_stream_step_aligned.argtypes = [P, i32, ctypes.POINTER(ChunkParams), ctypes.POINTER(ctypes.c_float), i32,
+                                          ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), i32,
+                                          P, i32, P, i32, i32, P, P, P, P, P, P, P]
     L.cwl_gated_lora_linear_packed.argtypes = [dp, P, P, P, P, P, sz, P]
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -413,6 +417,45 @@ def stream_step(entropy, state, l_min, l_max, theta_hard, delta_dev, thresholds,
                                  _ptr(state), _ptr(out["gate"]), _ptr(out["closed_len"]),
                                  _ptr(out["closed_sum"]), _ptr(out["status_word"]), _stream()),
            "cwl_stream_step")
+    return out
+
+
+def bucket_state(n_buckets, device):
+    """Zeroed open chunks of the buckets' mean series: int64 [n_buckets, 2], one cwl_bucket_state per row
+    (sum, n in the low half of the second word)."""
+    return torch.zeros((n_buckets, 2), dtype=torch.int64, device=device)
+
+
+def stream_step_aligned(entropy, state, l_min, l_max, theta_hard, delta_dev, thresholds, ranks, scales, blend_w,
+                        bucket=None, bucket_st=None, k_high=1, budget=0, n_high=None, out=None):
+    """stream_step for a batch under the batch controller: `bucket` (int32 [B]) + `bucket_st` (from
+    bucket_state) share the close decision inside each bucket; `n_high` (int32 [B], zero at the start,
+    updated in place) applies a budget of `budget` chunks per sequence on rungs >= k_high."""
+    assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
+    assert state.is_cuda and state.dtype == torch.int64 and state.is_contiguous()
+    B, dev, K = entropy.numel(), entropy.device, len(ranks)
+    assert state.shape == (B, 4)
+    n_buckets = 0
+    if bucket is not None:
+        assert bucket.is_cuda and bucket.dtype == torch.int32 and bucket.numel() == B
+        assert bucket_st is not None and bucket_st.dtype == torch.int64 and bucket_st.is_contiguous()
+        n_buckets = bucket_st.shape[0]
+    if n_high is not None:
+        assert n_high.is_cuda and n_high.dtype == torch.int32 and n_high.numel() == B
+    if out is None:
+        out = {"gate": torch.empty((B, 4), dtype=torch.int32, device=dev),
+               "closed_len": torch.empty(B, dtype=torch.int32, device=dev),
+               "closed_sum": torch.empty(B, dtype=torch.int64, device=dev),
+               "status_word": torch.zeros(1, dtype=torch.int32, device=dev)}
+    p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
+    th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
+    rk = (ctypes.c_int32 * max(K, 1))(*[int(r) for r in ranks])
+    sc = (ctypes.c_float * max(K, 1))(*[float(v) for v in scales])
+    _check(lib().cwl_stream_step_aligned(_ptr(entropy), B, ctypes.byref(p), th, K, rk, sc, int(blend_w),
+                                         _ptr(bucket), n_buckets, _ptr(bucket_st), int(k_high), int(budget),
+                                         _ptr(n_high), _ptr(state), _ptr(out["gate"]), _ptr(out["closed_len"]),
+                                         _ptr(out["closed_sum"]), _ptr(out["status_word"]), _stream()),
+           "cwl_stream_step_aligned")
     return out
 
 

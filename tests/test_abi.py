@@ -257,3 +257,30 @@ def test_budget_bucket_aligned_argument_errors(L):
     p = B.ChunkParams(4, 8, 1.0, 1.0)
     assert L.cwl_aligned_workspace_bytes(1000, 8, 2, ctypes.byref(p)) > L.cwl_partition_workspace_bytes(1000, 2, ctypes.byref(p))
     assert L.cwl_aligned_workspace_bytes(1000, 8, 0, ctypes.byref(p)) == 0
+
+
+def test_aligned_stream_step_argument_errors(L):
+    f = L.cwl_stream_step_aligned
+    th = (ctypes.c_float * 2)(1.0, 2.0)
+    rk = (ctypes.c_int32 * 3)(4, 8, 16)
+    sc = (ctypes.c_float * 3)(1.0, 1.0, 1.0)
+
+    def call(n_seqs=4, l_min=2, l_max=4, bucket=P(), n_buckets=2, bst=P(), k_high=1, budget=0, n_high=P(),
+             state=P(), gate=P(), status=P(), ent=P()):
+        p = B.ChunkParams(l_min, l_max, math.inf, math.inf)
+        return f(ent, n_seqs, ctypes.byref(p), th, 3, rk, sc, 1, bucket, n_buckets, bst, k_high, budget, n_high,
+                 state, gate, None, None, status, None)
+
+    assert call(l_min=3, l_max=4) == B.ERR_INFEASIBLE
+    assert call(n_buckets=0) == B.ERR_INVALID_ARG
+    assert call(bst=None) == B.ERR_NULL
+    assert call(n_seqs=4097) == B.ERR_UNSUPPORTED
+    assert call(n_buckets=4097) == B.ERR_UNSUPPORTED
+    assert call(k_high=0) == B.ERR_INVALID_ARG
+    assert call(budget=-1) == B.ERR_INVALID_ARG
+    assert call(k_high=0, n_high=None, bucket=None, n_seqs=0) == B.OK     # budget arguments unread without n_high
+    assert call(state=None) == B.ERR_NULL
+    assert call(gate=None) == B.ERR_NULL
+    assert call(status=None) == B.ERR_NULL
+    assert call(ent=None) == B.ERR_NULL
+    assert call(n_seqs=0) == B.OK

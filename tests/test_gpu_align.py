@@ -200,3 +200,82 @@ def test_aligned_table_feeds_the_linear():
     ref = O.linear(x.numpy(), W.numpy(), A.numpy(), Bm.numpy(), ranks, scales, 2, so, tab["chunk_offsets"],
                    tab["chunk_start"], tab["chunk_len"], tab["rank_idx"])
     assert rel_err(host(y), ref) <= TOL_F32
+
+
+# ---------------------------------------------------------------- decode step of a batch: aligned, budgeted
+
+def gate_fields(gate):
+    g = gate.cpu().numpy()
+    return g[:, 0].copy(), g[:, 1].copy(), g[:, 2].copy().view(np.float32), g[:, 3].copy().view(np.float32)
+
+
+@pytest.mark.parametrize("n_seqs,n_buckets,steps,l_min,l_max,w,ladder,k_high,budget", [
+    (37, 3, 300, 4, 9, 2, ([4, 8, 16], [4.0, 2.0, 1.0]), 2, 3),
+    (300, 7, 120, 8, 64, 4, ([8, 16, 32, 64], [2.0, 1.0, 0.5, 0.25]), 2, 1),
+    (64, 1, 200, 3, 40, 3, ([0, 4, 16], [0.0, 2.0, 1.0]), 1, 0),
+    (4096, 4096, 12, 2, 4, 1, ([4, 8], [1.0, 0.5]), 1, 2),         # the largest batch the call takes
+    (9, 12, 150, 4, 16, 2, ([4, 8, 16], [4.0, 2.0, 1.0]), 2, None),  # empty buckets, no budget
+    (50, 0, 150, 4, 16, 2, ([4, 8, 16], [4.0, 2.0, 1.0]), 2, 2),     # no buckets, budget only
+])
+def test_aligned_stream_step_matches_oracle(n_seqs, n_buckets, steps, l_min, l_max, w, ladder, k_high, budget):
+    ranks, scales = ladder
+    K = len(ranks)
+    vocab_ln = math.log(32000.0)
+    theta, delta = 0.9 * vocab_ln, 0.3 * vocab_ln
+    taus = [vocab_ln * f for f in np.linspace(0.3, 0.9, K - 1)] if K > 1 else []
+    rng = np.random.RandomState(n_seqs + 1)
+    level = rng.choice([0.15, 0.5, 0.95], size=(n_seqs, steps // 10 + 1)).repeat(10, axis=1)[:, :steps]
+    h_all = (level * vocab_ln + rng.uniform(-0.4, 0.4, size=(n_seqs, steps))).astype(np.float32)
+    use_b = n_buckets > 0
+    bucket = rng.randint(0, max(n_buckets, 1), n_seqs).astype(np.int32) if use_b else None
+    bucket_d = torch.from_numpy(bucket).to(DEV) if use_b else None
+    bst_d = B.bucket_state(n_buckets, DEV) if use_b else None
+    n_high_d = torch.zeros(n_seqs, dtype=torch.int32, device=DEV) if budget is not None else None
+    state = B.stream_state(n_seqs, DEV)
+    dev_out = []
+    for t in range(steps):
+        h = torch.from_numpy(h_all[:, t].copy()).to(DEV)
+        out = B.stream_step_aligned(h, state, l_min, l_max, theta, delta, taus, ranks, scales, w, bucket=bucket_d,
+                                    bucket_st=bst_d, k_high=k_high, budget=budget or 0, n_high=n_high_d)
+        dev_out.append({k: v.clone() for k, v in out.items()})
+    torch.cuda.synchronize()
+    ost = O.StreamState(n_seqs)
+    obst = O.BucketState(n_buckets) if use_b else None
+    o_high = np.zeros(n_seqs, np.int32) if budget is not None else None
+    tq = [O.quantise_threshold(t) for t in taus]
+    for t in range(steps):
+        q, _ = O.quantise(h_all[:, t])
+        code, ref = O.stream_step_aligned(ost, q, l_min, l_max, O.quantise_threshold(theta),
+                                          O.quantise_threshold(delta), tq, ranks, scales, w, bucket=bucket,
+                                          bucket_state=obst, k_high=k_high, budget=budget or 0, n_high=o_high)
+        assert code == 0
+        r_cur, r_prev, g_cur, g_prev = gate_fields(dev_out[t]["gate"])
+        assert np.array_equal(r_cur, ref["r_cur"]) and np.array_equal(r_prev, ref["r_prev"]), t
+        assert np.array_equal(dev_out[t]["closed_len"].cpu().numpy(), ref["closed_len"]), t
+        assert np.array_equal(dev_out[t]["closed_sum"].cpu().numpy(), ref["closed_sum"]), t
+        np.testing.assert_allclose(g_cur, ref["g_cur"], rtol=1e-6, atol=0)
+        np.testing.assert_allclose(g_prev, ref["g_prev"], rtol=1e-6, atol=0)
+        assert int(dev_out[t]["status_word"].item()) == 0
+    f = B.stream_state_fields(state)
+    assert np.array_equal(f["n"], ost.n) and np.array_equal(f["sum"], ost.sum)
+    assert np.array_equal(f["k_cur"], ost.k_cur) and np.array_equal(f["n_chunks"], ost.chunks)
+    if use_b:
+        bs = bst_d.cpu().numpy()
+        assert np.array_equal(bs[:, 0], obst.sum) and np.array_equal((bs[:, 1] & 0xffffffff).astype(np.int32), obst.n)
+    if budget is not None:
+        assert np.array_equal(n_high_d.cpu().numpy(), o_high)
+    assert ost.chunks.sum() > 0
+
+
+def test_aligned_stream_step_flags():
+    state = B.stream_state(3, DEV)
+    bst = B.bucket_state(2, DEV)
+    h = torch.tensor([1.0, float("nan"), 2.0], device=DEV)
+    bucket = torch.tensor([0, 5, -1], dtype=torch.int32, device=DEV)
+    out = B.stream_step_aligned(h, state, 2, 4, math.inf, math.inf, [1.5], [4, 8], [1.0, 0.5], 0, bucket=bucket,
+                                bucket_st=bst)
+    torch.cuda.synchronize()
+    assert int(out["status_word"].item()) == B.STATUS_NAN_SCORE | B.STATUS_BAD_BUCKET
+    # buckets taken as 0, 1, 0: bucket 0 sees (1024 + 2048) // 2, bucket 1 the NaN scored as 0
+    bs = bst.cpu().numpy()
+    assert bs[:, 0].tolist() == [1536, 0] and (bs[:, 1] & 0xffffffff).tolist() == [1, 1]
