@@ -21,6 +21,7 @@ from .reference import (  # noqa: F401
     partition_aligned,
     BucketState,
     stream_step_aligned,
+    build_ladder,
     num_threads,
     set_num_threads,
     bf16_round,

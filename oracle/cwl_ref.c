@@ -24,6 +24,8 @@
  *     complexity-balanced micro-batches                                        -> cwl_ref_bucket_sequences
  *   - Sec. III-G chunk boundaries aligned inside a bucket                       -> cwl_ref_partition_aligned
  *   - the two above one token at a time, for a batch that is being decoded      -> cwl_ref_stream_step_aligned
+ *   - Sec. III-C the ladder itself, one SVD of the adapter update: in reference.py (build_ladder),
+ *     a float64 library SVD of the product written out
  *
  * The paper gives no formulas for the chunk rule, the rung map or the cross-fade weights; the
  * readings taken are written out step by step in the comments of each function.

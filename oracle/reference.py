@@ -337,6 +337,35 @@ def partition_aligned(q, seq_offsets, bucket, n_buckets, l_min, l_max, theta_q, 
                 "chunk_len": length[:n].copy(), "chunk_sum": csum[:n].copy()}
 
 
+def build_ladder(A, B):
+    """Rank ladder of the adapter update by one SVD (Sec. III-C: the ladder is obtained once by an SVD of
+    the adapter matrix, and a rung slices its first r directions).
+
+    dW = A B = U diag(sigma) V^T with sigma descending (float64 library SVD of the product written out).
+    Reading: the two factors share the singular values evenly, A' = U[:, :r] diag(sqrt(sigma)),
+    B' = diag(sqrt(sigma)) V^T[:r, :], so that A'[:, :k] B'[:k, :] is the best rank-k approximation of
+    dW for every k and A' B' = dW.  Directions whose sigma is below 1e-12 sigma_max carry nothing and
+    are set to zero.  Singular vectors are fixed only up to sign (and rotation inside equal singular
+    values); sigma and the truncated products are unique.  Returns (A' [d_in, r], B' [r, d_out],
+    sigma [r]) in float64."""
+    A64 = np.asarray(A, dtype=np.float32).astype(np.float64)
+    B64 = np.asarray(B, dtype=np.float32).astype(np.float64)
+    r = A64.shape[1]
+    assert B64.shape[0] == r
+    U, S, Vt = np.linalg.svd(A64 @ B64, full_matrices=False)
+    n = min(r, S.shape[0])
+    sigma = np.zeros(r)
+    sigma[:n] = S[:n]
+    A2 = np.zeros((A64.shape[0], r))
+    B2 = np.zeros((r, B64.shape[1]))
+    keep = sigma[:n] > 1e-12 * max(sigma[0], 1e-300)
+    root = np.sqrt(sigma[:n]) * keep
+    A2[:, :n] = U[:, :n] * root
+    B2[:n, :] = root[:, None] * Vt[:n, :]
+    sigma[:n] *= keep
+    return A2, B2, sigma
+
+
 def bf16_round(y):
     """Round float64 values to the bf16 grid (nearest, ties to even), returned as float64."""
     f = np.asarray(y, dtype=np.float64).astype(np.float32)   # fp32 first: bf16 is its top half
