@@ -358,6 +358,17 @@ def main():
             "chunks_aligned": int(tab_a["chunk_offsets"][-1].item()),
         }
 
+    # ---- set-up work: the ladder of this projection's adapter by one SVD (offline in the paper) ----
+    if not args.no_variants:
+        B.build_ladder(A, Bm)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.build_ladder(A, Bm)
+        torch.cuda.synchronize()
+        out["ladder_build"] = {"note": "cwl_build_ladder on this projection's adapter, once per adapter, wall clock",
+                               "d_in": d_in, "d_out": d_out, "r": wl.r_max,
+                               "ms": (time.perf_counter() - t0) * 1e3}
+
     # ---- every projection of the workload with the same chunk table -------------------------------
     if args.all_projections:
         per = {}

@@ -387,6 +387,29 @@ cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x,
                                         size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_build_ladder -- the rank ladder of a trained adapter (Sec. III-C: obtained once by an SVD of
+ * the adapter matrix; a rung then slices its first r directions).  With dW = A B = U diag(sigma) V^T,
+ * sigma descending, the call writes
+ *      A' = U[:, :r] diag(sqrt(sigma))        B' = diag(sqrt(sigma)) V^T[:r, :]
+ * so that A' B' = dW and A'[:, :k] B'[:k, :] is the best rank-k approximation of dW for every k:
+ * A' and B' are the factors cwl_chunkwise_lora_linear slices.  Directions whose singular value is
+ * below 1e-12 of the largest carry nothing and come out as zero columns / rows with sigma = 0.
+ * Singular vectors are fixed only up to sign (and rotation inside equal singular values); sigma and
+ * the truncated products are unique.  Set-up work, run once per adapter; fp64 inside.
+ *
+ *   A [d_in, r] (lda)     B [r, d_out] (ldb)     element type `dt`, 1 <= r <= CWL_MAX_RANK
+ *   A_out [d_in, r] (lda_out), B_out [r, d_out] (ldb_out): written, type `dt`; may be A and B
+ *   sigma  [r] device, fp64, written
+ *   workspace >= cwl_ladder_workspace_bytes(r) bytes, 256-byte aligned
+ * ------------------------------------------------------------------------------------------- */
+size_t cwl_ladder_workspace_bytes(int32_t r);
+
+cwl_status cwl_build_ladder(cwl_dtype dt, const void* A, int64_t lda, const void* B, int64_t ldb,
+                            int64_t d_in, int64_t d_out, int32_t r, void* A_out, int64_t lda_out,
+                            void* B_out, int64_t ldb_out, double* sigma, void* workspace,
+                            size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel durations from HIP events.
  * cwl_profile_enable(slot_mask), bit i standing for slot i, creates the events on first use (this
  * is the one place the library creates runtime objects), zeroes the counters and makes every

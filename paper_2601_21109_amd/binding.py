@@ -25,7 +25,7 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_stream_step_aligned",
-           "cwl_gated_lora_linear_packed",
+           "cwl_gated_lora_linear_packed", "cwl_ladder_workspace_bytes", "cwl_build_ladder",
            "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
 PROF_SLOTS = 6
@@ -100,6 +100,9 @@ def lib():
     L.cwl_stream_step_aligned.argtypes = [P, i32, ctypes.POINTER(ChunkParams), ctypes.POINTER(ctypes.c_float), i32,
                                           ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_float), i32,
                                           P, i32, P, i32, i32, P, P, P, P, P, P, P]
+    L.cwl_ladder_workspace_bytes.argtypes = [i32]
+    L.cwl_ladder_workspace_bytes.restype = sz
+    L.cwl_build_ladder.argtypes = [ctypes.c_int, P, i64, P, i64, i64, i64, i32, P, i64, P, i64, P, P, sz, P]
     L.cwl_gated_lora_linear_packed.argtypes = [dp, P, P, P, P, P, sz, P]
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
@@ -457,6 +460,28 @@ def stream_step_aligned(entropy, state, l_min, l_max, theta_hard, delta_dev, thr
                                          _ptr(out["closed_sum"]), _ptr(out["status_word"]), _stream()),
            "cwl_stream_step_aligned")
     return out
+
+
+def build_ladder(A, B):
+    """Rank ladder of the adapter update A B by one SVD: returns (A', B', sigma) on the device, A' / B' in the
+    dtype of A / B (fp32 or bf16), sigma float64 [r] descending."""
+    assert A.is_cuda and B.is_cuda and A.dim() == 2 and B.dim() == 2 and A.dtype == B.dtype
+    assert A.stride(1) == 1 and B.stride(1) == 1
+    d_in, r = A.shape
+    d_out = B.shape[1]
+    assert B.shape[0] == r
+    A2, B2 = torch.empty_like(A, memory_format=torch.contiguous_format), torch.empty_like(
+        B, memory_format=torch.contiguous_format)
+    sigma = torch.empty(r, dtype=torch.float64, device=A.device)
+    nbytes = lib().cwl_ladder_workspace_bytes(int(r))
+    if nbytes == 0:
+        raise CwlError(ERR_INVALID_ARG, "cwl_ladder_workspace_bytes")
+    ws = _ws(nbytes, A.device)
+    lda = A.stride(0) if d_in > 1 else r
+    ldb = B.stride(0) if r > 1 else d_out
+    _check(lib().cwl_build_ladder(_dt(A), _ptr(A), lda, _ptr(B), ldb, d_in, d_out, r, _ptr(A2), r, _ptr(B2), d_out,
+                                  _ptr(sigma), _ptr(ws), ws.numel(), _stream()), "cwl_build_ladder")
+    return A2, B2, sigma
 
 
 def gated_lora_linear(x, packed, gate, ranks, scales, out=None, workspace=None):

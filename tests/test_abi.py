@@ -284,3 +284,24 @@ def test_aligned_stream_step_argument_errors(L):
     assert call(status=None) == B.ERR_NULL
     assert call(ent=None) == B.ERR_NULL
     assert call(n_seqs=0) == B.OK
+
+
+def test_build_ladder_argument_errors(L):
+    f = L.cwl_build_ladder
+
+    def call(dt=B.F32, A=P(), lda=8, Bm=P(), ldb=32, d_in=16, d_out=32, r=8, Ao=P(), ldao=8, Bo=P(), ldbo=32,
+             sig=P(), ws=P(0x10000), ws_bytes=1 << 24):
+        return f(dt, A, lda, Bm, ldb, d_in, d_out, r, Ao, ldao, Bo, ldbo, sig, ws, ws_bytes, None)
+
+    assert call(dt=3) == B.ERR_INVALID_ARG
+    assert call(r=0) == B.ERR_INVALID_ARG
+    assert call(r=B.MAX_RANK + 1, lda=512, ldao=512) == B.ERR_INVALID_ARG
+    assert call(d_in=0) == B.ERR_INVALID_ARG
+    assert call(lda=7) == B.ERR_INVALID_ARG
+    assert call(ldbo=31) == B.ERR_INVALID_ARG
+    for k in ("A", "Bm", "Ao", "Bo", "sig", "ws"):
+        assert call(**{k: None}) == B.ERR_NULL, k
+    assert call(ws=P(0x10010)) == B.ERR_INVALID_ARG
+    assert call(ws_bytes=1024) == B.ERR_CAPACITY
+    assert L.cwl_ladder_workspace_bytes(64) >= 8 * 64 * 64 * 8
+    assert L.cwl_ladder_workspace_bytes(0) == 0 and L.cwl_ladder_workspace_bytes(B.MAX_RANK + 1) == 0
