@@ -354,9 +354,23 @@ def main():
             "select_ranks_us": us(lambda: B.select_ranks(table, wl.taus(), K, out=ri)),
             "select_ranks_budget_us": us(lambda: B.select_ranks_budget(table, wl.taus(), K, K - 1, 4, out=ri_b,
                                                                        n_asked=asked)),
+            "stream_step_aligned_us_64_sequences": None,
             "chunks_plain": int(table["chunk_offsets"][-1].item()),
             "chunks_aligned": int(tab_a["chunk_offsets"][-1].item()),
         }
+
+        # the decode step of a batch of 64 sequences in 4 buckets with a budget
+        st64 = B.stream_state(64, dev)
+        bst4 = B.bucket_state(4, dev)
+        bk64 = (torch.arange(64, device=dev, dtype=torch.int32) % 4).contiguous()
+        nh64 = torch.zeros(64, dtype=torch.int32, device=dev)
+        h64 = h[:64].contiguous()
+        so64 = B.stream_step_aligned(h64, st64, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), wl.ladder,
+                                     wl.scales, wl.blend_w, bucket=bk64, bucket_st=bst4, k_high=K - 1, budget=4,
+                                     n_high=nh64)
+        out["scheduler_variants"]["stream_step_aligned_us_64_sequences"] = us(lambda: B.stream_step_aligned(
+            h64, st64, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), wl.ladder, wl.scales, wl.blend_w,
+            bucket=bk64, bucket_st=bst4, k_high=K - 1, budget=4, n_high=nh64, out=so64))
 
     # ---- set-up work: the ladder of this projection's adapter by one SVD (offline in the paper) ----
     if not args.no_variants:
