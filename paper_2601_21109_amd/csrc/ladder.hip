@@ -3,7 +3,8 @@
 // gfx950 only.  include/cwl.h states what is computed; this is how.
 //
 // dW is d_in x d_out but has rank <= r <= 256, so the SVD is taken through r x r matrices, in fp64:
-//   1. Gram matrices G_A = A^T A and G_B = B B^T (whole chip, one 32 x 32 tile of G per workgroup);
+//   1. Gram matrices G_A = A^T A and G_B = B B^T (whole chip: one 32 x 32 tile of G over one slab of
+//      the samples per workgroup, the slabs added in a fixed order afterwards);
 //   2. one workgroup: eigen-decompositions G_A = V_A L_A V_A^T, G_B = V_B L_B V_B^T, which give
 //      A = Q_A (L_A^1/2 V_A^T) and B = (V_B L_B^1/2) Q_B^T with orthonormal Q_A = A V_A L_A^-1/2 and
 //      Q_B^T = L_B^-1/2 V_B^T B; the core M = L_A^1/2 V_A^T V_B L_B^1/2; its SVD M = U S V^T, so that
@@ -15,9 +16,9 @@
 // All three decompositions use one routine, the one-sided Jacobi method (Hestenes): plane rotations
 // from the right make the columns of X orthogonal, X V = Y; column norms of Y are the singular values
 // (for a symmetric positive semi-definite X: the eigenvalues, and V the eigenvectors).  The r / 2
-// disjoint column pairs of a round-robin round are rotated at once, a few threads per pair.  The
-// matrices (up to 512 KiB each) stay in the workspace and are served from L2; this is set-up work
-// that runs once per adapter (a few milliseconds at r = 64, a few tens at r = 256).
+// disjoint column pairs of a round-robin round are rotated at once, a few threads per pair.  Up to
+// r = 96 the two matrices of a decomposition are worked on in LDS; larger ones (up to 512 KiB each)
+// stay in the workspace and are served from L2.  This is set-up work that runs once per adapter.
 #include "common.h"
 
 namespace cwl {
@@ -31,23 +32,39 @@ constexpr double kSigTol = 1e-12;      // singular values below this fraction of
 
 struct LadderWs {
     double *GA, *VA, *GB, *VB, *M, *VM, *TA, *TB;    // r x r each; G*, V*, M column-major, T* [k][i]
+    double *PA, *PB;                                  // [slabs] partial Gram matrices, one per slab of samples
     double *lamA, *lamB, *sig;                        // [r]
     int32_t* perm;                                    // [r] column of M's SVD that has rank i
+    int32_t slabs;
 };
+
+constexpr int kGramTile = 32, kGramSamples = 64;
+
+// slabs of samples a Gram matrix is summed over: enough workgroups for the chip, at most 32
+int32_t gram_slabs(int32_t r) {
+    const int32_t tiles = (r + kGramTile - 1) / kGramTile;
+    int32_t slabs = 256 / (tiles * tiles);
+    return slabs < 1 ? 1 : (slabs > 32 ? 32 : slabs);
+}
 
 size_t ladder_ws_layout(int32_t r, void* base, LadderWs* ws) {
     const size_t mat = align_up(sizeof(double) * (size_t)r * (size_t)r, 256);
     const size_t vec = align_up(sizeof(double) * (size_t)r, 256);
+    const int32_t slabs = gram_slabs(r);
     if (ws) {
         char* b = static_cast<char*>(base);
         double** mats[8] = {&ws->GA, &ws->VA, &ws->GB, &ws->VB, &ws->M, &ws->VM, &ws->TA, &ws->TB};
         for (int i = 0; i < 8; ++i) *mats[i] = reinterpret_cast<double*>(b + mat * i);
-        ws->lamA = reinterpret_cast<double*>(b + mat * 8);
-        ws->lamB = reinterpret_cast<double*>(b + mat * 8 + vec);
-        ws->sig = reinterpret_cast<double*>(b + mat * 8 + vec * 2);
-        ws->perm = reinterpret_cast<int32_t*>(b + mat * 8 + vec * 3);
+        ws->PA = reinterpret_cast<double*>(b + mat * 8);
+        ws->PB = reinterpret_cast<double*>(b + mat * (8 + slabs));
+        char* v = b + mat * (8 + 2 * (size_t)slabs);
+        ws->lamA = reinterpret_cast<double*>(v);
+        ws->lamB = reinterpret_cast<double*>(v + vec);
+        ws->sig = reinterpret_cast<double*>(v + vec * 2);
+        ws->perm = reinterpret_cast<int32_t*>(v + vec * 3);
+        ws->slabs = slabs;
     }
-    return mat * 8 + vec * 4;
+    return mat * (8 + 2 * (size_t)slabs) + vec * 4;
 }
 
 __device__ __forceinline__ float load_elem(const void* p, int64_t idx, int bf16) {
@@ -67,12 +84,15 @@ __device__ __forceinline__ void store_elem(void* p, int64_t idx, float v, int bf
 }
 
 // ---- 1. Gram matrix over samples: G[i][j] = sum_s X(s, i) X(s, j), X(s, c) = X[s*ss + c*cs] ----
-// A: sample = row (ss = lda, cs = 1); B: sample = column (ss = 1, cs = ldb).
-constexpr int kGramTile = 32, kGramSamples = 64;
-
+// A: sample = row (ss = lda, cs = 1); B: sample = column (ss = 1, cs = ldb).  blockIdx.z takes one slab
+// of the samples and writes its own partial matrix; the core kernel adds the slabs in a fixed order.
 __global__ void __launch_bounds__(256)
-gram_kernel(const void* __restrict__ X, int bf16, int64_t n_samples, int64_t ss, int64_t cs, int32_t r,
-            double* __restrict__ G /*column-major r x r*/) {
+gram_kernel(const void* __restrict__ X, int bf16, int64_t n_all, int64_t ss, int64_t cs, int32_t r,
+            double* __restrict__ P /*[slabs] column-major r x r*/) {
+    const int64_t per = ((n_all + gridDim.z - 1) / gridDim.z + kGramSamples - 1) / kGramSamples * kGramSamples;
+    const int64_t s_begin = (int64_t)blockIdx.z * per;
+    const int64_t n_samples = s_begin + per < n_all ? s_begin + per : n_all;
+    double* G = P + (size_t)blockIdx.z * r * r;
     __shared__ float sI[kGramSamples][kGramTile + 1];
     __shared__ float sJ[kGramSamples][kGramTile + 1];
     const int tid = threadIdx.x;
@@ -80,7 +100,7 @@ gram_kernel(const void* __restrict__ X, int bf16, int64_t n_samples, int64_t ss,
     const int ti = (tid & 15) * 2, tj = (tid >> 4) * 2;
     double acc[2][2] = {{0, 0}, {0, 0}};
     const bool comp_fast = cs == 1;
-    for (int64_t s0 = 0; s0 < n_samples; s0 += kGramSamples) {
+    for (int64_t s0 = s_begin; s0 < n_samples; s0 += kGramSamples) {
         for (int e = tid; e < kGramSamples * kGramTile; e += 256) {
             const int c = comp_fast ? (e % kGramTile) : (e / kGramSamples);
             const int s = comp_fast ? (e / kGramTile) : (e % kGramSamples);
@@ -115,7 +135,27 @@ gram_kernel(const void* __restrict__ X, int bf16, int64_t n_samples, int64_t ss,
 
 // One-sided Jacobi: on return the columns of X (column-major n x n) are mutually orthogonal,
 // X_out = X_in V.  Every thread of the workgroup must call it.
-__device__ void jacobi_orthogonalise(double* __restrict__ X, double* __restrict__ V, int32_t n, int* flag /*LDS*/) {
+__device__ void jacobi_sweeps(double* __restrict__ X, double* __restrict__ V, int32_t n, int* flag /*LDS*/);
+
+// The matrices are worked on in LDS when both fit there (n <= lds_n), else in place.
+__device__ void jacobi_orthogonalise(double* __restrict__ X, double* __restrict__ V, int32_t n, int* flag,
+                                     double* lds, int32_t lds_n) {
+    if (n <= lds_n) {
+        double* Xl = lds;
+        double* Vl = lds + (size_t)n * n;
+        for (int32_t e = threadIdx.x; e < n * n; e += kCoreThreads) Xl[e] = X[e];
+        jacobi_sweeps(Xl, Vl, n, flag);
+        for (int32_t e = threadIdx.x; e < n * n; e += kCoreThreads) {
+            X[e] = Xl[e];
+            V[e] = Vl[e];
+        }
+        __syncthreads();
+    } else {
+        jacobi_sweeps(X, V, n, flag);
+    }
+}
+
+__device__ void jacobi_sweeps(double* __restrict__ X, double* __restrict__ V, int32_t n, int* flag /*LDS*/) {
     const int tid = threadIdx.x;
     for (int32_t e = tid; e < n * n; e += kCoreThreads) V[e] = (e / n == e % n) ? 1.0 : 0.0;
     const int32_t h = (n + 1) / 2, m = 2 * h;          // m players; player n (if n is odd) sits out
@@ -199,14 +239,26 @@ __device__ double max_of(const double* v, int32_t n, double* red /*LDS[kCoreThre
 }
 
 __global__ void __launch_bounds__(kCoreThreads)
-ladder_core_kernel(int32_t r, LadderWs ws, double* __restrict__ sigma_out) {
+ladder_core_kernel(int32_t r, LadderWs ws, double* __restrict__ sigma_out, int32_t lds_n) {
+    extern __shared__ double lds[];               // two lds_n x lds_n matrices
     __shared__ int flag;
     __shared__ double red[kCoreThreads / 64];
     const int tid = threadIdx.x;
+    // the Gram matrices: slabs added in slab order
+    for (int32_t e = tid; e < r * r; e += kCoreThreads) {
+        double a = 0.0, b = 0.0;
+        for (int32_t p = 0; p < ws.slabs; ++p) {
+            a += ws.PA[(size_t)p * r * r + e];
+            b += ws.PB[(size_t)p * r * r + e];
+        }
+        ws.GA[e] = a;
+        ws.GB[e] = b;
+    }
+    __syncthreads();
     // eigen-decompositions of the two Gram matrices
-    jacobi_orthogonalise(ws.GA, ws.VA, r, &flag);
+    jacobi_orthogonalise(ws.GA, ws.VA, r, &flag, lds, lds_n);
     column_norms(ws.GA, r, ws.lamA);
-    jacobi_orthogonalise(ws.GB, ws.VB, r, &flag);
+    jacobi_orthogonalise(ws.GB, ws.VB, r, &flag, lds, lds_n);
     column_norms(ws.GB, r, ws.lamB);
     const double lamA_max = max_of(ws.lamA, r, red), lamB_max = max_of(ws.lamB, r, red);
     // core M = L_A^1/2 V_A^T V_B L_B^1/2 (column-major), zero in the directions that carry nothing
@@ -222,7 +274,7 @@ ladder_core_kernel(int32_t r, LadderWs ws, double* __restrict__ sigma_out) {
         ws.M[e] = v;
     }
     __syncthreads();
-    jacobi_orthogonalise(ws.M, ws.VM, r, &flag);      // M <- Y = U S
+    jacobi_orthogonalise(ws.M, ws.VM, r, &flag, lds, lds_n);      // M <- Y = U S
     column_norms(ws.M, r, ws.sig);
     const double sig_max = max_of(ws.sig, r, red);
     // rank of every column by descending singular value (ties by column index)
@@ -332,11 +384,22 @@ extern "C" cwl_status cwl_build_ladder(cwl_dtype dt, const void* A, int64_t lda,
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int bf16 = dt == CWL_BF16 ? 1 : 0;
     const unsigned tiles = (unsigned)((r + kGramTile - 1) / kGramTile);
-    gram_kernel<<<dim3(tiles, tiles), dim3(256), 0, s>>>(A, bf16, d_in, lda, 1, r, ws.GA);
+    gram_kernel<<<dim3(tiles, tiles, (unsigned)ws.slabs), dim3(256), 0, s>>>(A, bf16, d_in, lda, 1, r, ws.PA);
     CWL_RETURN_IF_LAUNCH_FAILED();
-    gram_kernel<<<dim3(tiles, tiles), dim3(256), 0, s>>>(B, bf16, d_out, 1, ldb, r, ws.GB);
+    gram_kernel<<<dim3(tiles, tiles, (unsigned)ws.slabs), dim3(256), 0, s>>>(B, bf16, d_out, 1, ldb, r, ws.PB);
     CWL_RETURN_IF_LAUNCH_FAILED();
-    ladder_core_kernel<<<dim3(1), dim3(kCoreThreads), 0, s>>>(r, ws, sigma);
+    // the r x r matrices of a decomposition are worked on in LDS when two of them fit into 144 KiB (r <= 96)
+    constexpr size_t kCoreLdsMax = 144 * 1024;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(ladder_core_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCoreLdsMax) != hipSuccess)
+            return CWL_ERR_DEVICE;
+        attr_set = true;
+    }
+    const size_t core_lds = 2 * sizeof(double) * (size_t)r * (size_t)r;
+    const bool in_lds = core_lds <= kCoreLdsMax;
+    ladder_core_kernel<<<dim3(1), dim3(kCoreThreads), in_lds ? core_lds : 0, s>>>(r, ws, sigma, in_lds ? r : 0);
     CWL_RETURN_IF_LAUNCH_FAILED();
     const size_t lds = sizeof(float) * (size_t)kApplySamples * (size_t)(r + 1);
     apply_map_kernel<<<dim3((unsigned)((d_in + kApplySamples - 1) / kApplySamples)), dim3(256), lds, s>>>(
