@@ -279,3 +279,35 @@ def test_aligned_stream_step_flags():
     # buckets taken as 0, 1, 0: bucket 0 sees (1024 + 2048) // 2, bucket 1 the NaN scored as 0
     bs = bst.cpu().numpy()
     assert bs[:, 0].tolist() == [1536, 0] and (bs[:, 1] & 0xffffffff).tolist() == [1, 1]
+
+
+def test_aligned_degenerate_batches():
+    lnv = math.log(1024)
+    # no sequences at all
+    so = torch.zeros(1, dtype=torch.int32, device=DEV)
+    t = B.partition_chunks_aligned(torch.empty(0, device=DEV), so, torch.empty(0, dtype=torch.int32, device=DEV), 3,
+                                   4, 16, 0.9 * lnv, 0.25 * lnv)
+    torch.cuda.synchronize()
+    assert t["chunk_offsets"].cpu().tolist() == [0] and int(t["status_word"].item()) == 0
+    # only empty sequences
+    gpu, ref, st, _ = run_aligned(np.empty(0, np.float32), [0, 0, 0], [0, 1, 0], 2, 4, 16, 0.9 * lnv, 0.25 * lnv)
+    assert st == 0 and gpu["status"] == 0
+    assert_tables_equal(gpu, ref)
+    assert gpu["chunk_offsets"].tolist() == [0, 0, 0, 0]
+    # sequences shorter than l_min, more buckets than sequences
+    h = scores_by_sequence([3, 1, 2], 1024, 1)
+    gpu, ref, st, _ = run_aligned(h, [3, 1, 2], [4, 4, 0], 6, 4, 16, 0.9 * lnv, 0.25 * lnv)
+    assert st == 0 and gpu["status"] == 0
+    assert_tables_equal(gpu, ref)
+
+
+@pytest.mark.parametrize("n_buckets", [1, 64, 4096])
+def test_aligned_largest_batch(n_buckets):
+    rng = np.random.RandomState(3)
+    seq_lens = rng.randint(0, 40, 4096).tolist()
+    h = scores_by_sequence(seq_lens, 1024, 12)
+    bucket = rng.randint(0, n_buckets, 4096)
+    lnv = math.log(1024)
+    gpu, ref, st, _ = run_aligned(h, seq_lens, bucket, n_buckets, 3, 9, 0.9 * lnv, 0.25 * lnv)
+    assert st == 0 and gpu["status"] == 0
+    assert_tables_equal(gpu, ref)
