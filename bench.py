@@ -383,6 +383,54 @@ def main():
                                "d_in": d_in, "d_out": d_out, "r": wl.r_max,
                                "ms": (time.perf_counter() - t0) * 1e3}
 
+    # ---- projections that share x (q/k/v) as ONE projection: weights fused by columns, adapter
+    #      [Aq|Ak|Av] with block-diagonal B, ladder rebuilt on the fused update; against three calls ----
+    if not args.no_variants and bf16 and d_in == d_out:
+        gq = torch.Generator(device=dev)
+        gq.manual_seed(1234)
+        mk = lambda shape, scale: (torch.randn(shape, generator=gq, device=dev) * scale).to(wl.dtype)
+        Ws3 = [Wm] + [mk((d_in, d_out), d_in ** -0.5) for _ in range(2)]
+        As3 = [A] + [mk((d_in, wl.r_max), d_in ** -0.5) for _ in range(2)]
+        Bs3 = [Bm] + [mk((wl.r_max, d_out), wl.r_max ** -0.5) for _ in range(2)]
+        pk3 = [packed] + [B.prepack_weights(w_, a_, b_) for w_, a_, b_ in zip(Ws3[1:], As3[1:], Bs3[1:])]
+        Bf = torch.zeros((3 * wl.r_max, 3 * d_out), dtype=wl.dtype, device=dev)
+        for i in range(3):
+            Bf[i * wl.r_max:(i + 1) * wl.r_max, i * d_out:(i + 1) * d_out] = Bs3[i]
+        A2f, B2f, _ = B.build_ladder(torch.cat(As3, dim=1).contiguous(), Bf)
+        pkf = B.prepack_weights(torch.cat(Ws3, dim=1).contiguous(), A2f, B2f)
+        del Bf, A2f, B2f, Ws3, As3, Bs3
+        lad3 = [3 * v for v in wl.ladder]
+        fused = {}
+        for rows in (64, N):
+            if rows == N:
+                sod_q, tab_q, rid_q, x_q = sod, table, ri, x
+            else:
+                tb = W.random_chunk_table(1, [rows], min(wl.l_min, rows), max(min(wl.l_max, rows), 1), K, 11)
+                sod_q, tab_q, rid_q = B.table_from_host(*tb, dev)
+                x_q = x[:rows]
+            ws1 = B.linear_workspace((rows, d_in), wl.dtype, d_out, wl.r_max, wl.ladder, wl.scales, wl.blend_w, dev)
+            wsf = B.linear_workspace((rows, d_in), wl.dtype, 3 * d_out, 3 * wl.r_max, lad3, wl.scales, wl.blend_w, dev)
+            y1 = torch.empty((rows, d_out), dtype=wl.dtype, device=dev)
+            yf = torch.empty((rows, 3 * d_out), dtype=wl.dtype, device=dev)
+
+            def three():
+                for pk in pk3:
+                    B.chunkwise_lora_linear(x_q, pk, None, None, wl.ladder, wl.scales, wl.blend_w, sod_q, tab_q,
+                                            rid_q, out=y1, workspace=ws1)
+
+            def one():
+                B.chunkwise_lora_linear(x_q, pkf, None, None, lad3, wl.scales, wl.blend_w, sod_q, tab_q, rid_q,
+                                        out=yf, workspace=wsf)
+
+            reps = max(args.steps // 2, 5)
+            fused[str(rows)] = {"three_calls_us": timed(three, reps, 3)[0] * 1e3,
+                                "one_fused_call_us": timed(one, reps, 3)[0] * 1e3}
+            del ws1, wsf, y1, yf
+        del pk3, pkf
+        torch.cuda.empty_cache()
+        out["fused_qkv"] = {"note": "three d_in -> d_out projections of the same x: three calls against one call on "
+                                    "[Wq|Wk|Wv] with the ladder of the fused adapter (ranks x 3)", **fused}
+
     # ---- every projection of the workload with the same chunk table -------------------------------
     if args.all_projections:
         per = {}

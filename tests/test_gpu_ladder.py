@@ -138,3 +138,35 @@ def test_ladder_at_workload_sizes(d_in, d_out, r, dtype):
     assert np.max(np.abs(B2 @ B2.T - np.diag(s))) <= 10 * tol * s[0]
     rows = np.unique(np.linspace(0, d_in - 1, 97).astype(np.int64))
     assert rel_err(A2[rows] @ B2, A64[rows] @ B64) <= (TOL_F32 if dtype == torch.float32 else 2 * TOL_BF16)
+
+
+def test_projections_that_share_x_as_one_fused_projection():
+    """q/k/v-style projections fused by columns: W = [W0|W1|W2], A = [A0|A1|A2], B block-diagonal, ladder
+    rebuilt on the fused update.  At full rank the fused layer is the three layers side by side."""
+    d_in, d_out, r, n = 128, 64, 8, 48
+    g = torch.Generator(device="cpu").manual_seed(11)
+    Ws = [torch.randn(d_in, d_out, generator=g) / d_in ** 0.5 for _ in range(3)]
+    As = [torch.randn(d_in, r, generator=g) / d_in ** 0.5 for _ in range(3)]
+    Bs = [torch.randn(r, d_out, generator=g) / r ** 0.5 for _ in range(3)]
+    x = torch.randn(n, d_in, generator=g)
+    Af = torch.cat(As, dim=1)
+    Bf = torch.zeros(3 * r, 3 * d_out)
+    for i in range(3):
+        Bf[i * r:(i + 1) * r, i * d_out:(i + 1) * d_out] = Bs[i]
+    A2, B2, sigma = B.build_ladder(Af.to(DEV), Bf.to(DEV))
+    sod, table, rid = B.table_from_host(np.array([0, n], np.int32), np.array([0, 2], np.int32),
+                                        np.array([0, 30], np.int32), np.array([30, 18], np.int32),
+                                        np.array([1, 0], np.int32), DEV)
+    ranks, scales = [6, 3 * r], [1.0, 1.0]
+    y = B.chunkwise_lora_linear(x.to(DEV), torch.cat(Ws, dim=1).to(DEV), A2, B2, ranks, scales, 0, sod, table, rid)
+    torch.cuda.synchronize()
+    x64 = x.numpy().astype(np.float64)
+    rA, rB, rs = O.build_ladder(Af.numpy(), Bf.numpy())
+    ref = np.concatenate([x64 @ W.numpy().astype(np.float64) for W in Ws], axis=1)
+    # rows of the full-rank chunk: each projection's own textbook LoRA layer
+    ref[:30] += np.concatenate([x64[:30] @ (a.numpy().astype(np.float64) @ b.numpy().astype(np.float64))
+                                for a, b in zip(As, Bs)], axis=1)
+    # rows of the rank-6 chunk: the best rank-6 approximation of the fused update
+    ref[30:] += x64[30:] @ (rA[:, :6] @ rB[:6, :])
+    assert rel_err(host(y), ref) <= 2 * TOL_F32
+    assert np.max(np.abs(sigma.cpu().numpy() - rs)) <= TOL_F32 * rs[0]
