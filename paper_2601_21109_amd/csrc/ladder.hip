@@ -179,6 +179,7 @@ __device__ void jacobi_sweeps(double* __restrict__ X, double* __restrict__ V, in
             if (live) {
                 const double* xp = X + (size_t)p * n;
                 const double* xq = X + (size_t)q * n;
+#pragma unroll 8
                 for (int32_t row = sub; row < n; row += T) {
                     const double a = xp[row], b = xq[row];
                     alpha += a * a;
@@ -199,6 +200,7 @@ __device__ void jacobi_sweeps(double* __restrict__ X, double* __restrict__ V, in
                 double* xq = X + (size_t)q * n;
                 double* vp = V + (size_t)p * n;
                 double* vq = V + (size_t)q * n;
+#pragma unroll 8
                 for (int32_t row = sub; row < n; row += T) {
                     const double a = xp[row], b = xq[row];
                     xp[row] = c * a - s * b;
