@@ -151,13 +151,23 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d) {
     SmallPlan p = {};
     const int64_t R = padded_rank(d->r_max);
     const int64_t n_cols = d->d_out + R;
-    const int64_t bm = d->n_rows <= 64 ? 64 : 128;
+    int64_t bm = d->n_rows <= 64 ? 64 : 128;
     p.n_tile = d->n_rows <= 256 ? 64 : 128;           // from 257 rows the tile count suffices with 128 x 128
-    const int64_t tiles = (n_cols + p.n_tile - 1) / p.n_tile * ((d->n_rows + bm - 1) / bm);
+    int64_t tiles = (n_cols + p.n_tile - 1) / p.n_tile * ((d->n_rows + bm - 1) / bm);
+    int64_t bytes_cap = d->d_in / (4 * d->n_rows);    // partial sums <= half the weights' bytes
+    if (p.n_tile == 128 && tiles * 2 > 256) {
+        // 128 x 128 tiles (one workgroup per compute unit) that cannot even be cut in two within one round of
+        // workgroups: tiles of 256 x 128 instead, a third fewer bytes per flop, and the reduction dimension cut
+        // further (partial sums up to the weights' bytes)
+        bm = 256;
+        tiles = (n_cols + 127) / 128 * ((d->n_rows + 255) / 256);
+        bytes_cap = d->d_in / (2 * d->n_rows);
+    }
+    p.m_tile = (int32_t)bm;
     const int64_t stages = d->d_in / 64;
     int64_t s = (p.n_tile == 64 ? 512 : 256) / tiles;   // what fits at once: two (one) workgroups per compute unit
     if (s > stages / 4) s = stages / 4;
-    if (s > d->d_in / (4 * d->n_rows)) s = d->d_in / (4 * d->n_rows);   // partial sums <= half the weights' bytes
+    if (s > bytes_cap) s = bytes_cap;
     if (s > 32) s = 32;
     if (s < 1) s = 1;
     p.ks_per_split = (int32_t)((stages + s - 1) / s);
@@ -183,6 +193,7 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
     pa.K1 = (int32_t)d->d_in;
     pa.M = d->n_rows;   pa.N = d->d_out + R;
     pa.N_tile = p.n_tile;
+    pa.M_tile = p.m_tile;
     pa.splits = p.splits;
     pa.ks_per_split = p.ks_per_split;
     pa.partial = partial;
