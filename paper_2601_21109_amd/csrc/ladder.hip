@@ -280,11 +280,14 @@ ladder_core_kernel(int32_t r, LadderWs ws, double* __restrict__ sigma_out, int32
     column_norms(ws.M, r, ws.sig);
     const double sig_max = max_of(ws.sig, r, red);
     // rank of every column by descending singular value (ties by column index)
+    // (a NaN norm, from NaN in the inputs, is ranked as +inf, so that the ranks are a permutation whatever the data)
     for (int32_t c = tid; c < r; c += kCoreThreads) {
-        const double mine = ws.sig[c];
+        const double raw = ws.sig[c];
+        const double mine = raw == raw ? raw : INFINITY;
         int32_t rank = 0;
         for (int32_t u = 0; u < r; ++u) {
-            const double v = ws.sig[u];
+            const double w = ws.sig[u];
+            const double v = w == w ? w : INFINITY;
             rank += (v > mine || (v == mine && u < c)) ? 1 : 0;
         }
         ws.perm[rank] = c;

@@ -170,3 +170,17 @@ def test_projections_that_share_x_as_one_fused_projection():
     ref[30:] += x64[30:] @ (rA[:, :6] @ rB[:6, :])
     assert rel_err(host(y), ref) <= 2 * TOL_F32
     assert np.max(np.abs(sigma.cpu().numpy() - rs)) <= TOL_F32 * rs[0]
+
+
+def test_ladder_with_nan_in_the_factors_poisons_the_result_and_nothing_else():
+    A, Bm = factors(64, 48, 8, 2, torch.float32)
+    A[5, 3] = float("nan")
+    A2, B2, sigma = B.build_ladder(A.to(DEV), Bm.to(DEV))
+    torch.cuda.synchronize()
+    assert torch.isnan(sigma).any() or torch.isnan(A2).any()
+    # the next call on clean factors is unaffected
+    A, Bm = factors(64, 48, 8, 2, torch.float32)
+    A2, B2, sigma = B.build_ladder(A.to(DEV), Bm.to(DEV))
+    torch.cuda.synchronize()
+    rA, rB, rs = O.build_ladder(A.numpy(), Bm.numpy())
+    assert np.max(np.abs(sigma.cpu().numpy() - rs)) <= TOL_F32 * rs[0]
