@@ -385,7 +385,7 @@ def main():
 
     # ---- projections that share x (q/k/v) as ONE projection: weights fused by columns, adapter
     #      [Aq|Ak|Av] with block-diagonal B, ladder rebuilt on the fused update; against three calls ----
-    if not args.no_variants and bf16 and d_in == d_out:
+    if not args.no_variants and bf16 and d_in == d_out and 3 * wl.r_max <= B.MAX_RANK:
         gq = torch.Generator(device=dev)
         gq.manual_seed(1234)
         mk = lambda shape, scale: (torch.randn(shape, generator=gq, device=dev) * scale).to(wl.dtype)
