@@ -7,6 +7,12 @@
  *
  *      cwl_score_tokens  ->  cwl_partition_chunks  ->  cwl_select_ranks  ->  cwl_chunkwise_lora_linear
  *
+ * Around them: cwl_compose_scores (the other difficulty signals of Sec. III-A mixed into the score),
+ * cwl_select_ranks_budget / cwl_bucket_sequences / cwl_partition_chunks_aligned (the chunker's budget
+ * and the batch controller of Sec. III-G and IV-D), cwl_stream_step[_aligned] +
+ * cwl_gated_lora_linear_packed (the same rules one token per sequence at a time, for decoding), and
+ * the set-up calls cwl_prepack_weights and cwl_build_ladder (the ladder of Sec. III-C by one SVD).
+ *
  * General rules
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
  *   - The caller owns every buffer.  The library never allocates, frees or synchronises; every
