@@ -367,3 +367,39 @@ def test_aligned_step_errors(oracle):
     assert oracle.stream_step_aligned(st, [1, 2], 2, 4, 100, 100, TAUS, *LADDER, 0, k_high=0, budget=1,
                                       n_high=np.zeros(2, np.int32))[0] != 0
     assert oracle.stream_step_aligned(st, [1, 2], 3, 4, 100, 100, TAUS, *LADDER, 0)[0] == 3
+
+
+# ---------------------------------------------------------------- the integer means are floors
+
+def test_sequence_mean_is_a_floor(oracle):
+    # sums 10 and 8 over 4 tokens: floors 2 and 2 tie and go by index; rounded up or to nearest the first would be 3
+    st, o = oracle.bucket_sequences([3, 3, 2, 2, 2, 2, 2, 2], [0, 4, 8], 2, 0)
+    assert st == 0 and o["seq_sum"].tolist() == [10, 8]
+    assert o["order"].tolist() == [0, 1] and o["bucket"].tolist() == [0, 1]
+
+
+def test_bucket_mean_series_is_a_floor(oracle):
+    # members score 10 and 11 at position 2, theta = 11: the mean floor(21 / 2) = 10 stays below it, so nothing closes the
+    # first chunk before L_max; rounded to nearest the mean would be 11 and close it in front of position 2
+    a = [0, 0, 10, 0, 0, 0, 0, 0]
+    b = [0, 0, 11, 0, 0, 0, 0, 0]
+    st, al = oracle.partition_aligned(a + b, [0, 8, 16], [0, 0], 1, 2, 4, 11, INF_Q)
+    assert st == 0
+    assert al["chunk_len"].tolist() == [4, 4, 4, 4]
+    # with 12 in place of 11 the floor reaches theta and the chunk is closed there: [0,2), then [2,6) (nothing fires,
+    # L_max), then the tail [6,8)
+    b[2] = 12
+    st, al = oracle.partition_aligned(a + b, [0, 8, 16], [0, 0], 1, 2, 4, 11, INF_Q)
+    assert al["chunk_len"].tolist() == [2, 4, 2, 2, 4, 2]
+
+
+def test_bucket_mean_of_a_step_is_a_floor(oracle):
+    st = oracle.StreamState(2)
+    bst = oracle.BucketState(1)
+    closed = []
+    for q in ([0, 0], [0, 0], [10, 11], [0, 0], [0, 0], [10, 12]):
+        code, out = oracle.stream_step_aligned(st, q, 2, 8, 11, INF_Q, TAUS, *LADDER, 0, bucket=[0, 0], bucket_state=bst)
+        assert code == 0
+        closed.append(out["closed_len"].tolist())
+    # (10 + 11) // 2 = 10 < theta: no close; (10 + 12) // 2 = 11 >= theta: the five tokens so far are closed
+    assert closed == [[0, 0], [0, 0], [0, 0], [0, 0], [0, 0], [5, 5]]
