@@ -25,10 +25,6 @@ constexpr int kMaxBuckets = 4096;
 constexpr int kOne = 1024;          // threads of the single-workgroup kernels
 constexpr int kPer = kMaxSeqs / kOne;
 
-struct Thresholds {
-    int64_t tau_q[CWL_MAX_LADDER];
-};
-
 __device__ __forceinline__ int64_t shfl_up_i64(int64_t v, int delta) {
     int lo = __shfl_up((int)(v & 0xffffffffll), delta);
     int hi = __shfl_up((int)(v >> 32), delta);
@@ -69,7 +65,7 @@ __device__ int64_t block_excl_scan(int64_t v, int64_t* wave_tot /*LDS[waves]*/, 
 // ---- rung selection under a budget: one wavefront per sequence ----
 __global__ void __launch_bounds__(256)
 select_budget_kernel(const int64_t* __restrict__ chunk_sum, const int32_t* __restrict__ chunk_len,
-                     const int32_t* __restrict__ chunk_offsets, int32_t n_seqs, int32_t cap, Thresholds th,
+                     const int32_t* __restrict__ chunk_offsets, int32_t n_seqs, int32_t cap, TauTable th,
                      int32_t K, int32_t k_high, int32_t budget, int32_t* __restrict__ rank_idx,
                      int32_t* __restrict__ n_asked) {
     const int lane = threadIdx.x & 63;
@@ -384,13 +380,6 @@ align_emit_kernel(const float* __restrict__ score, int64_t n_rows, const int32_t
     }
 }
 
-cwl_status check_chunk_params(const cwl_chunk_params* p) {
-    if (!p) return CWL_ERR_NULL;
-    if (p->l_min < 1 || p->l_max < p->l_min) return CWL_ERR_INVALID_ARG;
-    if ((int64_t)p->l_max < 2 * (int64_t)p->l_min - 1) return CWL_ERR_INFEASIBLE;
-    return CWL_OK;
-}
-
 }  // namespace
 }  // namespace cwl
 
@@ -403,12 +392,8 @@ extern "C" cwl_status cwl_select_ranks_budget(const int64_t* chunk_sum, const in
                                               void* stream) {
     if (K < 1 || K > CWL_MAX_LADDER || n_seqs < 0 || cap < 0 || k_high < 1 || budget < 0) return CWL_ERR_INVALID_ARG;
     if (K > 1 && !thresholds) return CWL_ERR_NULL;
-    Thresholds th = {};
-    for (int32_t j = 0; j < K - 1; ++j) {
-        if (thresholds[j] != thresholds[j]) return CWL_ERR_INVALID_ARG;
-        if (j > 0 && thresholds[j] < thresholds[j - 1]) return CWL_ERR_INVALID_ARG;
-        th.tau_q[j] = quantise_threshold(thresholds[j]);
-    }
+    TauTable th;
+    if (fill_tau_table(thresholds, K, &th) != CWL_OK) return CWL_ERR_INVALID_ARG;
     if (n_seqs == 0) return CWL_OK;
     if (!chunk_offsets) return CWL_ERR_NULL;
     if (cap > 0 && (!chunk_sum || !chunk_len || !rank_idx)) return CWL_ERR_NULL;

@@ -39,6 +39,30 @@ inline int64_t quantise_threshold(float h) {
     return (int64_t)f;
 }
 
+// the selector's thresholds, quantised like the scores (kernel argument)
+struct TauTable {
+    int64_t tau_q[CWL_MAX_LADDER];
+};
+
+// K-1 ascending thresholds in nats -> table; CWL_ERR_INVALID_ARG for NaN or descending entries
+inline cwl_status fill_tau_table(const float* thresholds, int32_t K, TauTable* t) {
+    *t = TauTable{};
+    for (int32_t j = 0; j < K - 1; ++j) {
+        if (thresholds[j] != thresholds[j]) return CWL_ERR_INVALID_ARG;
+        if (j > 0 && thresholds[j] < thresholds[j - 1]) return CWL_ERR_INVALID_ARG;
+        t->tau_q[j] = quantise_threshold(thresholds[j]);
+    }
+    return CWL_OK;
+}
+
+// length bounds of the chunker
+inline cwl_status check_chunk_params(const cwl_chunk_params* p) {
+    if (!p) return CWL_ERR_NULL;
+    if (p->l_min < 1 || p->l_max < p->l_min) return CWL_ERR_INVALID_ARG;
+    if ((int64_t)p->l_max < 2 * (int64_t)p->l_min - 1) return CWL_ERR_INFEASIBLE;
+    return CWL_OK;
+}
+
 // sequence b: validated (first row, length); a malformed entry yields length 0
 __device__ __forceinline__ void seq_extent(const int32_t* seq_offsets, int32_t b, int64_t n_rows,
                                            int64_t* base, int64_t* T, bool* bad) {

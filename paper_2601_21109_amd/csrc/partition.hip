@@ -482,14 +482,10 @@ partition_compact_kernel(int32_t n_seqs, PartWs ws, int32_t* __restrict__ chunk_
     }
 }
 
-struct Thresholds {
-    int64_t tau_q[CWL_MAX_LADDER];
-};
-
 __global__ void select_ranks_kernel(const int64_t* __restrict__ chunk_sum,
                                     const int32_t* __restrict__ chunk_len,
                                     const int32_t* __restrict__ chunk_offsets, int32_t n_seqs,
-                                    int32_t cap, Thresholds th, int32_t K,
+                                    int32_t cap, cwl::TauTable th, int32_t K,
                                     int32_t* __restrict__ rank_idx) {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t n = chunk_offsets[n_seqs];
@@ -502,18 +498,11 @@ __global__ void select_ranks_kernel(const int64_t* __restrict__ chunk_sum,
     rank_idx[c] = k;
 }
 
-cwl_status check_params(const cwl_chunk_params* p) {
-    if (!p) return CWL_ERR_NULL;
-    if (p->l_min < 1 || p->l_max < p->l_min) return CWL_ERR_INVALID_ARG;
-    if ((int64_t)p->l_max < 2 * (int64_t)p->l_min - 1) return CWL_ERR_INFEASIBLE;
-    return CWL_OK;
-}
-
 }  // namespace
 
 extern "C" size_t cwl_partition_workspace_bytes(int64_t n_rows, int32_t n_seqs,
                                                 const cwl_chunk_params* p) {
-    if (n_rows < 0 || n_seqs < 0 || check_params(p) != CWL_OK) return 0;
+    if (n_rows < 0 || n_seqs < 0 || cwl::check_chunk_params(p) != CWL_OK) return 0;
     return part_ws_layout(n_rows, n_seqs, p->l_min, nullptr, nullptr, nullptr);
 }
 
@@ -525,7 +514,7 @@ cwl_status cwl::partition_chunks_avg_len(const float* entropy, int64_t n_rows,
                                          int64_t* chunk_sum, int32_t cap, int32_t* status_word,
                                          void* workspace, size_t workspace_bytes, void* stream,
                                          int64_t avg_len) {
-    cwl_status st = check_params(p);
+    cwl_status st = cwl::check_chunk_params(p);
     if (st != CWL_OK) return st;
     if (n_rows < 0 || n_rows >= (int64_t)1 << 31 || n_seqs < 0 || cap < 0) return CWL_ERR_INVALID_ARG;
     if (!seq_offsets || !chunk_offsets || !status_word) return CWL_ERR_NULL;
@@ -611,12 +600,8 @@ extern "C" cwl_status cwl_select_ranks(const int64_t* chunk_sum, const int32_t* 
                                        void* stream) {
     if (K < 1 || K > CWL_MAX_LADDER || n_seqs < 0 || cap < 0) return CWL_ERR_INVALID_ARG;
     if (K > 1 && !thresholds) return CWL_ERR_NULL;
-    Thresholds th = {};
-    for (int32_t j = 0; j < K - 1; ++j) {
-        if (thresholds[j] != thresholds[j]) return CWL_ERR_INVALID_ARG;
-        if (j > 0 && thresholds[j] < thresholds[j - 1]) return CWL_ERR_INVALID_ARG;
-        th.tau_q[j] = cwl::quantise_threshold(thresholds[j]);
-    }
+    cwl::TauTable th;
+    if (cwl::fill_tau_table(thresholds, K, &th) != CWL_OK) return CWL_ERR_INVALID_ARG;
     if (cap == 0) return CWL_OK;
     if (!chunk_sum || !chunk_len || !chunk_offsets || !rank_idx) return CWL_ERR_NULL;
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -12,10 +12,6 @@
 namespace cwl {
 namespace {
 
-struct StreamTaus {
-    int64_t tau_q[CWL_MAX_LADDER];
-};
-
 static_assert(sizeof(cwl_stream_state) == 32, "layout of the cached state");
 static_assert(sizeof(cwl_bucket_state) == 16, "layout of a bucket's open chunk");
 static_assert(sizeof(cwl_token_gate) == sizeof(TokMeta), "a gate entry is a TokMeta");
@@ -28,7 +24,7 @@ __device__ __forceinline__ bool close_test(int64_t n, int64_t S, int64_t qe, int
     return n == l_max || S >= theta_q * n || qe >= theta_q || d > delta_q * n;
 }
 
-__device__ __forceinline__ int32_t rung_of(int64_t S, int64_t n, const StreamTaus& taus, int32_t K) {
+__device__ __forceinline__ int32_t rung_of(int64_t S, int64_t n, const TauTable& taus, int32_t K) {
     int32_t k = 0;
 #pragma unroll
     for (int j = 0; j < CWL_MAX_LADDER - 1; ++j) k += (j < K - 1 && S >= taus.tau_q[j] * n) ? 1 : 0;
@@ -39,7 +35,7 @@ __device__ __forceinline__ int32_t rung_of(int64_t S, int64_t n, const StreamTau
 // otherwise the decision (0 / 1) was taken for its bucket.  n_high: counters of the budget, or NULL.
 __device__ __forceinline__ void
 step_sequence(int32_t b, int64_t qe, int shared_close, int32_t l_min, int32_t l_max, int64_t theta_q,
-              int64_t delta_q, const StreamTaus& taus, const Ladder& lad, int32_t blend_w, int32_t k_high,
+              int64_t delta_q, const TauTable& taus, const Ladder& lad, int32_t blend_w, int32_t k_high,
               int32_t budget, int32_t* __restrict__ n_high, cwl_stream_state* __restrict__ state,
               cwl_token_gate* __restrict__ gate, int32_t* __restrict__ closed_len,
               int64_t* __restrict__ closed_sum) {
@@ -93,7 +89,7 @@ step_sequence(int32_t b, int64_t qe, int shared_close, int32_t l_min, int32_t l_
 
 __global__ void __launch_bounds__(256)
 stream_step_kernel(const float* __restrict__ entropy, int32_t n_seqs, int32_t l_min, int32_t l_max,
-                   int64_t theta_q, int64_t delta_q, StreamTaus taus, Ladder lad, int32_t blend_w,
+                   int64_t theta_q, int64_t delta_q, TauTable taus, Ladder lad, int32_t blend_w,
                    int32_t k_high, int32_t budget, int32_t* __restrict__ n_high,
                    cwl_stream_state* __restrict__ state, cwl_token_gate* __restrict__ gate,
                    int32_t* __restrict__ closed_len, int64_t* __restrict__ closed_sum,
@@ -115,7 +111,7 @@ constexpr int kAlignedMax = 4096;     // sequences and buckets the one workgroup
 
 __global__ void __launch_bounds__(kAlignedThreads)
 stream_step_aligned_kernel(const float* __restrict__ entropy, int32_t n_seqs, int32_t l_min, int32_t l_max,
-                           int64_t theta_q, int64_t delta_q, StreamTaus taus, Ladder lad, int32_t blend_w,
+                           int64_t theta_q, int64_t delta_q, TauTable taus, Ladder lad, int32_t blend_w,
                            const int32_t* __restrict__ bucket, int32_t n_buckets,
                            cwl_bucket_state* __restrict__ bucket_state, int32_t k_high, int32_t budget,
                            int32_t* __restrict__ n_high, cwl_stream_state* __restrict__ state,
@@ -190,18 +186,13 @@ extern "C" cwl_status cwl_stream_step_aligned(const float* entropy, int32_t n_se
                                               cwl_token_gate* gate, int32_t* closed_len, int64_t* closed_sum,
                                               int32_t* status_word, void* stream) {
     if (!p) return CWL_ERR_NULL;
-    if (p->l_min < 1 || p->l_max < p->l_min) return CWL_ERR_INVALID_ARG;
-    if ((int64_t)p->l_max < 2 * (int64_t)p->l_min - 1) return CWL_ERR_INFEASIBLE;
+    if (cwl_status ps = check_chunk_params(p); ps != CWL_OK) return ps;
     if (K < 1 || K > CWL_MAX_LADDER || n_seqs < 0 || blend_w < 0) return CWL_ERR_INVALID_ARG;
     if (!ranks || !scales || (K > 1 && !thresholds)) return CWL_ERR_NULL;
-    StreamTaus taus = {};
+    TauTable taus;
+    if (fill_tau_table(thresholds, K, &taus) != CWL_OK) return CWL_ERR_INVALID_ARG;
     Ladder lad = {};
     lad.K = K;
-    for (int32_t j = 0; j < K - 1; ++j) {
-        if (thresholds[j] != thresholds[j]) return CWL_ERR_INVALID_ARG;
-        if (j > 0 && thresholds[j] < thresholds[j - 1]) return CWL_ERR_INVALID_ARG;
-        taus.tau_q[j] = quantise_threshold(thresholds[j]);
-    }
     for (int32_t k = 0; k < K; ++k) {
         if (ranks[k] < 0 || ranks[k] > CWL_MAX_RANK || scales[k] != scales[k]) return CWL_ERR_INVALID_ARG;
         if (k > 0 && ranks[k] < ranks[k - 1]) return CWL_ERR_INVALID_ARG;
