@@ -25,22 +25,6 @@ constexpr int kMaxBuckets = 4096;
 constexpr int kOne = 1024;          // threads of the single-workgroup kernels
 constexpr int kPer = kMaxSeqs / kOne;
 
-__device__ __forceinline__ int64_t shfl_up_i64(int64_t v, int delta) {
-    int lo = __shfl_up((int)(v & 0xffffffffll), delta);
-    int hi = __shfl_up((int)(v >> 32), delta);
-    return ((int64_t)hi << 32) | (uint32_t)lo;
-}
-
-__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        int lo = __shfl_xor((int)(v & 0xffffffffll), off);
-        int hi = __shfl_xor((int)(v >> 32), off);
-        v += ((int64_t)hi << 32) | (uint32_t)lo;
-    }
-    return v;
-}
-
 // exclusive prefix sum over the workgroup of one value per thread; *total = the sum
 __device__ int64_t block_excl_scan(int64_t v, int64_t* wave_tot /*LDS[waves]*/, int64_t* total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

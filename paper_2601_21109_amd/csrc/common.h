@@ -77,6 +77,24 @@ __device__ __forceinline__ void seq_extent(const int32_t* seq_offsets, int32_t b
     }
 }
 
+// 64-bit integers through the 32-bit wavefront shuffles
+__device__ __forceinline__ int64_t shfl_up_i64(int64_t v, int delta) {
+    int lo = __shfl_up((int)(v & 0xffffffffll), delta);
+    int hi = __shfl_up((int)(v >> 32), delta);
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+// sum over the 64 lanes of a wavefront; every lane gets the result
+__device__ __forceinline__ int64_t wave_sum_i64(int64_t v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        int lo = __shfl_xor((int)(v & 0xffffffffll), off);
+        int hi = __shfl_xor((int)(v >> 32), off);
+        v += ((int64_t)hi << 32) | (uint32_t)lo;
+    }
+    return v;
+}
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) {
     return __uint_as_float(bits16 << 16);
 }

@@ -33,6 +33,8 @@ namespace {
 
 using cwl::quantise_score;
 using cwl::seq_extent;
+using cwl::shfl_up_i64;
+using cwl::wave_sum_i64;
 
 constexpr int kThreads = 256;    // compact and next kernels
 constexpr int kBig = 1024;       // scan and walk kernels: one workgroup per sequence, so a wide one
@@ -88,20 +90,9 @@ __host__ size_t part_ws_layout(int64_t n_rows, int32_t n_seqs, int32_t l_min, vo
     return off;
 }
 
-__device__ __forceinline__ int64_t shfl_up_i64(int64_t v, int delta) {
-    int lo = __shfl_up((int)(v & 0xffffffffll), delta);
-    int hi = __shfl_up((int)(v >> 32), delta);
-    return ((int64_t)hi << 32) | (uint32_t)lo;
-}
-
 // sum over the block of one int64 per thread; every thread gets the result
 __device__ int64_t block_sum_i64(int64_t v, int64_t* smem /*[waves]*/) {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) {
-        int lo = __shfl_xor((int)(v & 0xffffffffll), off);
-        int hi = __shfl_xor((int)(v >> 32), off);
-        v += ((int64_t)hi << 32) | (uint32_t)lo;
-    }
+    v = wave_sum_i64(v);
     __syncthreads();
     if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = v;
     __syncthreads();
