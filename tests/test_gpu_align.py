@@ -311,3 +311,53 @@ def test_aligned_largest_batch(n_buckets):
     gpu, ref, st, _ = run_aligned(h, seq_lens, bucket, n_buckets, 3, 9, 0.9 * lnv, 0.25 * lnv)
     assert st == 0 and gpu["status"] == 0
     assert_tables_equal(gpu, ref)
+
+
+def test_aligned_decode_step_replays_from_a_hip_graph():
+    """The bucketed, budgeted scheduler step only enqueues one kernel: captured once, every replay (with eager work
+    and synchronisations in between) must leave the same state, gates and counters as the eager call."""
+    n_seqs, n_buckets = 24, 3
+    ranks, scales = [4, 8, 16], [4.0, 2.0, 1.0]
+    lnv = math.log(1500)
+    args = (2, 4, 0.9 * lnv, 0.3 * lnv, [0.45 * lnv, 0.9 * lnv], ranks, scales, 2)
+    h = torch.empty(n_seqs, dtype=torch.float32, device=DEV)
+    bucket = (torch.arange(n_seqs, device=DEV, dtype=torch.int32) % n_buckets).contiguous()
+    state, bst = B.stream_state(n_seqs, DEV), B.bucket_state(n_buckets, DEV)
+    n_high = torch.zeros(n_seqs, dtype=torch.int32, device=DEV)
+    kw = dict(bucket=bucket, bucket_st=bst, k_high=1, budget=2, n_high=n_high)
+    out = B.stream_step_aligned(h.zero_(), state, *args, **kw)          # allocates the outputs once, outside the graph
+
+    def reset():
+        state.zero_(); bst.zero_(); n_high.zero_()
+
+    def new_scores(i):
+        gi = torch.Generator(device=DEV).manual_seed(500 + i)
+        h.copy_(torch.rand(n_seqs, generator=gi, device=DEV) * lnv)
+
+    reset()
+    eager = []
+    for i in range(8):
+        new_scores(i)
+        B.stream_step_aligned(h, state, *args, out=out, **kw)
+        torch.cuda.synchronize()
+        eager.append((state.clone(), bst.clone(), n_high.clone(), out["gate"].clone(), out["closed_len"].clone()))
+    reset()
+    new_scores(0)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.stream_step_aligned(h, state, *args, out=out, **kw)           # warm-up on the capture stream
+        reset()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        B.stream_step_aligned(h, state, *args, out=out, **kw)
+    for i in range(8):
+        new_scores(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (state, bst, n_high, out["gate"], out["closed_len"])
+        for a, b in zip(got, eager[i]):
+            assert torch.equal(a, b), i
+    assert int(n_high.sum().item()) > 0 and int(out["status_word"].item()) == 0
