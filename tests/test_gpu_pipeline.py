@@ -93,3 +93,73 @@ def test_cfg1_full_size_scoring_and_table():
     lens = gpu["chunk_len"]
     assert lens.min() >= wl.l_min and lens.max() <= wl.l_max and int(lens.sum()) == wl.n_rows
     assert len(set(gpu["rank_idx"].tolist())) >= 3
+
+
+@pytest.mark.parametrize("n_seqs,seq_len,d_in,d_out,group_rows", [
+    (3, 700, 256, 512, 0),        # 128 x 128 tiles, split shrink
+    (8, 2048, 512, 1024, 0),      # persistent 256 x 256 kernel
+    (2, 200, 256, 320, 0),        # few-row path (partial products + fix-up)
+    (8, 2048, 512, 1024, 1),      # rows grouped by rank
+])
+def test_whole_step_replays_from_a_hip_graph(n_seqs, seq_len, d_in, d_out, group_rows):
+    """The four calls only enqueue kernels on the caller's stream: a whole step captured once must give, on every
+    replay (with eager work and synchronisations in between), the bits of the eager step on the same inputs."""
+    vocab, r_max = 2000, 32
+    ranks, scales = [8, 16, 32], [2.0, 1.0, 0.5]
+    lnv = float(np.log(vocab))
+    theta, delta, taus = 0.9 * lnv, 0.25 * lnv, [0.35 * lnv, 0.7 * lnv]
+    N = n_seqs * seq_len
+    sod = torch.arange(0, N + 1, seq_len, dtype=torch.int32, device=DEV)
+    g = torch.Generator(device=DEV).manual_seed(3)
+    mk = lambda *s: (torch.randn(s, generator=g, device=DEV) / s[0] ** 0.5).to(torch.bfloat16)
+    packed = B.prepack_weights(mk(d_in, d_out), mk(d_in, r_max), mk(r_max, d_out))
+    logits = torch.empty((N, vocab), dtype=torch.bfloat16, device=DEV)
+    x = torch.empty((N, d_in), dtype=torch.bfloat16, device=DEV)
+    h = torch.empty(N, dtype=torch.float32, device=DEV)
+    y = torch.empty((N, d_out), dtype=torch.bfloat16, device=DEV)
+    ws = B.linear_workspace((N, d_in), torch.bfloat16, d_out, r_max, ranks, scales, 3, DEV)
+
+    def new_inputs(i):
+        gi = torch.Generator(device=DEV).manual_seed(40 + i)
+        # spans of 50 tokens at one of three temperatures: low, middle and high entropy
+        sigma = torch.tensor([0.5, 2.5, 7.0], device=DEV)[torch.randint(0, 3, (N // 50 + 1,), generator=gi, device=DEV)]
+        sigma = sigma.repeat_interleave(50)[:N, None]
+        logits.copy_((torch.randn((N, vocab), generator=gi, device=DEV) * sigma).to(torch.bfloat16))
+        x.copy_(torch.randn((N, d_in), generator=gi, device=DEV).to(torch.bfloat16))
+
+    new_inputs(0)
+    table = B.partition_chunks(B.score_tokens(logits, out=h), sod, 8, 64, theta, delta)
+    ri = B.select_ranks(table, taus, 3)
+
+    def step():
+        B.score_tokens(logits, out=h)
+        B.partition_chunks(h, sod, 8, 64, theta, delta, out=table)
+        B.select_ranks(table, taus, 3, out=ri)
+        B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, 3, sod, table, ri, out=y, group_rows=group_rows,
+                                workspace=ws)
+
+    eager = []
+    for i in range(4):
+        new_inputs(i)
+        step()
+        torch.cuda.synchronize()
+        eager.append((y.clone(), table["chunk_start"].clone(), ri.clone(), table["chunk_offsets"].clone()))
+    assert len({int(e[3][-1].item()) for e in eager}) > 1      # the inputs do lead to different chunk tables
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                 # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for i in (2, 0, 3, 1):
+        new_inputs(i)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(table["status_word"].item()) == 0
+        assert torch.equal(table["chunk_offsets"], eager[i][3]), i
+        n = int(eager[i][3][-1].item())
+        assert torch.equal(table["chunk_start"][:n], eager[i][1][:n]) and torch.equal(ri[:n], eager[i][2][:n]), i
+        assert torch.equal(y, eager[i][0]), i
