@@ -225,3 +225,18 @@ def test_bf16_full_size_q_proj_sampled_rows():
             y_again = B.chunkwise_lora_linear(x, pw, None, None, wl.ladder, wl.scales, wl.blend_w, sod,
                                               tab, rid)
             assert torch.equal(y, y_again)
+
+
+@pytest.mark.parametrize("dtype,tol", [(torch.float32, TOL_F32), (torch.bfloat16, TOL_BF16)])
+@pytest.mark.parametrize("seq_lens", [[40], [300, 212], [2100, 1500, 3000]])
+@pytest.mark.parametrize("group_rows", [0, 1])
+def test_largest_ladder_and_rank(dtype, tol, seq_lens, group_rows):
+    """The limits of the ABI at once: sixteen rungs, the top one at rank 256 (four stages of the rank part in
+    the bf16 kernels), on the few-row, the mid-size and the persistent path."""
+    ranks = [0] + [16 * k + (8 if k % 2 else 0) for k in range(1, 15)] + [256]
+    assert len(ranks) == B.MAX_LADDER and ranks[-1] == B.MAX_RANK and ranks == sorted(ranks)
+    n = int(np.sum(seq_lens))
+    rows = None if n <= 1000 else np.unique(np.concatenate([np.arange(0, n, 37), np.arange(n - 40, n)]))
+    yh, ref, _ = run_case(len(seq_lens), seq_lens, 512, 640, ranks, 5, dtype, 23, l_min=6, l_max=48,
+                          group_rows=group_rows, packed=(dtype == torch.bfloat16), rows=rows)
+    assert rel_err(yh, ref) <= tol
