@@ -216,6 +216,7 @@ def gate_fields(gate):
     (4096, 4096, 12, 2, 4, 1, ([4, 8], [1.0, 0.5]), 1, 2),         # the largest batch the call takes
     (9, 12, 150, 4, 16, 2, ([4, 8, 16], [4.0, 2.0, 1.0]), 2, None),  # empty buckets, no budget
     (50, 0, 150, 4, 16, 2, ([4, 8, 16], [4.0, 2.0, 1.0]), 2, 2),     # no buckets, budget only
+    (40, 5, 150, 4, 16, 3, (list(range(0, 256, 16)), [0.0] + [16.0 / r for r in range(16, 256, 16)]), 9, 2),  # 16 rungs
 ])
 def test_aligned_stream_step_matches_oracle(n_seqs, n_buckets, steps, l_min, l_max, w, ladder, k_high, budget):
     ranks, scales = ladder

@@ -32,6 +32,7 @@ def make_gate(r_cur, r_prev, g_cur, g_prev):
     (300, 120, 8, 64, 4, ([8, 16, 32, 64], [2.0, 1.0, 0.5, 0.25])),
     (1, 400, 1, 1, 0, ([0, 5], [7.0, 3.2])),
     (5, 200, 3, 40, 3, ([16], [1.0])),
+    (33, 150, 4, 16, 3, (list(range(0, 256, 16)), [0.0] + [16.0 / r for r in range(16, 256, 16)])),   # 16 rungs
 ])
 def test_stream_step_matches_oracle(n_seqs, steps, l_min, l_max, w, ladder):
     ranks, scales = ladder
