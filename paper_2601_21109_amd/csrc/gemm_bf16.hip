@@ -439,7 +439,9 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
 // many bytes of the weight matrix are in flight).
 cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st) {
     if (a.M_tile == 256) return launch_partial_cfg<256, 128, 2, 2, 3>(a, job, st);
+    if (a.M <= 64 && a.three_per_cu) return launch_partial_cfg<64, 64, 2, 2, 3>(a, job, st);
     if (a.M <= 64) return launch_partial_cfg<64, 64, 2, 2, 4>(a, job, st);
+    if (a.N_tile == 64 && a.three_per_cu) return launch_partial_cfg<128, 64, 2, 2, 2>(a, job, st);
     if (a.N_tile == 64) return launch_partial_cfg<128, 64, 2, 2, 3>(a, job, st);
     return launch_partial_cfg<128, 128, 2, 2, 4>(a, job, st);
 }

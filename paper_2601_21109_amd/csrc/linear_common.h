@@ -63,6 +63,7 @@ struct GemmArgs {
     int64_t ldp, partial_stride;
     int32_t N_tile;         // EPI_PARTIAL: column tile the plan was made for (64 or 128)
     int32_t M_tile;         // EPI_PARTIAL: row tile of the plan (256: tiles of 256 x 128; else by M and N_tile)
+    int32_t three_per_cu;   // EPI_PARTIAL, M <= 64: the plan counts on three workgroups per compute unit (shallower ring)
 };
 
 // EPI_STORE: C = result in the launch's element type.  EPI_GATE: C[g, n] = result * G[perm[g], n].
@@ -93,7 +94,7 @@ cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_
 // ---- few rows (linear_small.hip): bf16, packed weights, token order ----
 constexpr int64_t kSmallRows = 512;
 struct SmallPlan {
-    int32_t splits, ks_per_split, n_tile, m_tile;
+    int32_t splits, ks_per_split, n_tile, m_tile, three_per_cu;
     int64_t ldp, partial_stride;      // elements
     size_t partial_bytes;
 };

@@ -166,6 +166,14 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d) {
     p.m_tile = (int32_t)bm;
     const int64_t stages = d->d_in / 64;
     int64_t s = (p.n_tile == 64 ? 512 : 256) / tiles;   // what fits at once: two (one) workgroups per compute unit
+    if (p.n_tile == 64 && s < 3) {
+        // wide outputs leave room for one or two slices only (173 tiles of 4096 -> 11008: 346 workgroups on 256
+        // compute units); with a ring one stage shallower three workgroups fit on a unit, and 4 slices of
+        // 4096 -> 11008 stream the weights 20 % faster than 2 (64 rows: 19 against 24 us; 256 rows: 39 against 47).
+        // With three slices or more already, the deeper ring is the better one.
+        s = 768 / tiles;
+        p.three_per_cu = 1;
+    }
     if (s > stages / 4) s = stages / 4;
     if (s > bytes_cap) s = bytes_cap;
     if (s > 32) s = 32;
@@ -194,6 +202,7 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
     pa.M = d->n_rows;   pa.N = d->d_out + R;
     pa.N_tile = p.n_tile;
     pa.M_tile = p.m_tile;
+    pa.three_per_cu = p.three_per_cu;
     pa.splits = p.splits;
     pa.ks_per_split = p.ks_per_split;
     pa.partial = partial;
