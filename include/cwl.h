@@ -291,6 +291,30 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
                                             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_chunkwise_lora_linear_packed_static -- cwl_chunkwise_lora_linear_packed for callers that
+ * cannot allocate device memory and have no workspace to hand over: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same
+ * bits in y; the scratch memory is an array of CWL_STATIC_SCRATCH_BYTES that the library holds in
+ * the device's memory from the moment it is loaded until the process ends (one copy per GPU).  The
+ * call allocates and frees nothing; its first call on a device looks up the array's address there.
+ *
+ *   CWL_ERR_CAPACITY   the descriptor needs more than CWL_STATIC_SCRATCH_BYTES
+ *                      (cwl_linear_packed_workspace_bytes(d) says how much); nothing is launched
+ *
+ * Every call on one GPU uses the same array: calls that may overlap on one GPU (two streams, two
+ * host threads) race and must be ordered by the caller.  The array keeps the last call's contents;
+ * nothing in it has to start at zero, every kernel reads only what the same call wrote.
+ * ------------------------------------------------------------------------------------------- */
+#define CWL_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+
+cwl_status cwl_chunkwise_lora_linear_packed_static(const cwl_linear_desc* d, const void* x,
+                                                   const void* packed, const int32_t* seq_offsets,
+                                                   int32_t n_seqs, const int32_t* chunk_offsets,
+                                                   const int32_t* chunk_start, const int32_t* chunk_len,
+                                                   const int32_t* rank_idx, int32_t chunk_cap, void* y,
+                                                   void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * cwl_stream_step -- the chunker, the selector and the cross-fade one token at a time (Sec. III-A
  * and III-B run the estimator and the chunker while decoding; Sec. III-F keeps the scheduler's state
  * between steps).  One call consumes ONE new token per sequence: its score, quantised as in

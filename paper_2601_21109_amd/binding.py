@@ -17,6 +17,7 @@ OK, ERR_NULL, ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_CAPACITY, ERR_UNSUPPORTED, ER
 F32, BF16 = 0, 1
 STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS, STATUS_BAD_BUCKET = 1, 2, 4, 8
 MAX_LADDER, MAX_RANK = 16, 256
+STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_compose_scores",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
@@ -24,7 +25,8 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_partition_chunks_aligned",
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
-           "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_stream_step_aligned",
+           "cwl_chunkwise_lora_linear_packed", "cwl_chunkwise_lora_linear_packed_static",
+           "cwl_stream_step", "cwl_stream_step_aligned",
            "cwl_gated_lora_linear_packed", "cwl_ladder_workspace_bytes", "cwl_build_ladder",
            "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
@@ -106,12 +108,13 @@ def lib():
     L.cwl_gated_lora_linear_packed.argtypes = [dp, P, P, P, P, P, sz, P]
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
-    for name in ("cwl_profile_enable", "cwl_profile_read", "cwl_score_tokens", "cwl_partition_chunks", "cwl_select_ranks",
-           "cwl_select_ranks_budget", "cwl_bucket_sequences", "cwl_aligned_workspace_bytes",
-           "cwl_partition_chunks_aligned",
-                 "cwl_prepack_weights", "cwl_chunkwise_lora_linear",
-                 "cwl_chunkwise_lora_linear_packed", "cwl_stream_step", "cwl_gated_lora_linear_packed"):
-        getattr(L, name).restype = ctypes.c_int
+    L.cwl_chunkwise_lora_linear_packed_static.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P]
+    # return types: byte counts are size_t, everything else but the two informational calls a status
+    for name in EXPORTS:
+        if name.endswith("_bytes"):
+            getattr(L, name).restype = sz
+        elif name not in ("cwl_status_string", "cwl_abi_version"):
+            getattr(L, name).restype = ctypes.c_int
     _lib = L
     return L
 
@@ -379,6 +382,21 @@ def chunkwise_lora_linear(x, W, A, B, ranks, scales, blend_w, seq_offsets, table
         _check(L.cwl_chunkwise_lora_linear(d.ref(), _ptr(x), _ptr(W), _ptr(A if r_max else None),
                                            _ptr(B if r_max else None), *common),
                "cwl_chunkwise_lora_linear")
+    return out
+
+
+def chunkwise_lora_linear_static(x, packed, ranks, scales, blend_w, seq_offsets, table, rank_idx, out=None):
+    """chunkwise_lora_linear on PackedWeights with the library's own static scratch array instead of a
+    workspace: the call allocates nothing when `out` is given."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(packed, PackedWeights)
+    assert packed.dtype == x.dtype and packed.d_in == x.shape[1]
+    if out is None:
+        out = torch.empty((x.shape[0], packed.d_out), dtype=x.dtype, device=x.device)
+    d = _desc_for(x, packed.d_out, packed.r_max, ranks, scales, blend_w, out)
+    _check(lib().cwl_chunkwise_lora_linear_packed_static(
+        d.ref(), _ptr(x), _ptr(packed.blob), _ptr(seq_offsets), seq_offsets.numel() - 1,
+        _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
+        table["cap"], _ptr(out), _stream()), "cwl_chunkwise_lora_linear_packed_static")
     return out
 
 

@@ -4,6 +4,11 @@
 #include "linear_common.h"
 #include "token_meta.h"
 
+// Scratch memory of cwl_chunkwise_lora_linear_packed_static: held in every GPU's memory from the
+// moment the library is loaded there.  In host code this name is only a handle for
+// hipGetSymbolAddress, never a device address; kernels get the looked-up pointer as an argument.
+static __device__ __align__(256) unsigned char scratch[CWL_STATIC_SCRATCH_BYTES];
+
 namespace cwl {
 namespace {
 
@@ -559,21 +564,40 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     return s;
 }
 
+// ws_given: the caller brings the workspace (checked here); else the library's own array is used
 cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* seq_offsets,
                       int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
                       const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap,
-                      const void* y, const void* ws) {
+                      const void* y, const void* ws, bool ws_given = true) {
     if (n_seqs < 0 || chunk_cap < 0) return CWL_ERR_INVALID_ARG;
     if (d->n_rows == 0) return CWL_OK;
-    if (!x || !y || !ws) return CWL_ERR_NULL;
+    if (!x || !y || (ws_given && !ws)) return CWL_ERR_NULL;
     if (n_seqs > 0 && (!seq_offsets || !chunk_offsets)) return CWL_ERR_NULL;
     if (n_seqs > 0 && chunk_cap > 0 && (!chunk_start || !chunk_len || !rank_idx)) return CWL_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(ws) % 256) return CWL_ERR_INVALID_ARG;
+    if (ws_given && reinterpret_cast<uintptr_t>(ws) % 256) return CWL_ERR_INVALID_ARG;
     if (d->dt == CWL_BF16 &&
         (reinterpret_cast<uintptr_t>(x) % 16 || reinterpret_cast<uintptr_t>(y) % 16))
         return CWL_ERR_UNSUPPORTED;
     if (d->dt == CWL_F32 && (reinterpret_cast<uintptr_t>(x) % 4 || reinterpret_cast<uintptr_t>(y) % 4))
         return CWL_ERR_INVALID_ARG;
+    return CWL_OK;
+}
+
+// Address of the static scratch array on the current device, looked up once per device (each GPU
+// holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+cwl_status static_scratch(char** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CWL_ERR_DEVICE;
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CWL_ERR_DEVICE;
+        if (reinterpret_cast<uintptr_t>(p) % 256) return CWL_ERR_DEVICE;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<char*>(g_scratch_ptr[dev]);
     return CWL_OK;
 }
 
@@ -631,6 +655,27 @@ extern "C" cwl_status cwl_chunkwise_lora_linear_packed(
     return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
                       chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y,
                       static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+extern "C" cwl_status cwl_chunkwise_lora_linear_packed_static(
+    const cwl_linear_desc* d, const void* x, const void* packed, const int32_t* seq_offsets,
+    int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
+    const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap, void* y, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_call(d, x, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                   chunk_cap, y, nullptr, false);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
+    if (ws_layout(d).total > CWL_STATIC_SCRATCH_BYTES) return CWL_ERR_CAPACITY;
+    char* ws = nullptr;
+    s = static_scratch(&ws);
+    if (s != CWL_OK) return s;
+    return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
+                      chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y, ws,
+                      static_cast<hipStream_t>(stream));
 }
 
 extern "C" cwl_status cwl_chunkwise_lora_linear(

@@ -33,6 +33,27 @@ def test_every_declared_symbol_is_exported(L):
     assert sorted(B.EXPORTS) == names
 
 
+def test_static_scratch_entry_argument_errors(L):
+    """The entry point without a workspace argument rejects bad arguments, and descriptors that need more
+    than its static array, before it touches the device."""
+    f = L.cwl_chunkwise_lora_linear_packed_static
+
+    def status(d, x=P(0x10000), packed=P(0x20000), y=P(0x30000)):
+        return f(d.ref(), x, packed, P(), 1, P(), P(), P(), P(), 8, y, None)
+
+    assert status(make_desc(n_rows=-1)) == B.ERR_INVALID_ARG
+    assert status(make_desc(), x=None) == B.ERR_NULL
+    assert status(make_desc(), y=None) == B.ERR_NULL
+    assert status(make_desc(), packed=None) == B.ERR_NULL
+    assert status(make_desc(), packed=P(0x20010)) == B.ERR_INVALID_ARG
+    assert status(make_desc(n_rows=0)) == B.OK
+    big = make_desc(n_rows=1 << 20)                          # gate table alone: 16 MiB
+    assert L.cwl_linear_packed_workspace_bytes(big.ref()) > B.STATIC_SCRATCH_BYTES
+    assert status(big) == B.ERR_CAPACITY
+    text = open(os.path.join(ROOT, "include", "cwl.h")).read()
+    assert f"#define CWL_STATIC_SCRATCH_BYTES ((size_t){B.STATIC_SCRATCH_BYTES >> 20} << 20)" in text
+
+
 def test_version_and_status_strings(L):
     assert L.cwl_abi_version() == 1
     seen = {B.status_string(s) for s in range(7)}
