@@ -33,6 +33,15 @@ def test_every_declared_symbol_is_exported(L):
     assert sorted(B.EXPORTS) == names
 
 
+def test_return_types_of_the_exports(L):
+    """Byte counts come back as size_t (a workspace may exceed 2 GiB), statuses as int."""
+    for n in B.EXPORTS:
+        if n.endswith("_bytes"):
+            assert getattr(L, n).restype is ctypes.c_size_t, n
+        elif n not in ("cwl_status_string", "cwl_abi_version"):
+            assert getattr(L, n).restype is ctypes.c_int, n
+
+
 def test_static_scratch_entry_argument_errors(L):
     """The entry point without a workspace argument rejects bad arguments, and descriptors that need more
     than its static array, before it touches the device."""
