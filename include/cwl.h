@@ -9,7 +9,7 @@
  *
  * Around them: cwl_compose_scores (the other difficulty signals of Sec. III-A mixed into the score),
  * cwl_select_ranks_budget / cwl_bucket_sequences / cwl_partition_chunks_aligned (the chunker's budget
- * and the batch controller of Sec. III-G and IV-D), cwl_stream_step[_aligned] +
+ * and the batch controller of Sec. III-G and IV-F), cwl_stream_step[_aligned] +
  * cwl_gated_lora_linear_packed (the same rules one token per sequence at a time, for decoding), and
  * the set-up calls cwl_prepack_weights and cwl_build_ladder (the ladder of Sec. III-C by one SVD).
  *
@@ -24,6 +24,10 @@
  *     synchronously.  Data-dependent conditions are reported through a device status word.
  *   - Token rows, chunk indices and sequence offsets are 32-bit: n_rows < 2^31.
  *   - Results are deterministic: the same inputs give bitwise identical outputs.
+ *   - Calls work on the current HIP device; pointers and `stream` must belong to it.  The library
+ *     keeps a little set-once host state per device (kernel attributes, the number of compute
+ *     units) without locking: the first call of an entry point on a device should not run
+ *     concurrently with another host thread's first call on the same device.
  */
 #ifndef CWL_H
 #define CWL_H
@@ -177,7 +181,7 @@ cwl_status cwl_select_ranks_budget(const int64_t* chunk_sum, const int32_t* chun
 
 /* ---------------------------------------------------------------------------------------------
  * cwl_bucket_sequences -- buckets of the sequences of a batch by complexity percentile (Sec. III-G)
- * and complexity-balanced micro-batches (Sec. IV-D).  The complexity of a sequence is the mean of
+ * and complexity-balanced micro-batches (Sec. IV-F).  The complexity of a sequence is the mean of
  * its scores, quantised as in cwl_partition_chunks: m_s = floor(seq_sum[s] / T_s), 0 when empty.
  * Sequences are ranked by (m_s, s) ascending, order[rho] = the sequence of rank rho, and
  *      bucket[s] = floor(rho_s * n_buckets / n_seqs)          equal-count percentile bins,

@@ -20,7 +20,7 @@
  *   - Sec. III-A signals (ii) n-gram novelty against the recent context and (iv) positional
  *     prior, mixed with the entropy into one score                             -> cwl_ref_compose_scores
  *   - Sec. III-B budget of high-capacity regions per sequence                   -> cwl_ref_limit_high
- *   - Sec. III-G buckets of sequences by complexity percentile, Sec. IV-D
+ *   - Sec. III-G buckets of sequences by complexity percentile, Sec. IV-F
  *     complexity-balanced micro-batches                                        -> cwl_ref_bucket_sequences
  *   - Sec. III-G chunk boundaries aligned inside a bucket                       -> cwl_ref_partition_aligned
  *   - the two above one token at a time, for a batch that is being decoded      -> cwl_ref_stream_step_aligned
@@ -505,7 +505,7 @@ int cwl_ref_limit_high(int32_t* rank_idx, const int32_t* chunk_offsets, int32_t 
 /* ------------------------------------------------------------------------------------------
  * Buckets of sequences by complexity percentile, and complexity-balanced micro-batches
  * (Sec. III-G: sequences of a batch are bucketed by complexity percentiles so that their chunk
- * boundaries can be aligned; Sec. IV-D: a batch controller keeps micro-batches balanced in
+ * boundaries can be aligned; Sec. IV-F: a batch controller keeps micro-batches balanced in
  * complexity).  Reading: the complexity of a sequence is the mean of its quantised scores,
  * m_s = floor(sum_s / T_s) (0 for an empty sequence).  Sequences are ranked by (m_s, s) ascending,
  * rho_s being the rank; order[rho_s] = s.  With n_buckets equal-count percentile bins,

@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("CWL_LIB_PATH", os.path.join(_HERE, "libcwl.so"))   # override: another build
+LIB_PATH = os.path.join(_HERE, "libcwl.so")
 
 OK, ERR_NULL, ERR_INVALID_ARG, ERR_INFEASIBLE, ERR_CAPACITY, ERR_UNSUPPORTED, ERR_DEVICE = range(7)
 F32, BF16 = 0, 1

@@ -1,7 +1,7 @@
 // cwl_select_ranks_budget, cwl_bucket_sequences and cwl_partition_chunks_aligned (gfx950 only): the
 // budget of high-capacity regions per sequence (Sec. III-B of arxiv 2601.21109), the buckets of
 // sequences by complexity percentile with the complexity-balanced micro-batches (Sec. III-G,
-// Sec. IV-D), and the chunker whose boundaries are shared inside a bucket (Sec. III-G).
+// Sec. IV-F), and the chunker whose boundaries are shared inside a bucket (Sec. III-G).
 // include/cwl.h states the readings taken.  All of it is integer work on the quantised scores and
 // on tables of a few thousand entries: short kernels whose cost is their launch.
 //

@@ -18,6 +18,34 @@ constexpr int64_t kQThresholdMax = 1 << 21;  // clamp of a quantised threshold: 
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Set-once launch state (a kernel's dynamic-LDS limit, the number of compute units, the address of
+// a device symbol) belongs to a (kernel, device) pair, so it is remembered per device, indexed by
+// the current device's ordinal.  Not synchronised: two host threads that make the first call on a
+// device at the same moment both do the same idempotent set-up.
+constexpr int kMaxDevices = 64;
+
+inline int device_slot() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    return dev;
+}
+
+struct PerDeviceFlag {
+    bool done[kMaxDevices] = {};
+};
+
+// raises a kernel's dynamic shared-memory limit on the current device, the first time it is asked to
+inline cwl_status ensure_dynamic_lds(const void* kernel, int bytes, PerDeviceFlag& flag) {
+    const int dev = device_slot();
+    if (dev < 0) return CWL_ERR_DEVICE;
+    if (!flag.done[dev]) {
+        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+            return CWL_ERR_DEVICE;
+        flag.done[dev] = true;
+    }
+    return CWL_OK;
+}
+
 // Score -> Q10 fixed-point nats, q = floor(h*1024 + 0.5) in fp32.  h*1024 is exact, so a fused
 // multiply-add gives the same value as a separate multiply and add.
 __host__ __device__ inline int32_t quantise_score(float h, bool* is_nan) {

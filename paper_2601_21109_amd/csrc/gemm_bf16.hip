@@ -369,13 +369,8 @@ cwl_status launch_partial_cfg(GemmArgs a, const MetaJob& job, hipStream_t st) {
     if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
     if (a.splits < 1 || a.ks_per_split < 1 || !a.partial) return CWL_ERR_INVALID_ARG;
     auto kern = partial_bf16_kernel<BM, BN, WM, WN, NST>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem_bytes, lds_set) != CWL_OK) return CWL_ERR_DEVICE;
     a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
     if (job.n_blocks < 0 || (job.n_blocks > 0 && !job.meta)) return CWL_ERR_INVALID_ARG;
@@ -392,13 +387,8 @@ cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
     static_assert(smem_bytes <= 160 * 1024, "LDS budget of a gfx950 compute unit");
     if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
     auto kern = gemm_bf16_tn_kernel<BM, BN, WM, WN, NST, EPI, BK>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem_bytes, lds_set) != CWL_OK) return CWL_ERR_DEVICE;
     a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
     const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;

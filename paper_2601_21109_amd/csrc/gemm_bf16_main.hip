@@ -410,13 +410,9 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     if (a.perm || a.lda1 > kMaxLd || a.ldb1 > kMaxLd || a.lda2 > kMaxLd || a.ldb2 > kMaxLd)
         return launch_main_bf16_general(a_in, st);
     if (a.K1 < BK || a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(main_bf16_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(main_bf16_kernel), SMEM_BYTES, lds_set) != CWL_OK)
+        return CWL_ERR_DEVICE;
     a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
     const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;
@@ -428,14 +424,16 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     const int64_t n_virtual = (n_tiles + 7) / 8 * 8;       // workgroup slots, 8 XCDs round-robin
     if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
     // persistent: one workgroup per compute unit (160 KiB of LDS each), a multiple of 8 of them
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
+    static int n_cu_of[kMaxDevices] = {};
+    const int dev = device_slot();
+    if (dev < 0) return CWL_ERR_DEVICE;
+    if (n_cu_of[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
             return CWL_ERR_DEVICE;
-        n_cu = v / 8 * 8;
+        n_cu_of[dev] = v / 8 * 8;
     }
+    const int n_cu = n_cu_of[dev];
     const int64_t grid = n_virtual < n_cu ? n_virtual : n_cu;
     main_bf16_kernel<<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a, (int32_t)n_virtual);
     CWL_RETURN_IF_LAUNCH_FAILED();

@@ -395,13 +395,9 @@ extern "C" cwl_status cwl_build_ladder(cwl_dtype dt, const void* A, int64_t lda,
     CWL_RETURN_IF_LAUNCH_FAILED();
     // the r x r matrices of a decomposition are worked on in LDS when two of them fit into 144 KiB (r <= 96)
     constexpr size_t kCoreLdsMax = 144 * 1024;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(ladder_core_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kCoreLdsMax) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(ladder_core_kernel), (int)kCoreLdsMax, lds_set) != CWL_OK)
+        return CWL_ERR_DEVICE;
     const size_t core_lds = 2 * sizeof(double) * (size_t)r * (size_t)r;
     const bool in_lds = core_lds <= kCoreLdsMax;
     ladder_core_kernel<<<dim3(1), dim3(kCoreThreads), in_lds ? core_lds : 0, s>>>(r, ws, sigma, in_lds ? r : 0);

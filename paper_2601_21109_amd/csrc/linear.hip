@@ -585,12 +585,11 @@ cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* se
 
 // Address of the static scratch array on the current device, looked up once per device (each GPU
 // holds its own copy of the array at its own address).
-constexpr int kMaxDevices = 64;
 void* g_scratch_ptr[kMaxDevices] = {};
 
 cwl_status static_scratch(char** out) {
-    int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return CWL_ERR_DEVICE;
+    const int dev = device_slot();
+    if (dev < 0) return CWL_ERR_DEVICE;
     if (!g_scratch_ptr[dev]) {
         void* p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CWL_ERR_DEVICE;

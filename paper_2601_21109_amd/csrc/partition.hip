@@ -533,22 +533,11 @@ cwl_status cwl::partition_chunks_avg_len(const float* entropy, int64_t n_rows,
     const int32_t lds_rows = (win * 12 <= (int64_t)kLdsMax) ? (int32_t)win : 0;
     const size_t next_lds = (size_t)lds_rows * 12;
     const size_t walk_lds = (size_t)kWalkLds * sizeof(int32_t);
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(partition_next_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax) != hipSuccess ||
-            hipFuncSetAttribute(reinterpret_cast<const void*>(partition_walk_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)walk_lds) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        attr_set = true;
-    }
-    static bool seq_attr_set = false;
-    if (!seq_attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(partition_seq_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSeqLdsBytes) != hipSuccess)
-            return CWL_ERR_DEVICE;
-        seq_attr_set = true;
-    }
+    static PerDeviceFlag next_set, walk_set, seq_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(partition_next_kernel), (int)kLdsMax, next_set) != CWL_OK ||
+        ensure_dynamic_lds(reinterpret_cast<const void*>(partition_walk_kernel), (int)walk_lds, walk_set) != CWL_OK ||
+        ensure_dynamic_lds(reinterpret_cast<const void*>(partition_seq_kernel), (int)kSeqLdsBytes, seq_set) != CWL_OK)
+        return CWL_ERR_DEVICE;
     // which path: the host knows only the batch average of the sequence lengths
     const bool long_sequences = avg_len > 4096;
     cwl::prof_begin(CWL_PROF_PARTITION, s);

@@ -4,7 +4,7 @@
 // cwl_partition_chunks / cwl_select_ranks / cwl_chunkwise_lora_linear applied to what is known when
 // a token arrives (include/cwl.h states them).  One thread per sequence: a step touches 32 bytes
 // of state per sequence and is pure launch latency.  cwl_stream_step_aligned adds what the batch
-// controller of Sec. III-G / IV-D and the budget of Sec. III-B mean for a batch that is being decoded:
+// controller of Sec. III-G / IV-F and the budget of Sec. III-B mean for a batch that is being decoded:
 // one close decision per bucket, taken on the bucket's mean score, and a counter of high-capacity
 // chunks per sequence.
 #include "linear_common.h"

@@ -23,6 +23,17 @@ DEV = "cuda:0"
 ])
 @pytest.mark.parametrize("group_rows", [0, 1])
 def test_linear_full_size_sampled(name, proj, n_uniform, group_rows):
+    linear_full_size_sampled(name, proj, n_uniform, group_rows)
+
+
+@pytest.mark.parametrize("proj", [1, 2, 3, 4, 5, 6])
+def test_linear_full_size_sampled_every_projection_of_the_decoder_layer(proj):
+    """k, v, o, gate, up and down of the 32 x 2048 workload (q is covered above): all seven projections of the
+    layer at full size, each with its own x, W, A, B."""
+    linear_full_size_sampled("cfg3", proj, 24, 0)
+
+
+def linear_full_size_sampled(name, proj, n_uniform, group_rows):
     wl = W.WORKLOADS[name]
     x, Wm, A, Bm = W.linear_operands(wl, proj, DEV)
     so, co, cs, cl, ri = W.random_chunk_table(wl.n_seqs, [wl.seq_len] * wl.n_seqs, wl.l_min, wl.l_max,
@@ -41,14 +52,16 @@ def test_linear_full_size_sampled(name, proj, n_uniform, group_rows):
     assert len(set(ri.tolist())) == len(wl.ladder)
 
 
-def test_scoring_128k_vocab_tile():
-    """One 4096-row tile of the 128000-entry-vocabulary workload (the long-context workload streams
+def test_scoring_128k_vocab_tiles():
+    """All eight 4096-row tiles of the 128000-entry-vocabulary workload (the long-context workload streams
     its logits in such tiles through one reused buffer)."""
     wl = W.WORKLOADS["cfg4"]
     sig = W.token_sigmas(wl)
-    h = torch.empty(2 * wl.logit_tile_rows, dtype=torch.float32, device=DEV)
+    n_tiles = wl.n_rows // wl.logit_tile_rows
+    assert n_tiles == 8
+    h = torch.empty(wl.n_rows, dtype=torch.float32, device=DEV)
     rows = np.arange(0, wl.logit_tile_rows, 97)
-    for tile in range(2):
+    for tile in range(n_tiles):
         r0 = tile * wl.logit_tile_rows
         z = W.logits_rows(wl, r0, r0 + wl.logit_tile_rows, DEV, sigmas=sig)
         B.score_tokens(z, out=h[r0:r0 + wl.logit_tile_rows])
@@ -58,6 +71,23 @@ def test_scoring_128k_vocab_tile():
     # the three difficulty levels of the generator are all present and well separated
     lv = host(h) / np.log(wl.vocab)
     assert lv.min() < 0.3 and lv.max() > 0.95
+
+
+def test_scoring_full_size_65536_rows():
+    """The 65536 x 32000 bf16 logits (4.2 GB) of the two largest workloads in one call, as the benchmark
+    scores them; the oracle checks a row sample that reaches both ends and crosses every 512-row block."""
+    wl = W.WORKLOADS["cfg3"]
+    z = W.logits(wl, DEV)
+    assert z.shape == (65536, 32000) and z.is_contiguous()
+    h = B.score_tokens(z)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(0, wl.n_rows, 257), [wl.n_rows - 1]]))
+    ref = O.entropy(host(z[torch.from_numpy(rows).to(DEV)]))
+    assert entropy_err(host(h)[rows], ref, wl.vocab) <= TOL_F32
+    lv = host(h) / np.log(wl.vocab)
+    assert 0.6 < float(np.mean(lv > 0.9)) < 0.8        # the 70 % low-sigma (near-uniform) tokens
+    del z
+    torch.cuda.empty_cache()
 
 
 def test_cfg3_skewed_mix_table_bit_exact():

@@ -1,5 +1,5 @@
 """Pins for the oracle's budget of high-capacity chunks (Sec. III-B), its percentile buckets and
-micro-batches (Sec. III-G, IV-D) and its chunker with boundaries aligned inside a bucket
+micro-batches (Sec. III-G, IV-F) and its chunker with boundaries aligned inside a bucket
 (Sec. III-G): hand-worked cases, reductions to the plain chunker, invariants, and independent
 restatements with numpy's sort and Python integers."""
 import numpy as np
