@@ -354,7 +354,7 @@ __global__ void __launch_bounds__(WM * WN * 64) partial_bf16_kernel(GemmArgs a, 
                 r_eff = o > r_eff ? o : r_eff;
             }
             const int64_t blk = t / kRankBlock;
-            if ((threadIdx.x & 63) == 0 && blk * kRankBlock < a.M) job.blk_r[blk] = r_eff;
+            if ((threadIdx.x & 63) == 0) job.blk_r[blk] = r_eff;   // all four entries of the 256 rows
         }
         return;
     }

@@ -85,19 +85,15 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
     const int KS = a.K1 / BK;                        // stages of the first reduction part (>= 1)
 
     // stages of a row tile: the first part plus ceil(r_tile / 64), r_tile = largest effective
-    // rank among the tile's rows
+    // rank among the tile's rows.  The table holds four entries (one per 64 rows) for every started
+    // group of 256 rows, so a tile reads its four with one aligned scalar load.
+    typedef __attribute__((ext_vector_type(4))) int i32x4;
     auto stages_of = [&](int32_t bm) -> int {
         int32_t r_tile = 0;
         if (a.blk_r) {
-            const int64_t n_blk = (a.M + kRankBlock - 1) / kRankBlock;
-#pragma unroll
-            for (int i = 0; i < BM / kRankBlock; ++i) {
-                const int64_t blk = (int64_t)bm * (BM / kRankBlock) + i;
-                if (blk < n_blk) {
-                    const int32_t r = a.blk_r[blk];
-                    r_tile = r > r_tile ? r : r_tile;
-                }
-            }
+            const i32x4 q = *reinterpret_cast<const i32x4*>(a.blk_r + 4 * (int64_t)bm);
+            const int32_t q01 = q[0] > q[1] ? q[0] : q[1], q23 = q[2] > q[3] ? q[2] : q[3];
+            r_tile = q01 > q23 ? q01 : q23;
         }
         return KS + (r_tile + BK - 1) / BK;
     };
@@ -105,21 +101,22 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
     // ---- loaders ----
     // Wave w fills rows 64w .. 64w+63 of a slot, instruction i rows 64w+8i .. +7.  Address =
     // scalar (first row of the tile, current k) + 32-bit lane offset; rows past the end of the
-    // matrix are clamped to its last row (their products are never stored).  The x loader and
-    // the weight loader each walk (tile, stage) on their own, ahead of the MFMAs: the ring does
-    // not drain at a tile boundary.  Every stage requests exactly one x slot and one weight
-    // slot, so the reduction loop has a single branch-free body; what changes between stages
-    // (second reduction part, next tile) is patched into the loader state after the body.  A
-    // loader that has run out of tiles keeps re-requesting its last slot into buffers nobody
-    // reads (stepA / stepB = 0), which only happens in the last two stages of the kernel.
+    // matrix are clamped to its last row (their products are never stored).  The loader walks
+    // (tile, stage) on its own, two stages ahead of the MFMAs: the ring does not drain at a tile
+    // boundary.  Every stage requests exactly one x slot and one weight slot (the x slot half a
+    // stage before the weight slot), so the reduction loop has a single branch-free body and one
+    // walker serves both operands; what changes between stages (second reduction part, next tile)
+    // is patched into the loader state after the body.  A loader that has run out of tiles keeps
+    // re-requesting its last slots into buffers nobody reads (stepL = 0), which only happens in
+    // the last two stages of the kernel.
     uint32_t voffA[LPW], voffB[LPW];
     const char* sA = nullptr;
     const char* sB = nullptr;
-    int32_t vA = (int32_t)blockIdx.x, vB = (int32_t)blockIdx.x;
-    int cntA = 0, cntB = 0, SA = 0, SB = 0;          // next stage to request, stages of the loader's tile
-    int stepA = ROW_BYTES, stepB = ROW_BYTES;
+    int32_t vL = (int32_t)blockIdx.x;
+    int cntL = 0, SL = 0;                            // stages requested of the loader's tile, stages it has
+    int stepL = ROW_BYTES;
     int64_t m0A = 0, n0B = 0;
-    bool validA = false, validB = false;
+    bool validL = false;
     // (the lane index is made opaque where rarely-run code derives addresses from it: otherwise the
     // compiler computes all of that once, ahead of the tile loop, and the values crowd the register file)
     auto set_A = [&](const void* base, int64_t ld) {
@@ -148,43 +145,30 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             voffB[i] = (uint32_t)(((n - n0B) * ld + ch * 8) * 2);
         }
     };
-    auto tile_A = [&]() {
+    auto tile_L = [&]() {
         int32_t bm = 0, bn = 0;
-        validA = tile_of(vA, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn);
-        if (validA) {
+        validL = tile_of(vL, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn);
+        if (validL) {
             m0A = (int64_t)bm * BM;
-            SA = stages_of(bm);
-            cntA = 0;
-            set_A(a.A1, a.lda1);
-        } else {
-            sA -= ROW_BYTES;          // stay on the last slot requested
-            stepA = 0;
-        }
-    };
-    auto tile_B = [&]() {
-        int32_t bm = 0, bn = 0;
-        validB = tile_of(vB, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn);
-        if (validB) {
             n0B = (int64_t)bn * BN;
-            SB = stages_of(bm);
-            cntB = 0;
+            SL = stages_of(bm);
+            cntL = 0;
+            set_A(a.A1, a.lda1);
             set_B(a.B1, a.ldb1);
         } else {
+            sA -= ROW_BYTES;          // stay on the last slots requested
             sB -= ROW_BYTES;
-            stepB = 0;
+            stepL = 0;
         }
     };
-    // after a request: move the loader to its next tile, or to the second reduction part
-    auto patch_A = [&]() {
-        if (validA) {
-            if (cntA == SA) { vA += v_step; tile_A(); }
-            else if (cntA == KS) set_A(a.A2, a.lda2);          // from x to uhat
-        }
-    };
-    auto patch_B = [&]() {
-        if (validB) {
-            if (cntB == SB) { vB += v_step; tile_B(); }
-            else if (cntB == KS) set_B(a.B2, a.ldb2);          // from W^T to B^T
+    // after a stage's two requests: move the loader to its next tile, or to the second reduction part
+    auto patch_L = [&]() {
+        if (validL) {
+            if (cntL == SL) { vL += v_step; tile_L(); }
+            else if (cntL == KS) {
+                set_A(a.A2, a.lda2);                           // from x to uhat
+                set_B(a.B2, a.ldb2);                           // from W^T to B^T
+            }
         }
     };
     // one slot = 8 load instructions per wave
@@ -196,18 +180,17 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
                                                  // the scalar-base + 32-bit-offset form (in place: no copy)
             load_lds_16(sA + voffA[i], base + i * 1024);
         }
-        sA += stepA;
-        ++cntA;
+        sA += stepL;
     };
-    auto slot_B = [&](int buf) {
+    auto slot_B = [&](int buf) {                 // the second request of a stage: counts it
         char* base = smem + buf * SLOT_BYTES + wave * LPW * 1024;
 #pragma unroll
         for (int i = 0; i < LPW; ++i) {
             asm volatile("" : "+v"(voffB[i]));
             load_lds_16(sB + voffB[i], base + i * 1024);
         }
-        sB += stepB;
-        ++cntB;
+        sB += stepL;
+        ++cntL;
     };
 
     // ---- fragment addressing: lane l reads row l % 16 of a block, chunk 4 kk + l / 16 ----
@@ -271,12 +254,9 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
     // ---- this workgroup's first tile; prologue: slots x0 w0 x1 w1 into buffers 0..3 ----
     int32_t vC = (int32_t)blockIdx.x, bm = 0, bn = 0;
     if (!tile_of(vC, n_virtual, a.tiles_m, a.tiles_n, &bm, &bn)) return;
-    tile_A();
-    tile_B();
-    slot_A(0); patch_A();
-    slot_B(1); patch_B();
-    slot_A(2); patch_A();
-    slot_B(3); patch_B();
+    tile_L();
+    slot_A(0); slot_B(1); patch_L();
+    slot_A(2); slot_B(3); patch_L();
     wait_cnt<2 * LPW, 15>();          // stage 0 has landed
     sync();
     int bA = 0, bB = 1;               // buffers of the stage being computed
@@ -299,10 +279,7 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             wait_cnt<LPW, 0>();
             sync();
             read_frags(nA, nB, 0, 0); slot_B(bA); mfma_step(1); order_step();
-            if (patch) {
-                patch_A();
-                patch_B();
-            }
+            if (patch) patch_L();
             pA = bB; bA = nA; bB = nB;
         };
         // The first stage is peeled out of the loops: with the cleared accumulators entering a loop

@@ -29,7 +29,9 @@ __device__ __forceinline__ int bucket_of(int32_t r_eff, const Ladder& lad) {
 // ------------------------------------------------------------------------------------------
 // Per-token gate table (token_meta.h has the lookup).
 // A block of 256 threads covers 4 rank blocks of 64 rows; in token order (no grouping) each
-// wavefront also reduces the largest effective rank of its 64 rows into blk_r.
+// wavefront also reduces the largest effective rank of its 64 rows into blk_r.  The table has four
+// entries for every started group of 256 rows (0 for blocks past the last row), so that a 256-row
+// tile reads its four with one aligned 16-byte load.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
@@ -59,7 +61,7 @@ token_meta_kernel(int64_t n_rows, const int32_t* __restrict__ seq_offsets, int32
             r_eff = o > r_eff ? o : r_eff;
         }
         const int64_t blk = t / kRankBlock;
-        if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r_eff;
+        if ((threadIdx.x & 63) == 0) blk_r[blk] = r_eff;        // all four entries of the 256 rows, 0 past the end
     }
 }
 
@@ -227,7 +229,7 @@ block_rank_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32
         r = o > r ? o : r;
     }
     const int64_t blk = g / kRankBlock;
-    if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r;
+    if ((threadIdx.x & 63) == 0) blk_r[blk] = r;
 }
 
 // largest effective rank per block of 64 rows, from gate entries the caller supplies (ranks
@@ -248,7 +250,7 @@ block_rank_from_gate_kernel(int64_t n_rows, const TokMeta* __restrict__ gate, in
         r = o > r ? o : r;
     }
     const int64_t blk = t / kRankBlock;
-    if ((threadIdx.x & 63) == 0 && blk * kRankBlock < n_rows) blk_r[blk] = r;
+    if ((threadIdx.x & 63) == 0) blk_r[blk] = r;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -399,7 +401,7 @@ WsLayout ws_layout(const cwl_linear_desc* d) {
     const size_t R = (size_t)padded_rank(d->r_max);
     size_t off = 0;
     L.meta = off; off = align_up(off + sizeof(TokMeta) * (n + 1), 256);
-    L.blk_r = off; off = align_up(off + sizeof(int32_t) * (n / kRankBlock + 2), 256);
+    L.blk_r = off; off = align_up(off + sizeof(int32_t) * 4 * (n / 256 + 1), 256);   // four entries per 256 rows, padded
     L.r_eff = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.perm = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
