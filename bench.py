@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--all-projections", action="store_true",
                     help="also time the linear of every projection of the workload (own x, W, A, B; the same "
                          "chunk table) and report the sum")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the compact block on the other bf16 workloads (cfg2, cfg3 with all seven projections "
+                         "on one chunk table, cfg4)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings against)")
@@ -55,6 +58,115 @@ def read_traffic(tag):
             if line.startswith("traffic_bytes_per_launch."):
                 key, val = line.split(":", 1)
                 out[key.split(".", 1)[1].strip()] = float(val.split()[0])
+    return out
+
+
+def other_workload(name, steps, warmup):
+    """Compact figures of one of the other bf16 workloads: one whole step = score_tokens, partition_chunks,
+    select_ranks once and the linear of EVERY projection of the workload on that one chunk table (own x, W, A,
+    B each, weights prepacked).  Returns step time, the scoring kernel's HBM rate and, per projection, the whole
+    call and its main GEMM against the bf16 MFMA peak."""
+    import numpy as np
+    import torch
+    from paper_2601_21109_amd import binding as B
+    from paper_2601_21109_amd import workloads as W
+    dev = "cuda:0"
+    wl = W.WORKLOADS[name]
+    N, K = wl.n_rows, len(wl.ladder)
+    so = W.seq_offsets(wl)
+    sod = torch.from_numpy(so).to(dev)
+    h = torch.empty(N, dtype=torch.float32, device=dev)
+    tile = wl.logit_tile_rows or N
+    n_tiles = N // tile
+    sig = W.token_sigmas(wl)
+    for t in range(n_tiles):                        # scores of the real logits, tile by tile through one buffer
+        logits = W.logits_rows(wl, t * tile, (t + 1) * tile, dev, sigmas=sig)
+        B.score_tokens(logits, out=h[t * tile:(t + 1) * tile])
+    h_sink = torch.empty(tile, dtype=torch.float32, device=dev)
+    table = B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+    ri = B.select_ranks(table, wl.taus(), K)
+    projs = []
+    for p_i, (p_name, p_in, p_out) in enumerate(wl.projections):
+        xp, Wp, Ap, Bp = W.linear_operands(wl, p_i, dev)
+        pk = B.prepack_weights(Wp, Ap, Bp)
+        del Wp, Ap, Bp
+        projs.append((p_name, p_in, p_out, xp, pk, torch.empty((N, p_out), dtype=wl.dtype, device=dev),
+                      B.linear_workspace((N, p_in), wl.dtype, p_out, wl.r_max, wl.ladder, wl.scales, wl.blend_w, dev)))
+    torch.cuda.synchronize()
+
+    def linear(pr):
+        B.chunkwise_lora_linear(pr[3], pr[4], None, None, wl.ladder, wl.scales, wl.blend_w, sod, table, ri,
+                                out=pr[5], workspace=pr[6])
+
+    def step():
+        for t in range(n_tiles):                    # with tiles: the last tile's buffer stands in for all of them
+            B.score_tokens(logits, out=h_sink if n_tiles > 1 else h)
+        B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), out=table)
+        B.select_ranks(table, wl.taus(), K, out=ri)
+        for pr in projs:
+            linear(pr)
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ms_step = timed(step, steps)
+    # effective ranks of the rows, for the algorithmic flops
+    n_chunks = int(table["chunk_offsets"][-1].item())
+    cl = table["chunk_len"][:n_chunks].cpu().numpy()
+    cs = table["chunk_start"][:n_chunks].cpu().numpy()
+    co = table["chunk_offsets"].cpu().numpy()
+    rk = np.asarray(wl.ladder)[ri[:n_chunks].cpu().numpy()]
+    r_sum = 0.0
+    for b in range(wl.n_seqs):
+        for c in range(co[b], co[b + 1]):
+            r_sum += float(rk[c]) * float(cl[c])
+            if c > co[b] and wl.blend_w:
+                r_sum += float(max(rk[c], rk[c - 1]) - rk[c]) * float(min(wl.blend_w, cl[c]))
+    B.profile_enable((B.PROF_SCORE,))
+    for _ in range(steps):
+        for t in range(n_tiles):
+            B.score_tokens(logits, out=h_sink if n_tiles > 1 else h)
+    torch.cuda.synchronize()
+    t_s, n_s = B.profile_read(B.PROF_SCORE)
+    B.profile_enable(False)
+    score_ms = t_s / max(n_s, 1)
+    score_gbs = tile * (wl.vocab * 2 + 4.0) / (score_ms * 1e-3) / 1e9
+    calls, fl_all, ms_all = {}, 0.0, 0.0
+    for pr in projs:
+        p_name, p_in, p_out = pr[0], pr[1], pr[2]
+        call_ms = timed(lambda: linear(pr), max(steps // 2, 2))
+        B.profile_enable((B.PROF_MAIN,))
+        for _ in range(max(steps // 2, 2)):
+            linear(pr)
+        torch.cuda.synchronize()
+        t_m, n_m = B.profile_read(B.PROF_MAIN)
+        B.profile_enable(False)
+        main_ms = t_m / max(n_m, 1)
+        fl_call = 2.0 * N * p_in * p_out + 2.0 * r_sum * (p_in + p_out)
+        fl_main = 2.0 * N * p_in * p_out + 2.0 * r_sum * p_out
+        calls[p_name if p_name not in calls else f"{p_name}_{len(calls)}"] = {
+            "d_in": p_in, "d_out": p_out, "call_ms": call_ms,
+            "call_frac_of_bf16_peak": fl_call / (call_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "main_ms": main_ms, "main_frac_of_bf16_peak": fl_main / (main_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        fl_all += fl_call
+        ms_all += call_ms
+    out = {"n_rows": N, "vocab": wl.vocab, "ladder": wl.ladder, "chunks": n_chunks, "mean_r_eff": r_sum / N,
+           "steps": steps, "step_ms": ms_step, "tokens_per_s": N / (ms_step * 1e-3),
+           "score": {"ms_per_launch": score_ms, "launches_per_step": n_tiles, "GBps": score_gbs,
+                     "frac_of_hbm_peak": score_gbs / PEAK_HBM_GBS},
+           "linear_calls": calls,
+           "all_calls_frac_of_bf16_peak": fl_all / (ms_all * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    del projs, logits
+    torch.cuda.empty_cache()
     return out
 
 
@@ -122,6 +234,9 @@ def main():
     # few microseconds, so the other kernels are timed in a second pass of K steps right after.
     slots = (("score", B.PROF_SCORE), ("partition", B.PROF_PARTITION), ("select", B.PROF_SELECT),
              ("meta", B.PROF_META), ("shrink", B.PROF_SHRINK), ("main", B.PROF_MAIN))
+    # first exactly what the flags say, out of idle: W warm-up steps, K timed steps (reported as
+    # "first_pass"); then the spin-up steps and the sustained measurement that the headline uses
+    first_ms, _ = timed(step, args.steps, args.warmup)
     for _ in range(max(args.spin_up, 0)):
         step()
     torch.cuda.synchronize()
@@ -167,6 +282,10 @@ def main():
         "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "spin_up_steps": max(args.spin_up, 0),
         "ms_per_step": ms_step,
+        "first_pass": {"note": "the same K steps after the W warm-up steps only, straight out of idle (inside the "
+                               "clock dip that follows the first launches); the headline is measured after "
+                               "spin_up_steps more untimed steps",
+                       "ms_per_step": first_ms, "value": N / (first_ms * 1e-3)},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -200,6 +319,12 @@ def main():
                                         "traffic": traffic.get("score"), "avg_launch_ms": kern_ms["score"],
                                         "bytes_per_launch": bytes_score}
     lin_ms = sum(kern_ms[k] or 0.0 for k in ("meta", "shrink", "main"))
+    if lin_ms and "roofline" in out and bf16:
+        # the benchmark spec's target is stated for the whole call: gate table + shrink + main GEMM, priced with
+        # the whole layer's algorithmic flops
+        out["roofline"]["whole_call"] = {"kernels": "token_meta + shrink + main", "ms": lin_ms,
+                                         "flops": flops_alg, "achieved": flops_alg / (lin_ms * 1e-3) / 1e12,
+                                         "frac": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     out["linear"] = {"ms": lin_ms, "tokens_per_s": N / (lin_ms * 1e-3) if lin_ms else None,
                      "effective_tflops": flops_alg / (lin_ms * 1e-3) / 1e12 if lin_ms else None,
                      "frac_of_bf16_peak": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if lin_ms else None}
@@ -390,9 +515,10 @@ def main():
                                "d_in": d_in, "d_out": d_out, "r": wl.r_max,
                                "ms": (time.perf_counter() - t0) * 1e3}
 
-    # ---- projections that share x (q/k/v) as ONE projection: weights fused by columns, adapter
-    #      [Aq|Ak|Av] with block-diagonal B, ladder rebuilt on the fused update; against three calls ----
-    if not args.no_variants and bf16 and d_in == d_out and 3 * wl.r_max <= B.MAX_RANK:
+    # ---- projections that share x (q/k/v): three calls against ONE grouped call (each projection on its own
+    #      rungs: the same layers), and against one call on the fused weights with the ladder of the fused
+    #      adapter (the joint best truncation below full rank: NOT the same layers) ----------------------
+    if not args.no_variants and bf16 and d_in == d_out:
         gq = torch.Generator(device=dev)
         gq.manual_seed(1234)
         mk = lambda shape, scale: (torch.randn(shape, generator=gq, device=dev) * scale).to(wl.dtype)
@@ -400,12 +526,16 @@ def main():
         As3 = [A] + [mk((d_in, wl.r_max), d_in ** -0.5) for _ in range(2)]
         Bs3 = [Bm] + [mk((wl.r_max, d_out), wl.r_max ** -0.5) for _ in range(2)]
         pk3 = [packed] + [B.prepack_weights(w_, a_, b_) for w_, a_, b_ in zip(Ws3[1:], As3[1:], Bs3[1:])]
-        Bf = torch.zeros((3 * wl.r_max, 3 * d_out), dtype=wl.dtype, device=dev)
-        for i in range(3):
-            Bf[i * wl.r_max:(i + 1) * wl.r_max, i * d_out:(i + 1) * d_out] = Bs3[i]
-        A2f, B2f, _ = B.build_ladder(torch.cat(As3, dim=1).contiguous(), Bf)
-        pkf = B.prepack_weights(torch.cat(Ws3, dim=1).contiguous(), A2f, B2f)
-        del Bf, A2f, B2f, Ws3, As3, Bs3
+        pg3 = B.prepack_weights_grouped(Ws3, As3, Bs3)
+        joint = 3 * wl.r_max <= B.MAX_RANK
+        if joint:
+            Bf = torch.zeros((3 * wl.r_max, 3 * d_out), dtype=wl.dtype, device=dev)
+            for i in range(3):
+                Bf[i * wl.r_max:(i + 1) * wl.r_max, i * d_out:(i + 1) * d_out] = Bs3[i]
+            A2f, B2f, _ = B.build_ladder(torch.cat(As3, dim=1).contiguous(), Bf)
+            pkf = B.prepack_weights(torch.cat(Ws3, dim=1).contiguous(), A2f, B2f)
+            del Bf, A2f, B2f
+        del Ws3, As3, Bs3
         lad3 = [3 * v for v in wl.ladder]
         fused = {}
         for rows in (64, N):
@@ -416,7 +546,7 @@ def main():
                 sod_q, tab_q, rid_q = B.table_from_host(*tb, dev)
                 x_q = x[:rows]
             ws1 = B.linear_workspace((rows, d_in), wl.dtype, d_out, wl.r_max, wl.ladder, wl.scales, wl.blend_w, dev)
-            wsf = B.linear_workspace((rows, d_in), wl.dtype, 3 * d_out, 3 * wl.r_max, lad3, wl.scales, wl.blend_w, dev)
+            wsg = B.grouped_workspace(rows, pg3, wl.ladder, wl.scales, wl.blend_w, dev)
             y1 = torch.empty((rows, d_out), dtype=wl.dtype, device=dev)
             yf = torch.empty((rows, 3 * d_out), dtype=wl.dtype, device=dev)
 
@@ -425,18 +555,34 @@ def main():
                     B.chunkwise_lora_linear(x_q, pk, None, None, wl.ladder, wl.scales, wl.blend_w, sod_q, tab_q,
                                             rid_q, out=y1, workspace=ws1)
 
-            def one():
-                B.chunkwise_lora_linear(x_q, pkf, None, None, lad3, wl.scales, wl.blend_w, sod_q, tab_q, rid_q,
-                                        out=yf, workspace=wsf)
+            def grouped():
+                B.chunkwise_lora_linear_grouped(x_q, pg3, wl.ladder, wl.scales, wl.blend_w, sod_q, tab_q, rid_q,
+                                                out=yf, workspace=wsg)
 
             reps = max(args.steps // 2, 5)
             fused[str(rows)] = {"three_calls_us": timed(three, reps, 3)[0] * 1e3,
-                                "one_fused_call_us": timed(one, reps, 3)[0] * 1e3}
-            del ws1, wsf, y1, yf
-        del pk3, pkf
+                                "one_grouped_call_us": timed(grouped, reps, 3)[0] * 1e3}
+            if joint:
+                wsf = B.linear_workspace((rows, d_in), wl.dtype, 3 * d_out, 3 * wl.r_max, lad3, wl.scales,
+                                         wl.blend_w, dev)
+
+                def one():
+                    B.chunkwise_lora_linear(x_q, pkf, None, None, lad3, wl.scales, wl.blend_w, sod_q, tab_q, rid_q,
+                                            out=yf, workspace=wsf)
+
+                fused[str(rows)]["one_call_on_jointly_truncated_weights_us"] = timed(one, reps, 3)[0] * 1e3
+                del wsf
+            del ws1, wsg, y1, yf
+        del pk3, pg3
+        if joint:
+            del pkf
         torch.cuda.empty_cache()
-        out["fused_qkv"] = {"note": "three d_in -> d_out projections of the same x: three calls against one call on "
-                                    "[Wq|Wk|Wv] with the ladder of the fused adapter (ranks x 3)", **fused}
+        out["grouped_qkv"] = {"note": "three d_in -> d_out projections of the same x: three calls against one "
+                                      "grouped call (cwl_chunkwise_lora_linear_grouped_packed: the same three "
+                                      "layers, each on its own rungs); 'jointly_truncated': one call on [Wq|Wk|Wv] "
+                                      "with the ladder rebuilt on the fused adapter (ranks x 3), which below full "
+                                      "rank is a different, jointly truncated layer and is listed for its timing "
+                                      "only", **fused}
 
     # ---- every projection of the workload with the same chunk table -------------------------------
     if args.all_projections:
@@ -489,6 +635,18 @@ def main():
                                "sample": f"entropy on {n_ent} rows ({t_ent:.2f} s), partition+select on all "
                                          f"{N} rows ({t_part:.3f} s), linear on {len(rows_l)} rows "
                                          f"({t_lin:.2f} s); tokens/s extrapolated from the per-row times"}
+    # ---- the other bf16 workloads, compact (whole step with every projection on one chunk table) ---
+    if not args.no_other_workloads and not args.no_variants and args.workload == "cfg1":
+        del logits, x, Wm, A, Bm, packed, y, ws
+        torch.cuda.empty_cache()
+        n_other = max(3, min(args.steps // 4, 10))
+        out["other_workloads"] = {"note": "one step = scoring, partition and select once + the linear of every "
+                                          "projection of the workload on that chunk table; call = gate table + "
+                                          "shrink + main GEMM of one projection; fractions against the 2.5 PFLOP/s "
+                                          "bf16 peak with the method's own flops (r_eff, not r_max)"}
+        for other in ("cfg2", "cfg3", "cfg4"):
+            out["other_workloads"][other] = other_workload(other, n_other, 3)
+
     print(json.dumps(out))
 
 

@@ -270,7 +270,9 @@ typedef struct {
     cwl_dtype dt;
     int64_t ldx, ldw, lda, ldb, ldy;
     int32_t group_rows;      /* 0: rows in token order; 1: group token rows by rank bucket so
-                                that row tiles are rank-homogeneous (same result)             */
+                                that row tiles are rank-homogeneous (same result; from 65536
+                                rows up the fp32 sums of x A run in another order, so the last
+                                bit of a bf16 output may differ between the two settings)      */
 } cwl_linear_desc;
 
 size_t cwl_packed_weights_bytes(const cwl_linear_desc* d);
@@ -419,6 +421,52 @@ cwl_status cwl_stream_step_aligned(const float* entropy, int32_t n_seqs, const c
 cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x, const void* packed,
                                         const cwl_token_gate* gate, void* y, void* workspace,
                                         size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Projections that share their input (Sec. III-C and III-F: every LoRA-carrying projection of a layer
+ * slices its own ladder under the one chunk table; q/k/v read the same x, so do gate/up).  A group
+ * is 1 .. CWL_MAX_GROUP projections p with the same d_in, r_max, ladder and element type, each with
+ * its own W_p [d_in, d_out_p], A_p [d_in, r_max], B_p [r_max, d_out_p] (all contiguous, row-major).
+ * The grouped calls give exactly the layer of cwl_chunkwise_lora_linear for every projection,
+ *      y[:, c_p : c_p + d_out_p] = x W_p + (gated x A_p[:, :r]) B_p[:r, :],    c_p = d_out_0 + .. + d_out_{p-1},
+ * every projection on the prefixes of ITS OWN factors, in one wide output y [n_rows, sum d_out_p]:
+ * the gate table is made once, one shrink pass over x serves the adapters of all projections (as
+ * many as have 256 directions together per pass), and up to 512 rows the weights of all projections
+ * are streamed by one launch.  In `d`: d_out = sum of d_out_p, ldw / lda / ldb are not used,
+ * group_rows must be 0.  Sums may run in another order than in the single-projection calls.
+ *
+ *   cwl_group.W / A / B   device pointers, read by cwl_prepack_weights_grouped only
+ *   packed     >= cwl_packed_weights_grouped_bytes(d, g) bytes, 256-byte aligned
+ *   workspace  >= cwl_linear_grouped_workspace_bytes(d, g) bytes
+ *   the other arguments as for cwl_chunkwise_lora_linear_packed / cwl_gated_lora_linear_packed
+ * ------------------------------------------------------------------------------------------- */
+#define CWL_MAX_GROUP 8
+
+typedef struct {
+    int32_t n_proj;
+    int64_t d_out[CWL_MAX_GROUP];
+    const void* W[CWL_MAX_GROUP];
+    const void* A[CWL_MAX_GROUP];
+    const void* B[CWL_MAX_GROUP];
+} cwl_group;
+
+size_t cwl_packed_weights_grouped_bytes(const cwl_linear_desc* d, const cwl_group* g /*host*/);
+size_t cwl_linear_grouped_workspace_bytes(const cwl_linear_desc* d, const cwl_group* g /*host*/);
+
+cwl_status cwl_prepack_weights_grouped(const cwl_linear_desc* d, const cwl_group* g /*host*/, void* packed,
+                                       size_t packed_bytes, void* stream);
+
+cwl_status cwl_chunkwise_lora_linear_grouped_packed(const cwl_linear_desc* d, const cwl_group* g /*host*/,
+                                                    const void* x, const void* packed,
+                                                    const int32_t* seq_offsets, int32_t n_seqs,
+                                                    const int32_t* chunk_offsets, const int32_t* chunk_start,
+                                                    const int32_t* chunk_len, const int32_t* rank_idx,
+                                                    int32_t chunk_cap, void* y, void* workspace,
+                                                    size_t workspace_bytes, void* stream);
+
+cwl_status cwl_gated_lora_linear_grouped_packed(const cwl_linear_desc* d, const cwl_group* g /*host*/,
+                                                const void* x, const void* packed, const cwl_token_gate* gate,
+                                                void* y, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * cwl_build_ladder -- the rank ladder of a trained adapter (Sec. III-C: obtained once by an SVD of

@@ -18,6 +18,7 @@ F32, BF16 = 0, 1
 STATUS_CAPACITY, STATUS_NAN_SCORE, STATUS_BAD_OFFSETS, STATUS_BAD_BUCKET = 1, 2, 4, 8
 MAX_LADDER, MAX_RANK = 16, 256
 STATIC_SCRATCH_BYTES = 16 << 20
+MAX_GROUP = 8
 
 EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_compose_scores",
            "cwl_partition_workspace_bytes", "cwl_partition_chunks", "cwl_select_ranks",
@@ -27,7 +28,10 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_chunkwise_lora_linear_packed_static",
            "cwl_stream_step", "cwl_stream_step_aligned",
-           "cwl_gated_lora_linear_packed", "cwl_ladder_workspace_bytes", "cwl_build_ladder",
+           "cwl_gated_lora_linear_packed", "cwl_packed_weights_grouped_bytes",
+           "cwl_linear_grouped_workspace_bytes", "cwl_prepack_weights_grouped",
+           "cwl_chunkwise_lora_linear_grouped_packed", "cwl_gated_lora_linear_grouped_packed",
+           "cwl_ladder_workspace_bytes", "cwl_build_ladder",
            "cwl_profile_enable", "cwl_profile_read"]
 PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
 PROF_SLOTS = 6
@@ -50,6 +54,12 @@ class LinearDesc(ctypes.Structure):
                 ("blend_w", ctypes.c_int32), ("dt", ctypes.c_int),
                 ("ldx", ctypes.c_int64), ("ldw", ctypes.c_int64), ("lda", ctypes.c_int64),
                 ("ldb", ctypes.c_int64), ("ldy", ctypes.c_int64), ("group_rows", ctypes.c_int32)]
+
+
+class Group(ctypes.Structure):
+    _fields_ = [("n_proj", ctypes.c_int32), ("d_out", ctypes.c_int64 * MAX_GROUP),
+                ("W", ctypes.c_void_p * MAX_GROUP), ("A", ctypes.c_void_p * MAX_GROUP),
+                ("B", ctypes.c_void_p * MAX_GROUP)]
 
 
 class CwlError(RuntimeError):
@@ -108,6 +118,12 @@ def lib():
     L.cwl_gated_lora_linear_packed.argtypes = [dp, P, P, P, P, P, sz, P]
     L.cwl_profile_enable.argtypes = [i32]
     L.cwl_profile_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    gp = ctypes.POINTER(Group)
+    L.cwl_packed_weights_grouped_bytes.argtypes = [dp, gp]
+    L.cwl_linear_grouped_workspace_bytes.argtypes = [dp, gp]
+    L.cwl_prepack_weights_grouped.argtypes = [dp, gp, P, sz, P]
+    L.cwl_chunkwise_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
+    L.cwl_gated_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_static.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P]
     # return types: byte counts are size_t, everything else but the two informational calls a status
     for name in EXPORTS:
@@ -397,6 +413,104 @@ def chunkwise_lora_linear_static(x, packed, ranks, scales, blend_w, seq_offsets,
         d.ref(), _ptr(x), _ptr(packed.blob), _ptr(seq_offsets), seq_offsets.numel() - 1,
         _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
         table["cap"], _ptr(out), _stream()), "cwl_chunkwise_lora_linear_packed_static")
+    return out
+
+
+class PackedGroup:
+    """Static weights of projections that share x, re-laid out side by side by cwl_prepack_weights_grouped."""
+
+    def __init__(self, blob, d_in, d_outs, r_max, dtype):
+        self.blob, self.d_in, self.d_outs, self.r_max, self.dtype = blob, d_in, list(d_outs), r_max, dtype
+        self.d_out = sum(self.d_outs)
+
+    def group(self, Ws=None, As=None, Bs=None):
+        g = Group()
+        g.n_proj = len(self.d_outs)
+        for p, n in enumerate(self.d_outs):
+            g.d_out[p] = n
+            if Ws is not None:
+                g.W[p], g.A[p], g.B[p] = Ws[p].data_ptr(), As[p].data_ptr(), Bs[p].data_ptr()
+        return g
+
+    def split(self, y):
+        """Views of the wide output, one per projection."""
+        outs, c = [], 0
+        for n in self.d_outs:
+            outs.append(y[:, c:c + n])
+            c += n
+        return outs
+
+
+def _group_desc(x, pg, ranks, scales, blend_w, y):
+    return _desc_for(x, pg.d_out, pg.r_max, ranks, scales, blend_w, y)
+
+
+def prepack_weights_grouped(Ws, As, Bs):
+    """Lists of W_p [d_in, d_out_p], A_p [d_in, r_max], B_p [r_max, d_out_p] (contiguous, same d_in, r_max and
+    dtype) -> PackedGroup."""
+    assert 1 <= len(Ws) <= MAX_GROUP and len(As) == len(Ws) and len(Bs) == len(Ws)
+    d_in, r_max, dtype, dev = Ws[0].shape[0], As[0].shape[1], Ws[0].dtype, Ws[0].device
+    for W, A, B in zip(Ws, As, Bs):
+        assert W.is_cuda and W.is_contiguous() and A.is_contiguous() and B.is_contiguous()
+        assert W.shape[0] == d_in and A.shape == (d_in, r_max) and B.shape == (r_max, W.shape[1])
+        assert W.dtype == dtype and A.dtype == dtype and B.dtype == dtype
+    pg = PackedGroup(None, d_in, [W.shape[1] for W in Ws], r_max, dtype)
+    dummy_x = torch.empty((1, d_in), dtype=dtype, device=dev)
+    dummy_y = torch.empty((1, pg.d_out), dtype=dtype, device=dev)
+    d = _group_desc(dummy_x, pg, [r_max], [1.0], 0, dummy_y)
+    d.c.n_rows = 0
+    g = pg.group(Ws, As, Bs)
+    nbytes = lib().cwl_packed_weights_grouped_bytes(d.ref(), ctypes.byref(g))
+    if nbytes == 0:
+        raise CwlError(ERR_INVALID_ARG, "cwl_packed_weights_grouped_bytes")
+    pg.blob = _ws(nbytes, dev)
+    _check(lib().cwl_prepack_weights_grouped(d.ref(), ctypes.byref(g), _ptr(pg.blob), pg.blob.numel(), _stream()),
+           "cwl_prepack_weights_grouped")
+    return pg
+
+
+def grouped_workspace(n_rows, pg, ranks, scales, blend_w, device):
+    x = torch.empty((1, pg.d_in), dtype=pg.dtype, device=device)
+    y = torch.empty((1, pg.d_out), dtype=pg.dtype, device=device)
+    d = _group_desc(x, pg, ranks, scales, blend_w, y)
+    d.c.n_rows = n_rows
+    d.c.ldx, d.c.ldy = pg.d_in, pg.d_out
+    g = pg.group()
+    return _ws(lib().cwl_linear_grouped_workspace_bytes(d.ref(), ctypes.byref(g)), device)
+
+
+def chunkwise_lora_linear_grouped(x, pg, ranks, scales, blend_w, seq_offsets, table, rank_idx, out=None,
+                                  workspace=None):
+    """The layer for every projection of a PackedGroup at once; returns the wide output
+    [n_rows, sum d_out_p] (PackedGroup.split gives the per-projection views)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(pg, PackedGroup)
+    assert pg.dtype == x.dtype and pg.d_in == x.shape[1]
+    if out is None:
+        out = torch.empty((x.shape[0], pg.d_out), dtype=x.dtype, device=x.device)
+    d = _group_desc(x, pg, ranks, scales, blend_w, out)
+    g = pg.group()
+    need = lib().cwl_linear_grouped_workspace_bytes(d.ref(), ctypes.byref(g)) or 256
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    _check(lib().cwl_chunkwise_lora_linear_grouped_packed(
+        d.ref(), ctypes.byref(g), _ptr(x), _ptr(pg.blob), _ptr(seq_offsets), seq_offsets.numel() - 1,
+        _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
+        table["cap"], _ptr(out), _ptr(ws), ws.numel(), _stream()), "cwl_chunkwise_lora_linear_grouped_packed")
+    return out
+
+
+def gated_lora_linear_grouped(x, pg, gate, ranks, scales, out=None, workspace=None):
+    """gated_lora_linear for every projection of a PackedGroup at once (decode steps)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(pg, PackedGroup)
+    assert gate.is_cuda and gate.dtype == torch.int32 and gate.is_contiguous() and gate.shape == (x.shape[0], 4)
+    if out is None:
+        out = torch.empty((x.shape[0], pg.d_out), dtype=x.dtype, device=x.device)
+    d = _group_desc(x, pg, ranks, scales, 0, out)
+    g = pg.group()
+    need = lib().cwl_linear_grouped_workspace_bytes(d.ref(), ctypes.byref(g)) or 256
+    ws = workspace if workspace is not None else _ws(need, x.device)
+    _check(lib().cwl_gated_lora_linear_grouped_packed(d.ref(), ctypes.byref(g), _ptr(x), _ptr(pg.blob), _ptr(gate),
+                                                      _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "cwl_gated_lora_linear_grouped_packed")
     return out
 
 

@@ -104,10 +104,22 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
             }
         }
 #pragma unroll
-        for (int ni = 0; ni < NI; ++ni) ni_on[ni] = (wn * TN + ni * 32) < r_blk;
+        for (int ni = 0; ni < NI; ++ni) {
+            const int32_t c = (int32_t)n0 + wn * TN + ni * 32;      // 32 columns never straddle two adapters
+            ni_on[ni] = (a.gate_period > 0 ? c % a.gate_period : c) < r_blk;
+        }
         if (r_blk == 0) KS = 0;
     }
     int k_first = 0;                                  // first stage of this workgroup's slice
+    int k_wrap = -1;                                  // stages issued when a rotated walk wraps to stage 0
+    // Shrink with 256-row tiles (65536 rows and more, token order): all workgroups would walk the
+    // same columns of x at the same time, rows one leading dimension apart, which a few memory
+    // channels then serve (3.8 TB/s); tile bm starts its walk at stage bm % KS and wraps around
+    // instead (4.5 TB/s).  The fp32 sums of a row then run in a rotated order.
+    if (EPI == EPI_GATE && BM == 256 && !a.perm && KS > 1) {
+        k_first = bm % KS;
+        k_wrap = KS - k_first;
+    }
     if (EPI == EPI_PARTIAL) {
         k_first = split * a.ks_per_split;
         int k_end = k_first + a.ks_per_split;
@@ -162,6 +174,10 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
             gp[i] += BK;
         }
         ++issued;
+        if (EPI == EPI_GATE && issued == k_wrap) {
+#pragma unroll
+            for (int i = 0; i < LOADS; ++i) gp[i] -= a.K1;
+        }
     };
 
     // ---- fragment addressing ----
@@ -309,7 +325,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
                 for (int e = 0; e < 4; ++e) {
                     float v = acc[ni][mi][q * 4 + e];
                     if (EPI == EPI_GATE) {
-                        const int32_t i = (int32_t)n + e;
+                        const int32_t i = (a.gate_period > 0 ? (int32_t)(n % a.gate_period) : (int32_t)n) + e;
                         const float gate = (i < mt.r_prev ? mt.g_prev : 0.0f) + (i < mt.r_cur ? mt.g_cur : 0.0f);
                         v *= gate;
                     }

@@ -70,7 +70,8 @@ __global__ void __launch_bounds__(256) gemm_f32_tn_kernel(GemmArgs a) {
             for (int j = 0; j < 4; ++j) {
                 const int64_t n = n0 + tx * 4 + j;
                 if (n >= a.N) continue;
-                const float gate = (n < mt.r_prev ? mt.g_prev : 0.0f) + (n < mt.r_cur ? mt.g_cur : 0.0f);
+                const int64_t dir = a.gate_period > 0 ? n % a.gate_period : n;   // direction within its adapter
+                const float gate = (dir < mt.r_prev ? mt.g_prev : 0.0f) + (dir < mt.r_cur ? mt.g_cur : 0.0f);
                 C[g * a.ldc + n] = acc[i][j] * gate;
             }
         } else {

@@ -372,13 +372,15 @@ struct PackedLayout {       // byte offsets into the packed weight blob
     int32_t R;
 };
 
-PackedLayout packed_layout(const cwl_linear_desc* d) {
+// n_proj projections side by side (d->d_out: all their columns): W^T [d_out, d_in], the adapters'
+// A^T one after the other [n_proj R, d_in], B^T [d_out, R] (row n: the column of its own adapter)
+PackedLayout packed_layout(const cwl_linear_desc* d, int32_t n_proj = 1) {
     PackedLayout L;
     const size_t es = d->dt == CWL_F32 ? 4 : 2;
     L.R = padded_rank(d->r_max);
     size_t off = 0;
     L.wt = off; off = align_up(off + es * (size_t)d->d_out * (size_t)d->d_in, 256);
-    L.at = off; off = align_up(off + es * (size_t)L.R * (size_t)d->d_in, 256);
+    L.at = off; off = align_up(off + es * (size_t)n_proj * (size_t)L.R * (size_t)d->d_in, 256);
     L.bt = off; off = align_up(off + es * (size_t)d->d_out * (size_t)L.R, 256);
     L.total = off;
     return L;
@@ -394,11 +396,11 @@ bool small_rows_path(const cwl_linear_desc* d, const PackedLayout& P) {
            P.at == P.wt + sizeof(uint16_t) * (size_t)d->d_out * (size_t)d->d_in;
 }
 
-WsLayout ws_layout(const cwl_linear_desc* d) {
+WsLayout ws_layout(const cwl_linear_desc* d, int32_t n_proj = 1) {
     WsLayout L;
     const size_t es = d->dt == CWL_F32 ? 4 : 2;
     const size_t n = (size_t)d->n_rows;
-    const size_t R = (size_t)padded_rank(d->r_max);
+    const size_t R = (size_t)n_proj * (size_t)padded_rank(d->r_max);
     size_t off = 0;
     L.meta = off; off = align_up(off + sizeof(TokMeta) * (n + 1), 256);
     L.blk_r = off; off = align_up(off + sizeof(int32_t) * 4 * (n / 256 + 1), 256);   // four entries per 256 rows, padded
@@ -406,8 +408,8 @@ WsLayout ws_layout(const cwl_linear_desc* d) {
     L.perm = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
     L.partial = off;
-    if (small_rows_path(d, packed_layout(d))) off = align_up(off + small_rows_plan(d).partial_bytes, 256);
-    else if (shrink_split_plan(d).splits >= 2) off = align_up(off + shrink_split_plan(d).partial_bytes, 256);
+    if (small_rows_path(d, packed_layout(d, n_proj))) off = align_up(off + small_rows_plan(d, n_proj).partial_bytes, 256);
+    else if (n_proj == 1 && shrink_split_plan(d).splits >= 2) off = align_up(off + shrink_split_plan(d).partial_bytes, 256);
     L.total = off;
     return L;
 }
@@ -452,16 +454,72 @@ cwl_status prepack_typed(const cwl_linear_desc* d, const PackedLayout& L, const 
     return transpose_pad<T>(B, d->r_max, d->d_out, d->ldb, packed + L.bt, d->d_out, L.R, st);
 }
 
+// the weights of a group, projection by projection, into the rows of the shared W^T, A^T and B^T
+template <typename T>
+cwl_status prepack_group_typed(const cwl_linear_desc* d, const cwl_group* g, const PackedLayout& L,
+                               char* packed, hipStream_t st) {
+    int64_t col0 = 0;
+    for (int32_t p = 0; p < g->n_proj; ++p) {
+        const int64_t n = g->d_out[p];
+        char* wt = packed + L.wt + sizeof(T) * (size_t)col0 * (size_t)d->d_in;
+        char* at = packed + L.at + sizeof(T) * (size_t)p * (size_t)L.R * (size_t)d->d_in;
+        char* bt = packed + L.bt + sizeof(T) * (size_t)col0 * (size_t)L.R;
+        cwl_status s = transpose_pad<T>(g->W[p], d->d_in, n, n, wt, n, d->d_in, st);
+        if (s != CWL_OK) return s;
+        s = transpose_pad<T>(g->A[p], d->d_in, d->r_max, d->r_max > 0 ? d->r_max : 1, at, L.R, d->d_in, st);
+        if (s != CWL_OK) return s;
+        s = transpose_pad<T>(g->B[p], d->r_max, n, n, bt, n, L.R, st);
+        if (s != CWL_OK) return s;
+        col0 += n;
+    }
+    return CWL_OK;
+}
+
+// a group's shape: 1 .. CWL_MAX_GROUP projections whose columns add up to d->d_out; token order only
+cwl_status check_group(const cwl_linear_desc* d, const cwl_group* g) {
+    if (!g) return CWL_ERR_NULL;
+    if (g->n_proj < 1 || g->n_proj > CWL_MAX_GROUP) return CWL_ERR_INVALID_ARG;
+    int64_t sum = 0;
+    for (int32_t p = 0; p < g->n_proj; ++p) {
+        if (g->d_out[p] < 1 || g->d_out[p] > d->d_out) return CWL_ERR_INVALID_ARG;
+        if (d->dt == CWL_BF16 && g->d_out[p] % 8 != 0) return CWL_ERR_UNSUPPORTED;
+        sum += g->d_out[p];
+    }
+    if (sum != d->d_out) return CWL_ERR_INVALID_ARG;
+    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
+    return CWL_OK;
+}
+
+// Columns of the projections of a group, one after the other; a single projection is a group of one.
+GroupCols group_cols(const cwl_linear_desc* d, const cwl_group* g) {
+    GroupCols c = {};
+    if (!g) {
+        c.n_proj = 1;
+        c.cols[0] = d->d_out;
+        return c;
+    }
+    c.n_proj = g->n_proj;
+    int64_t off = 0;
+    for (int32_t p = 0; p < g->n_proj; ++p) {
+        c.col0[p] = off;
+        c.cols[p] = g->d_out[p];
+        off += g->d_out[p];
+    }
+    return c;
+}
+
 // `gate`: per-row gate entries supplied by the caller (then the chunk table is not looked at), or
-// NULL: the entries are derived from the chunk table
-cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packed,
+// NULL: the entries are derived from the chunk table.  `grp`: the projections that share x (their
+// weights packed side by side); every projection has its own directions of uhat and its own B.
+cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void* x, const char* packed,
                       const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                       const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
                       int32_t chunk_cap, const TokMeta* gate, void* y, char* ws, hipStream_t st) {
-    const PackedLayout P = packed_layout(d);
-    const WsLayout L = ws_layout(d);
+    const int32_t n_proj = grp.n_proj;
+    const PackedLayout P = packed_layout(d, n_proj);
+    const WsLayout L = ws_layout(d, n_proj);
     if (small_rows_path(d, P))
-        return run_small_rows(d, x, packed + P.wt, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
+        return run_small_rows(d, grp, x, packed + P.wt, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
                               chunk_start, chunk_len, rank_idx, chunk_cap, y,
                               reinterpret_cast<float*>(ws + L.partial),
                               reinterpret_cast<TokMeta*>(ws + L.meta), gate, st);
@@ -469,7 +527,9 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     int32_t* blk_r = reinterpret_cast<int32_t*>(ws + L.blk_r);
     int32_t* r_eff = reinterpret_cast<int32_t*>(ws + L.r_eff);
     int32_t* perm = reinterpret_cast<int32_t*>(ws + L.perm);
-    void* uhat = ws + L.uhat;
+    char* uhat = ws + L.uhat;
+    const size_t es = d->dt == CWL_F32 ? 4 : 2;
+    const int64_t R_all = (int64_t)n_proj * P.R;        // directions of all adapters: leading dimension of uhat
 
     Ladder lad = {};
     lad.K = d->K;
@@ -479,7 +539,10 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     }
     const bool grouped = d->group_rows == 1;
     const unsigned meta_blocks = (unsigned)((d->n_rows + 255) / 256);
-    const SmallPlan split = shrink_split_plan(d);      // splits >= 2: split shrink (bf16, token order)
+    // splits >= 2: split shrink (bf16, one projection)
+    SmallPlan split = {};
+    split.splits = 1;
+    if (n_proj == 1) split = shrink_split_plan(d);
     // with the split shrink in token order the gate table comes with the partial products
     const bool table_with_products = !gate && split.splits >= 2 && !grouped;
     prof_begin(CWL_PROF_META, st);
@@ -504,7 +567,7 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
     sh.K1 = (int32_t)d->d_in;
     sh.M = d->n_rows;     sh.N = P.R;
-    sh.C = uhat;          sh.ldc = P.R;
+    sh.C = uhat;          sh.ldc = R_all;
     sh.meta = meta;       sh.perm = grouped ? perm : nullptr;
     sh.gate_blk_r = blk_r;
 
@@ -512,14 +575,14 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
     mn.A1 = x;            mn.lda1 = d->ldx;
     mn.B1 = packed + P.wt; mn.ldb1 = d->d_in;
     mn.K1 = (int32_t)d->d_in;
-    mn.A2 = uhat;         mn.lda2 = P.R;
+    mn.A2 = uhat;         mn.lda2 = R_all;
     mn.B2 = packed + P.bt; mn.ldb2 = P.R;
     mn.blk_r = blk_r;
     mn.M = d->n_rows;     mn.N = d->d_out;
     mn.C = y;             mn.ldc = d->ldy;
     mn.meta = meta;       mn.perm = grouped ? perm : nullptr;
 
-    cwl_status s;
+    cwl_status s = CWL_OK;
     prof_begin(CWL_PROF_SHRINK, st);
     if (split.splits >= 2) {
         float* partial = reinterpret_cast<float*>(ws + L.partial);
@@ -555,18 +618,40 @@ cwl_status run_packed(const cwl_linear_desc* d, const void* x, const char* packe
             else if (split.splits <= 16) s = launch_shrink_fixup<16>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
             else s = launch_shrink_fixup<32>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
         }
-    } else {
+    } else if (n_proj == 1) {
         s = d->dt == CWL_F32 ? launch_gemm_f32(sh, EPI_GATE, st) : launch_shrink_bf16(sh, st);
+    } else {
+        // one shrink over the concatenated adapters: x is read once for as many adapters as fit the
+        // widest shrink tile (256 directions), their directions side by side in uhat
+        const int32_t per_launch = d->dt == CWL_F32 ? n_proj : (256 / P.R > 0 ? 256 / P.R : 1);
+        for (int32_t p0 = 0; p0 < n_proj && s == CWL_OK; p0 += per_launch) {
+            const int32_t np = n_proj - p0 < per_launch ? n_proj - p0 : per_launch;
+            GemmArgs g2 = sh;
+            g2.B1 = packed + P.at + es * (size_t)p0 * (size_t)P.R * (size_t)d->d_in;
+            g2.N = (int64_t)np * P.R;
+            g2.C = uhat + es * (size_t)p0 * (size_t)P.R;
+            g2.gate_period = P.R;
+            s = d->dt == CWL_F32 ? launch_gemm_f32(g2, EPI_GATE, st) : launch_shrink_bf16(g2, st);
+        }
     }
     prof_end(CWL_PROF_SHRINK, st);
     if (s != CWL_OK) return s;
     prof_begin(CWL_PROF_MAIN, st);
-    s = d->dt == CWL_F32 ? launch_gemm_f32(mn, EPI_STORE, st) : launch_main_bf16(mn, st);
+    for (int32_t p = 0; p < n_proj && s == CWL_OK; ++p) {
+        GemmArgs g2 = mn;
+        if (n_proj > 1) {
+            g2.B1 = packed + P.wt + es * (size_t)grp.col0[p] * (size_t)d->d_in;
+            g2.N = grp.cols[p];
+            g2.C = static_cast<char*>(y) + es * (size_t)grp.col0[p];
+            g2.A2 = uhat + es * (size_t)p * (size_t)P.R;
+            g2.B2 = packed + P.bt + es * (size_t)grp.col0[p] * (size_t)P.R;
+        }
+        s = d->dt == CWL_F32 ? launch_gemm_f32(g2, EPI_STORE, st) : launch_main_bf16(g2, st);
+    }
     prof_end(CWL_PROF_MAIN, st);
     return s;
 }
 
-// ws_given: the caller brings the workspace (checked here); else the library's own array is used
 cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* seq_offsets,
                       int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
                       const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap,
@@ -653,8 +738,8 @@ extern "C" cwl_status cwl_chunkwise_lora_linear_packed(
     if (!packed) return CWL_ERR_NULL;
     if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
     if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
-    return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
-                      chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y,
+    return run_packed(d, group_cols(d, nullptr), x, static_cast<const char*>(packed), seq_offsets, n_seqs,
+                      chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y,
                       static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
@@ -674,8 +759,8 @@ extern "C" cwl_status cwl_chunkwise_lora_linear_packed_static(
     char* ws = nullptr;
     s = static_scratch(&ws);
     if (s != CWL_OK) return s;
-    return run_packed(d, x, static_cast<const char*>(packed), seq_offsets, n_seqs, chunk_offsets,
-                      chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y, ws,
+    return run_packed(d, group_cols(d, nullptr), x, static_cast<const char*>(packed), seq_offsets, n_seqs,
+                      chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y, ws,
                       static_cast<hipStream_t>(stream));
 }
 
@@ -703,8 +788,8 @@ extern "C" cwl_status cwl_chunkwise_lora_linear(
     s = d->dt == CWL_F32 ? prepack_typed<float>(d, L, W, A, B, packed, st)
                          : prepack_typed<uint16_t>(d, L, W, A, B, packed, st);
     if (s != CWL_OK) return s;
-    return run_packed(d, x, packed, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len,
-                      rank_idx, chunk_cap, nullptr, y, ws, st);
+    return run_packed(d, group_cols(d, nullptr), x, packed, seq_offsets, n_seqs, chunk_offsets, chunk_start,
+                      chunk_len, rank_idx, chunk_cap, nullptr, y, ws, st);
 }
 
 extern "C" cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x,
@@ -722,8 +807,79 @@ extern "C" cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, con
     if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(gate) % 16)
         return CWL_ERR_INVALID_ARG;
     if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
-    return run_packed(d, x, static_cast<const char*>(packed), nullptr, 0, nullptr, nullptr, nullptr,
-                      nullptr, 0, reinterpret_cast<const TokMeta*>(gate), y,
+    return run_packed(d, group_cols(d, nullptr), x, static_cast<const char*>(packed), nullptr, 0, nullptr,
+                      nullptr, nullptr, nullptr, 0, reinterpret_cast<const TokMeta*>(gate), y,
+                      static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+// ---- projections that share x -----------------------------------------------------------------
+extern "C" size_t cwl_packed_weights_grouped_bytes(const cwl_linear_desc* d, const cwl_group* g) {
+    if (check_desc(d) != CWL_OK || check_group(d, g) != CWL_OK) return 0;
+    return packed_layout(d, g->n_proj).total;
+}
+
+extern "C" size_t cwl_linear_grouped_workspace_bytes(const cwl_linear_desc* d, const cwl_group* g) {
+    if (check_desc(d) != CWL_OK || check_group(d, g) != CWL_OK) return 0;
+    return ws_layout(d, g->n_proj).total;
+}
+
+extern "C" cwl_status cwl_prepack_weights_grouped(const cwl_linear_desc* d, const cwl_group* g, void* packed,
+                                                  size_t packed_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_group(d, g);
+    if (s != CWL_OK) return s;
+    if (!packed) return CWL_ERR_NULL;
+    for (int32_t p = 0; p < g->n_proj; ++p) {
+        if (!g->W[p]) return CWL_ERR_NULL;
+        if (d->r_max > 0 && (!g->A[p] || !g->B[p])) return CWL_ERR_NULL;
+    }
+    if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
+    const PackedLayout L = packed_layout(d, g->n_proj);
+    if (packed_bytes < L.total) return CWL_ERR_CAPACITY;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (d->dt == CWL_F32) return prepack_group_typed<float>(d, g, L, static_cast<char*>(packed), st);
+    return prepack_group_typed<uint16_t>(d, g, L, static_cast<char*>(packed), st);
+}
+
+extern "C" cwl_status cwl_chunkwise_lora_linear_grouped_packed(
+    const cwl_linear_desc* d, const cwl_group* g, const void* x, const void* packed,
+    const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
+    const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap, void* y, void* workspace,
+    size_t workspace_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_group(d, g);
+    if (s != CWL_OK) return s;
+    s = check_call(d, x, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                   chunk_cap, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256) return CWL_ERR_INVALID_ARG;
+    if (workspace_bytes < ws_layout(d, g->n_proj).total) return CWL_ERR_CAPACITY;
+    return run_packed(d, group_cols(d, g), x, static_cast<const char*>(packed), seq_offsets, n_seqs,
+                      chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y,
+                      static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+extern "C" cwl_status cwl_gated_lora_linear_grouped_packed(const cwl_linear_desc* d, const cwl_group* g,
+                                                           const void* x, const void* packed,
+                                                           const cwl_token_gate* gate, void* y, void* workspace,
+                                                           size_t workspace_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    s = check_group(d, g);
+    if (s != CWL_OK) return s;
+    s = check_call(d, x, nullptr, 0, nullptr, nullptr, nullptr, nullptr, 0, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed || !gate) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(gate) % 16)
+        return CWL_ERR_INVALID_ARG;
+    if (workspace_bytes < ws_layout(d, g->n_proj).total) return CWL_ERR_CAPACITY;
+    return run_packed(d, group_cols(d, g), x, static_cast<const char*>(packed), nullptr, 0, nullptr, nullptr,
+                      nullptr, nullptr, 0, reinterpret_cast<const TokMeta*>(gate), y,
                       static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 

@@ -64,6 +64,8 @@ struct GemmArgs {
     int32_t N_tile;         // EPI_PARTIAL: column tile the plan was made for (64 or 128)
     int32_t M_tile;         // EPI_PARTIAL: row tile of the plan (256: tiles of 256 x 128; else by M and N_tile)
     int32_t three_per_cu;   // EPI_PARTIAL, M <= 64: the plan counts on three workgroups per compute unit (shallower ring)
+    int32_t gate_period;    // EPI_GATE: output column n is direction n % gate_period of its adapter (several
+                            // adapters of one padded rank side by side); 0: direction n
 };
 
 // EPI_STORE: C = result in the launch's element type.  EPI_GATE: C[g, n] = result * G[perm[g], n].
@@ -98,12 +100,20 @@ struct SmallPlan {
     int64_t ldp, partial_stride;      // elements
     size_t partial_bytes;
 };
-SmallPlan small_rows_plan(const cwl_linear_desc* d);
-// wt_at: W^T [d_out, d_in] directly followed by A^T [padded rank, d_in]; bt: B^T [d_out, padded rank]
-cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* wt_at, const void* bt,
-                          const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
-                          const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
-                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, const TokMeta* gate,
-                          hipStream_t st);   // gate != NULL: use these entries, leave the chunk table alone
+// Projections that share x, side by side: projection p owns output columns [col0[p], col0[p] + cols[p])
+// of the wide product and directions [p R, (p + 1) R) of the concatenated adapters (R = padded rank).
+constexpr int kMaxGroup = CWL_MAX_GROUP;
+struct GroupCols {
+    int32_t n_proj;
+    int64_t col0[kMaxGroup], cols[kMaxGroup];
+};
+// d->d_out: all output columns; the concatenated adapters have grp.n_proj * padded_rank(d->r_max) directions
+SmallPlan small_rows_plan(const cwl_linear_desc* d, int32_t n_proj);
+// wt_at: W^T [d_out, d_in] directly followed by A^T [n_proj * padded rank, d_in]; bt: B^T [d_out, padded rank]
+cwl_status run_small_rows(const cwl_linear_desc* d, const GroupCols& grp, const void* x, const void* wt_at,
+                          const void* bt, const int32_t* seq_offsets, int32_t n_seqs,
+                          const int32_t* chunk_offsets, const int32_t* chunk_start, const int32_t* chunk_len,
+                          const int32_t* rank_idx, int32_t chunk_cap, void* y, float* partial, TokMeta* meta,
+                          const TokMeta* gate, hipStream_t st);   // gate != NULL: use these entries, leave the chunk table alone
 
 }  // namespace cwl

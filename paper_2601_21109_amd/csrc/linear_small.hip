@@ -35,9 +35,21 @@ constexpr int kMaxRankPadded = (CWL_MAX_RANK + kRankPad - 1) / kRankPad * kRankP
 // first value is needed: with a few hundred bytes per thread it is pure memory latency.
 template <int SP>
 __global__ void __launch_bounds__(256)
-small_fixup_kernel(int64_t n_rows, int64_t d_out, int32_t R, const float* __restrict__ partial,
-                   int32_t splits, int64_t ldp, int64_t pstride, const __bf16* __restrict__ Bt,
-                   const TokMeta* __restrict__ meta, __bf16* __restrict__ y, int64_t ldy) {
+small_fixup_kernel(int64_t n_rows, int64_t d_out_all, GroupCols grp, int32_t R, const float* __restrict__ partial,
+                   int32_t splits, int64_t ldp, int64_t pstride, const __bf16* __restrict__ Bt_all,
+                   const TokMeta* __restrict__ meta, __bf16* __restrict__ y_all, int64_t ldy) {
+    // projection blockIdx.z of the group: its columns of the wide product, its directions of the
+    // concatenated adapters (columns d_out_all + proj R ... of the partial products), its rows of B^T
+    const int proj = blockIdx.z;
+    int64_t pc0 = 0, d_out = 0;
+#pragma unroll
+    for (int q = 0; q < kMaxGroup; ++q)
+        if (q == proj) { pc0 = grp.col0[q]; d_out = grp.cols[q]; }
+    if ((int64_t)blockIdx.x * kFixCols >= d_out) return;
+    const int64_t u_col0 = d_out_all + (int64_t)proj * R;
+    const __bf16* Bt = Bt_all + pc0 * R;
+    __bf16* y = y_all + pc0;
+    const float* part_w = partial + pc0;                            // this projection's columns of x W
     extern __shared__ __attribute__((aligned(16))) char dyn[];      // uhat: kFixRows x (R + kUhPad) bf16
     __bf16* uh = reinterpret_cast<__bf16*>(dyn);
     const int ldu = R + kUhPad;
@@ -62,7 +74,7 @@ small_fixup_kernel(int64_t n_rows, int64_t d_out, int32_t R, const float* __rest
         for (int ij = 0; ij < kMaxRankPadded / 64; ++ij) {
             u_raw[mj][ij] = 0.0f;
             if (ij * 64 < R) {                                      // uniform
-                const float* p = partial + g * ldp + d_out + ij * 64 + lane;
+                const float* p = partial + g * ldp + u_col0 + ij * 64 + lane;
                 float v[SP];
 #pragma unroll
                 for (int s = 0; s < SP; ++s) v[s] = p[soff[s]];
@@ -83,7 +95,7 @@ small_fixup_kernel(int64_t n_rows, int64_t d_out, int32_t R, const float* __rest
         const int64_t cb = col0 + wave * 32 + b * 16;
         int64_t n = cb + g4 * 4;
         if (n > d_out - 4) n = d_out - 4;                        // columns past the end are not stored
-        const float* p = partial + gc * ldp + n;
+        const float* p = part_w + gc * ldp + n;
         f32x4 v[SP];
 #pragma unroll
         for (int s = 0; s < SP; ++s) v[s] = *reinterpret_cast<const f32x4*>(p + soff[s]);
@@ -131,12 +143,15 @@ small_fixup_kernel(int64_t n_rows, int64_t d_out, int32_t R, const float* __rest
 }
 
 template <int SP>
-cwl_status launch_fixup(const cwl_linear_desc* d, int32_t R, const SmallPlan& p, const float* partial,
-                        const void* bt, const TokMeta* meta, void* y, hipStream_t st) {
-    const dim3 grid((unsigned)((d->d_out + kFixCols - 1) / kFixCols), (unsigned)((d->n_rows + kFixRows - 1) / kFixRows));
+cwl_status launch_fixup(const cwl_linear_desc* d, const GroupCols& grp, int32_t R, const SmallPlan& p,
+                        const float* partial, const void* bt, const TokMeta* meta, void* y, hipStream_t st) {
+    int64_t widest = 0;
+    for (int q = 0; q < grp.n_proj; ++q) widest = grp.cols[q] > widest ? grp.cols[q] : widest;
+    const dim3 grid((unsigned)((widest + kFixCols - 1) / kFixCols), (unsigned)((d->n_rows + kFixRows - 1) / kFixRows),
+                    (unsigned)grp.n_proj);
     const size_t lds = sizeof(__bf16) * kFixRows * (size_t)(R + kUhPad);
     small_fixup_kernel<SP><<<grid, dim3(256), lds, st>>>(
-        d->n_rows, d->d_out, R, partial, p.splits, p.ldp, p.partial_stride, static_cast<const __bf16*>(bt),
+        d->n_rows, d->d_out, grp, R, partial, p.splits, p.ldp, p.partial_stride, static_cast<const __bf16*>(bt),
         meta, static_cast<__bf16*>(y), d->ldy);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
@@ -147,9 +162,9 @@ cwl_status launch_fixup(const cwl_linear_desc* d, int32_t R, const SmallPlan& p,
 // How the reduction dimension is cut for n_rows <= kSmallRows.  Enough workgroups to have the
 // weights in flight everywhere (about two per compute unit), at least four stages of 64 each, and
 // partial sums that stay well below the bytes of the weights themselves.
-SmallPlan small_rows_plan(const cwl_linear_desc* d) {
+SmallPlan small_rows_plan(const cwl_linear_desc* d, int32_t n_proj) {
     SmallPlan p = {};
-    const int64_t R = padded_rank(d->r_max);
+    const int64_t R = (int64_t)n_proj * padded_rank(d->r_max);     // directions of all adapters side by side
     const int64_t n_cols = d->d_out + R;
     int64_t bm = d->n_rows <= 64 ? 64 : 128;
     p.n_tile = d->n_rows <= 256 ? 64 : 128;           // from 257 rows the tile count suffices with 128 x 128
@@ -193,20 +208,20 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d) {
     return p;
 }
 
-cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* wt_at, const void* bt,
-                          const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
-                          const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
-                          int32_t chunk_cap, void* y, float* partial, TokMeta* meta, const TokMeta* gate,
-                          hipStream_t st) {
+cwl_status run_small_rows(const cwl_linear_desc* d, const GroupCols& grp, const void* x, const void* wt_at,
+                          const void* bt, const int32_t* seq_offsets, int32_t n_seqs,
+                          const int32_t* chunk_offsets, const int32_t* chunk_start, const int32_t* chunk_len,
+                          const int32_t* rank_idx, int32_t chunk_cap, void* y, float* partial, TokMeta* meta,
+                          const TokMeta* gate, hipStream_t st) {
     if (d->dt != CWL_BF16 || d->n_rows < 1 || d->n_rows > kSmallRows) return CWL_ERR_UNSUPPORTED;
-    const SmallPlan p = small_rows_plan(d);
-    const int32_t R = padded_rank(d->r_max);
+    const SmallPlan p = small_rows_plan(d, grp.n_proj);
+    const int32_t R = padded_rank(d->r_max);                       // of one adapter
 
     GemmArgs pa = {};
     pa.A1 = x;          pa.lda1 = d->ldx;
     pa.B1 = wt_at;      pa.ldb1 = d->d_in;
     pa.K1 = (int32_t)d->d_in;
-    pa.M = d->n_rows;   pa.N = d->d_out + R;
+    pa.M = d->n_rows;   pa.N = d->d_out + (int64_t)grp.n_proj * R;
     pa.N_tile = p.n_tile;
     pa.M_tile = p.m_tile;
     pa.three_per_cu = p.three_per_cu;
@@ -236,14 +251,15 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const void* x, const void* w
     prof_end(CWL_PROF_MAIN, st);
     if (s != CWL_OK) return s;
 
-    if (d->d_out < 8) return CWL_ERR_UNSUPPORTED;
+    for (int q = 0; q < grp.n_proj; ++q)
+        if (grp.cols[q] < 8) return CWL_ERR_UNSUPPORTED;
     prof_begin(CWL_PROF_META, st);
     const TokMeta* mt = gate ? gate : meta;
-    if (p.splits <= 2) s = launch_fixup<2>(d, R, p, partial, bt, mt, y, st);
-    else if (p.splits <= 4) s = launch_fixup<4>(d, R, p, partial, bt, mt, y, st);
-    else if (p.splits <= 8) s = launch_fixup<8>(d, R, p, partial, bt, mt, y, st);
-    else if (p.splits <= 16) s = launch_fixup<16>(d, R, p, partial, bt, mt, y, st);
-    else s = launch_fixup<32>(d, R, p, partial, bt, mt, y, st);
+    if (p.splits <= 2) s = launch_fixup<2>(d, grp, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 4) s = launch_fixup<4>(d, grp, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 8) s = launch_fixup<8>(d, grp, R, p, partial, bt, mt, y, st);
+    else if (p.splits <= 16) s = launch_fixup<16>(d, grp, R, p, partial, bt, mt, y, st);
+    else s = launch_fixup<32>(d, grp, R, p, partial, bt, mt, y, st);
     prof_end(CWL_PROF_META, st);
     if (s != CWL_OK) return s;
     return CWL_OK;

@@ -174,6 +174,48 @@ def test_linear_descriptor_errors(L):
     assert L.cwl_linear_packed_workspace_bytes(d.ref()) < L.cwl_linear_workspace_bytes(d.ref())
 
 
+def test_grouped_calls_argument_errors(L):
+    """Projections that share x: the group must have 1..8 projections whose columns add up to d_out."""
+    def group(d_outs, ptr=0x1000):
+        g = B.Group()
+        g.n_proj = len(d_outs)
+        for p, n in enumerate(d_outs[:B.MAX_GROUP]):
+            g.d_out[p] = n
+            g.W[p] = g.A[p] = g.B[p] = ptr
+        return g
+
+    d = make_desc(d_out=256, ldy=256)
+    ok = group([128, 128])
+    assert L.cwl_packed_weights_grouped_bytes(d.ref(), ctypes.byref(ok)) > L.cwl_packed_weights_bytes(d.ref())
+    assert L.cwl_linear_grouped_workspace_bytes(d.ref(), ctypes.byref(ok)) > L.cwl_linear_packed_workspace_bytes(d.ref())
+
+    def status(dd, g, x=P(0x10000), packed=P(0x20000), y=P(0x30000), ws=P(0x40000), nbytes=1 << 30):
+        return L.cwl_chunkwise_lora_linear_grouped_packed(dd.ref(), ctypes.byref(g) if g is not None else None, x,
+                                                          packed, P(), 1, P(), P(), P(), P(), 8, y, ws, nbytes, None)
+
+    assert status(d, None) == B.ERR_NULL
+    assert status(d, group([128, 64])) == B.ERR_INVALID_ARG           # columns do not add up
+    assert status(d, group([])) == B.ERR_INVALID_ARG
+    g9 = group([32] * 8)
+    g9.n_proj = 9
+    assert status(d, g9) == B.ERR_INVALID_ARG
+    assert status(d, group([256, 0])) == B.ERR_INVALID_ARG
+    assert status(make_desc(d_out=256, ldy=256, group_rows=1), ok) == B.ERR_UNSUPPORTED
+    assert status(make_desc(d_out=256, ldy=256, dt=B.BF16), group([252, 4])) == B.ERR_UNSUPPORTED
+    assert status(d, ok, x=None) == B.ERR_NULL
+    assert status(d, ok, packed=None) == B.ERR_NULL
+    assert status(d, ok, nbytes=64) == B.ERR_CAPACITY
+    assert status(make_desc(d_out=256, ldy=256, n_rows=0), ok) == B.OK
+    assert L.cwl_packed_weights_grouped_bytes(d.ref(), ctypes.byref(group([128, 64]))) == 0
+    # prepack: every projection brings its three pointers
+    bad = group([128, 128])
+    bad.B[1] = None
+    assert L.cwl_prepack_weights_grouped(d.ref(), ctypes.byref(bad), P(0x50000), 1 << 30, None) == B.ERR_NULL
+    assert L.cwl_prepack_weights_grouped(d.ref(), ctypes.byref(ok), P(0x50000), 16, None) == B.ERR_CAPACITY
+    assert L.cwl_gated_lora_linear_grouped_packed(d.ref(), ctypes.byref(ok), P(0x10000), P(0x20000), None, P(0x30000),
+                                                  P(0x40000), 1 << 30, None) == B.ERR_NULL
+
+
 def test_stream_step_and_gated_linear_argument_errors(L):
     f = L.cwl_stream_step
     p = B.ChunkParams(4, 9, 1.0, 1.0)
