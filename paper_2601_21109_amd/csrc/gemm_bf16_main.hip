@@ -224,10 +224,6 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
     // slot's eight loads one per four MFMAs (two reads per MFMA measured 5 % slower: with one wave
     // per SIMD whatever is issued between two MFMAs has to fit into the 16 cycles the first one runs)
     auto order_step = [&]() {
-#ifndef CWL_ORDER
-#define CWL_ORDER 0
-#endif
-#if CWL_ORDER == 0
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -239,38 +235,6 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
-#elif CWL_ORDER == 1      // reads every 4 MFMAs, a load after every second read
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-#elif CWL_ORDER == 2      // reads every 2 MFMAs over the first half, loads every 4 over the second
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-#elif CWL_ORDER == 3      // reads every 3 MFMAs (48), then loads every 2 MFMAs (16)
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-        }
-#endif
         __builtin_amdgcn_sched_barrier(0);
     };
     auto zero_acc = [&]() {
