@@ -23,6 +23,25 @@ def rel_err(y, ref):
     return float(np.max(np.abs(y - ref) / den))
 
 
+def gate_matrix(n_rows, r_max, ranks, scales, blend_w, seq_offsets, chunk_offsets, chunk_start, chunk_len, rank_idx):
+    """The per-token, per-direction weights G[t, i] of the layer (cross-fade included), built directly from the
+    definition: used by the tests only."""
+    G = np.zeros((n_rows, r_max), dtype=np.float64)
+    for b in range(len(seq_offsets) - 1):
+        for c in range(chunk_offsets[b], chunk_offsets[b + 1]):
+            s0, n = int(chunk_start[c]), int(chunk_len[c])
+            r, sc = int(ranks[rank_idx[c]]), float(np.float32(scales[rank_idx[c]]))
+            for j in range(n):
+                if c == chunk_offsets[b] or blend_w == 0 or j >= blend_w:
+                    G[s0 + j, :r] += sc
+                else:
+                    lam = float(np.float32(np.float32(j + 1) / np.float32(blend_w + 1)))
+                    rp, sp = int(ranks[rank_idx[c - 1]]), float(np.float32(scales[rank_idx[c - 1]]))
+                    G[s0 + j, :r] += lam * sc
+                    G[s0 + j, :rp] += (1.0 - lam) * sp
+    return G
+
+
 def entropy_err(h, ref, vocab):
     """|H - ref| / max(ref, 1e-3 ln max(V, 2), 0.05), maximum over rows.  The 0.05-nat floor is what
     fp32 accumulation can resolve: H = ln S - T/S is formed from S = 1 + eps for a peaked row, and
