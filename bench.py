@@ -159,12 +159,59 @@ def other_workload(name, steps, warmup):
             "main_ms": main_ms, "main_frac_of_bf16_peak": fl_main / (main_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         fl_all += fl_call
         ms_all += call_ms
+    # the projections that read the same activations (q/k/v; gate/up) as grouped calls: one gate table and one
+    # shrink pass over x per group, every projection still on its own rungs
+    grouped = None
+    names = [pr[0] for pr in projs]
+    groups = [g for g in (["q_proj", "k_proj", "v_proj"], ["gate_proj", "up_proj"], ["up_proj", "gate_proj"])
+              if all(n in names for n in g)]
+    if groups:
+        groups = groups[:2] if len(groups) > 2 else groups
+        seen, calls_g = set(), []
+        for g in groups:
+            if seen & set(g):
+                continue
+            seen |= set(g)
+            idx = [names.index(n) for n in g]
+            ops = [W.linear_operands(wl, i, dev) for i in idx]
+            pg = B.prepack_weights_grouped([o[1] for o in ops], [o[2] for o in ops], [o[3] for o in ops])
+            del ops
+            xg = projs[idx[0]][3]                  # the group reads the activations of its first projection
+            yg = torch.empty((N, pg.d_out), dtype=wl.dtype, device=dev)
+            wsg = B.grouped_workspace(N, pg, wl.ladder, wl.scales, wl.blend_w, dev)
+            calls_g.append((g, idx, pg, xg, yg, wsg))
+        rest = [pr for i, pr in enumerate(projs) if names[i] not in seen]
+
+        def step_grouped():
+            for t in range(n_tiles):
+                B.score_tokens(logits, out=h_sink if n_tiles > 1 else h)
+            B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), out=table)
+            B.select_ranks(table, wl.taus(), K, out=ri)
+            for _, _, pg, xg, yg, wsg in calls_g:
+                B.chunkwise_lora_linear_grouped(xg, pg, wl.ladder, wl.scales, wl.blend_w, sod, table, ri, out=yg,
+                                                workspace=wsg)
+            for pr in rest:
+                linear(pr)
+
+        step_grouped()
+        torch.cuda.synchronize()
+        ms_g = timed(step_grouped, steps)
+        grouped = {"groups": ["+".join(g) for g, *_ in calls_g], "step_ms": ms_g,
+                   "tokens_per_s": N / (ms_g * 1e-3),
+                   "group_call_ms": {"+".join(g): timed(lambda pg=pg, xg=xg, yg=yg, wsg=wsg: B.chunkwise_lora_linear_grouped(
+                       xg, pg, wl.ladder, wl.scales, wl.blend_w, sod, table, ri, out=yg, workspace=wsg), max(steps // 2, 2))
+                       for g, _, pg, xg, yg, wsg in calls_g},
+                   "separate_calls_ms": {"+".join(g): sum(calls[names[i]]["call_ms"] for i in idx)
+                                         for g, idx, *_ in calls_g}}
+        del calls_g
     out = {"n_rows": N, "vocab": wl.vocab, "ladder": wl.ladder, "chunks": n_chunks, "mean_r_eff": r_sum / N,
            "steps": steps, "step_ms": ms_step, "tokens_per_s": N / (ms_step * 1e-3),
            "score": {"ms_per_launch": score_ms, "launches_per_step": n_tiles, "GBps": score_gbs,
                      "frac_of_hbm_peak": score_gbs / PEAK_HBM_GBS},
            "linear_calls": calls,
            "all_calls_frac_of_bf16_peak": fl_all / (ms_all * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    if grouped:
+        out["with_grouped_calls"] = grouped
     del projs, logits
     torch.cuda.empty_cache()
     return out
