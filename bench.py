@@ -61,6 +61,17 @@ def read_traffic(tag):
     return out
 
 
+def tail_stage_ratio(r_eff, r_max, rows=256, step=64):
+    """Adapter stages the main GEMM's row tiles run (token order), over what they run at fixed r_max."""
+    import numpy as np
+    n = len(r_eff)
+    pad = (-n) % rows
+    r = np.concatenate([r_eff, np.zeros(pad, dtype=r_eff.dtype)]).reshape(-1, rows).max(axis=1)
+    run = np.ceil(r / step).sum()
+    full = np.ceil(r_max / step) * len(r)
+    return float(run / full) if full else 1.0
+
+
 def other_workload(name, steps, warmup):
     """Compact figures of one of the other bf16 workloads: one whole step = score_tokens, partition_chunks,
     select_ranks once and the linear of EVERY projection of the workload on that one chunk table (own x, W, A,
@@ -381,13 +392,15 @@ def main():
     if not args.no_variants:
         zero_idx = torch.zeros(max(n_chunks, 1), dtype=torch.int32, device=dev)
 
-        def make(ranks, scales, rid):
+        def make(ranks, scales, rid, group_rows=args.group_rows):
             return lambda: B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, wl.blend_w, sod,
-                                                   table, rid, out=y, group_rows=args.group_rows,
+                                                   table, rid, out=y, group_rows=group_rows,
                                                    workspace=ws)
         fns = {"chunkwise": make(wl.ladder, wl.scales, ri),
                "fixed_r_max": make([wl.r_max], [wl.alpha / wl.r_max], zero_idx),
-               "rank_0": make([0], [0.0], zero_idx)}
+               "rank_0": make([0], [0.0], zero_idx),
+               # the other setting of group_rows: rows sorted by effective rank before the GEMMs
+               "chunkwise_other_group_rows": make(wl.ladder, wl.scales, ri, 1 - args.group_rows)}
         for fn in fns.values():
             for _ in range(args.warmup):
                 fn()
@@ -410,6 +423,16 @@ def main():
             "fixed_r_max": {"ms": ms_v["fixed_r_max"], "effective_tflops": flops_fixed / ms_v["fixed_r_max"] / 1e9},
             "rank_0": {"ms": ms_v["rank_0"], "effective_tflops": flops_base / ms_v["rank_0"] / 1e9},
             "speedup_vs_fixed_r_max": ms_v["fixed_r_max"] / ms_v["chunkwise"],
+            "group_rows_%d" % (1 - args.group_rows): {"ms": ms_v["chunkwise_other_group_rows"],
+                                                      "effective_tflops": flops_alg / ms_v["chunkwise_other_group_rows"] / 1e9},
+            # what skipping can save at most: the share of the main GEMM's reduction stages that belong
+            # to the adapter part, and the share of those that the tiles' largest ranks leave out
+            "adapter_stage_share_of_main": ((wl.r_max + 63) // 64 * 64) / (d_in + (wl.r_max + 63) // 64 * 64),
+            "adapter_stages_run_over_fixed_r_max": tail_stage_ratio(r_eff, wl.r_max),
+            "note": "the main GEMM walks ceil(r_tile / 64) adapter stages per 256-row tile (r_tile = largest "
+                    "effective rank in the tile) after d_in / 64 base stages, so what rank skipping can save "
+                    "of the main GEMM is adapter_stage_share_of_main x (1 - adapter_stages_run_over_fixed_r_max); "
+                    "with one tile per compute unit (cfg1) the slowest tile sets the kernel time",
             "lora_flop_share_at_r_max": wl.r_max * (d_in + d_out) / (d_in * d_out),
         }
 
