@@ -430,9 +430,9 @@ cwl_status cwl_gated_lora_linear_packed(const cwl_linear_desc* d, const void* x,
  * The grouped calls give exactly the layer of cwl_chunkwise_lora_linear for every projection,
  *      y[:, c_p : c_p + d_out_p] = x W_p + (gated x A_p[:, :r]) B_p[:r, :],    c_p = d_out_0 + .. + d_out_{p-1},
  * every projection on the prefixes of ITS OWN factors, in one wide output y [n_rows, sum d_out_p]:
- * the gate table is made once, one shrink pass over x serves the adapters of all projections (as
- * many as have 256 directions together per pass), and up to 512 rows the weights of all projections
- * are streamed by one launch.  In `d`: d_out = sum of d_out_p, ldw / lda / ldb are not used,
+ * the gate table is made once, one shrink pass over x serves the adapters of all projections (below
+ * 65536 rows as many as have 256 directions together per pass), and up to 512 rows the weights of all
+ * projections are streamed by one launch.  In `d`: d_out = sum of d_out_p, ldw / lda / ldb are not used,
  * group_rows must be 0.  Sums may run in another order than in the single-projection calls.
  *
  *   cwl_group.W / A / B   device pointers, read by cwl_prepack_weights_grouped only

@@ -424,12 +424,12 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
     // to cover the memory latency with bytes in flight.
     // Every workgroup re-reads A^T from L2, as many bytes as it reads of x when the tile is 64 x 64;
     // with enough rows to keep all compute units busy, 256-row tiles quarter that.
-    if (a.M >= 128 * 512) {
-        switch (a.N) {
-            case 64: return launch_cfg<256, 64, 2, 2, 4, EPI_GATE, 64>(a, st);
-            case 128: return launch_cfg<256, 128, 2, 2, 3, EPI_GATE, 64>(a, st);
-            default: break;
-        }
+    // Several adapters side by side (a group of projections) are column tiles of the same launch: the
+    // tile order keeps the column tiles of eight row tiles on one XCD at the same time, so x comes
+    // from HBM once and from that L2 for the other column tiles.
+    if (a.M >= kShrinkTallRows) {
+        if (a.N % 128 == 0) return launch_cfg<256, 128, 2, 2, 3, EPI_GATE, 64>(a, st);
+        if (a.N % 64 == 0) return launch_cfg<256, 64, 2, 2, 4, EPI_GATE, 64>(a, st);
     }
     switch (a.N) {
         case 64: return launch_cfg<64, 64, 2, 2, 6, EPI_GATE, 64>(a, st);

@@ -75,6 +75,10 @@ __device__ __forceinline__ bool tile_of(int32_t v, int32_t n_virtual, int32_t ti
     return true;
 }
 
+// GATE: the shrink of a group of projections on many rows, uhat = (x . [A_1 .. A_P]) (.) G: one
+// reduction part, and the epilogue multiplies every value by its row's gate for its direction
+// (column modulo a.gate_period) before rounding, as the shrink kernels of gemm_bf16.hip do.
+template <bool GATE>
 __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_virtual) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
@@ -325,9 +329,24 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
             asm volatile("" : "+v"(le));
             const int l16e = le & 15, g4e = le >> 4;
             char* stg = smem + pA * SLOT_BYTES + wave * 8192;
+            // GATE: the gate entries of this lane's eight rows (one per block row), and the direction
+            // of the wave's first column (wave-uniform; block nb starts 16 nb further on, modulo the
+            // period, which is a multiple of 64)
+            TokMeta mt[GATE ? MB : 1];
+            int32_t dir0 = 0;
+            if constexpr (GATE) {
+#pragma unroll
+                for (int q = 0; q < MB; ++q) {
+                    int64_t g = m0 + wm * TM + q * 16 + l16e;
+                    if (g > a.M - 1) g = a.M - 1;
+                    mt[q] = a.meta[g];
+                }
+                dir0 = (int32_t)((n0 + wn * TN) % a.gate_period);
+            }
             auto put = [&](auto qc) {
                 constexpr int q = decltype(qc)::value;
                 char* rowp = stg + (q & 1) * 4096 + l16e * 256 + ((g4e & 1) << 3);
+                int32_t dir = dir0;                  // direction of block nb's first column
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
                     float x0, x1, x2, x3;
@@ -336,6 +355,16 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
                                  : "=v"(x0), "=v"(x1), "=v"(x2), "=v"(x3)
                                  : "a"(acc[nb][q][0]), "a"(acc[nb][q][1]), "a"(acc[nb][q][2]), "a"(acc[nb][q][3])
                                  : "memory");
+                    if constexpr (GATE) {
+                        const TokMeta& m = mt[q];
+                        const int32_t i0 = dir + 4 * g4e;
+                        x0 *= (i0 < m.r_prev ? m.g_prev : 0.0f) + (i0 < m.r_cur ? m.g_cur : 0.0f);
+                        x1 *= (i0 + 1 < m.r_prev ? m.g_prev : 0.0f) + (i0 + 1 < m.r_cur ? m.g_cur : 0.0f);
+                        x2 *= (i0 + 2 < m.r_prev ? m.g_prev : 0.0f) + (i0 + 2 < m.r_cur ? m.g_cur : 0.0f);
+                        x3 *= (i0 + 3 < m.r_prev ? m.g_prev : 0.0f) + (i0 + 3 < m.r_cur ? m.g_cur : 0.0f);
+                        dir += 16;
+                        if (dir >= a.gate_period) dir -= a.gate_period;
+                    }
                     bf16x4 o;
                     o[0] = (__bf16)x0; o[1] = (__bf16)x1; o[2] = (__bf16)x2; o[3] = (__bf16)x3;
                     *reinterpret_cast<bf16x4*>(rowp + (((nb * 2 + (g4e >> 1)) ^ l16e) << 4)) = o;
@@ -380,6 +409,46 @@ __global__ void __launch_bounds__(256) main_bf16_kernel(GemmArgs a, int32_t n_vi
 
 }  // namespace
 
+// compute units of the current device, rounded down to a multiple of 8 (0: error)
+static int persistent_grid_limit() {
+    static int n_cu_of[kMaxDevices] = {};
+    const int dev = device_slot();
+    if (dev < 0) return 0;
+    if (n_cu_of[dev] == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
+            return 0;
+        n_cu_of[dev] = v / 8 * 8;
+    }
+    return n_cu_of[dev];
+}
+
+bool shrink_wide_bf16_serves(const GemmArgs& a) {
+    return !a.perm && a.M >= kShrinkTallRows && a.N >= 192 && a.gate_period >= 64 &&
+           a.gate_period % 64 == 0 && a.lda1 <= kMaxLd && a.ldb1 <= kMaxLd && a.K1 >= BK && a.K1 % BK == 0;
+}
+
+cwl_status launch_shrink_wide_bf16(const GemmArgs& a_in, hipStream_t st) {
+    if (!shrink_wide_bf16_serves(a_in) || !a_in.meta) return CWL_ERR_UNSUPPORTED;
+    GemmArgs a = a_in;
+    a.blk_r = nullptr;                                 // one reduction part
+    a.A2 = a.B2 = nullptr;
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(main_bf16_kernel<true>), SMEM_BYTES, lds_set) != CWL_OK)
+        return CWL_ERR_DEVICE;
+    a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
+    a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
+    const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;
+    const int64_t n_virtual = (n_tiles + 7) / 8 * 8;
+    if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
+    const int n_cu = persistent_grid_limit();
+    if (n_cu == 0) return CWL_ERR_DEVICE;
+    const int64_t grid = n_virtual < n_cu ? n_virtual : n_cu;
+    main_bf16_kernel<true><<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a, (int32_t)n_virtual);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}
+
 cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     GemmArgs a = a_in;
     // gathered rows, and leading dimensions whose 256-row offsets do not fit 32 bits, take the
@@ -388,7 +457,7 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
         return launch_main_bf16_general(a_in, st);
     if (a.K1 < BK || a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
     static PerDeviceFlag lds_set;
-    if (ensure_dynamic_lds(reinterpret_cast<const void*>(main_bf16_kernel), SMEM_BYTES, lds_set) != CWL_OK)
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(main_bf16_kernel<false>), SMEM_BYTES, lds_set) != CWL_OK)
         return CWL_ERR_DEVICE;
     a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
     a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
@@ -401,18 +470,10 @@ cwl_status launch_main_bf16(const GemmArgs& a_in, hipStream_t st) {
     const int64_t n_virtual = (n_tiles + 7) / 8 * 8;       // workgroup slots, 8 XCDs round-robin
     if (n_virtual >= (int64_t)1 << 30) return CWL_ERR_UNSUPPORTED;
     // persistent: one workgroup per compute unit (160 KiB of LDS each), a multiple of 8 of them
-    static int n_cu_of[kMaxDevices] = {};
-    const int dev = device_slot();
-    if (dev < 0) return CWL_ERR_DEVICE;
-    if (n_cu_of[dev] == 0) {
-        int v = 0;
-        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8)
-            return CWL_ERR_DEVICE;
-        n_cu_of[dev] = v / 8 * 8;
-    }
-    const int n_cu = n_cu_of[dev];
+    const int n_cu = persistent_grid_limit();
+    if (n_cu == 0) return CWL_ERR_DEVICE;
     const int64_t grid = n_virtual < n_cu ? n_virtual : n_cu;
-    main_bf16_kernel<<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a, (int32_t)n_virtual);
+    main_bf16_kernel<false><<<dim3((unsigned)grid), dim3(256), SMEM_BYTES, st>>>(a, (int32_t)n_virtual);
     CWL_RETURN_IF_LAUNCH_FAILED();
     return CWL_OK;
 }

@@ -619,11 +619,17 @@ cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void
             else s = launch_shrink_fixup<32>(d->n_rows, P.R, partial, split.splits, split.partial_stride, meta, pa.perm, uhat, st);
         }
     } else if (n_proj == 1) {
-        s = d->dt == CWL_F32 ? launch_gemm_f32(sh, EPI_GATE, st) : launch_shrink_bf16(sh, st);
+        GemmArgs g1 = sh;
+        g1.gate_period = P.R;                          // one adapter: the direction is the column
+        if (d->dt == CWL_F32) s = launch_gemm_f32(sh, EPI_GATE, st);
+        else if (shrink_wide_bf16_serves(g1)) s = launch_shrink_wide_bf16(g1, st);
+        else s = launch_shrink_bf16(sh, st);
     } else {
         // one shrink over the concatenated adapters: x is read once for as many adapters as fit the
         // widest shrink tile (256 directions), their directions side by side in uhat
-        const int32_t per_launch = d->dt == CWL_F32 ? n_proj : (256 / P.R > 0 ? 256 / P.R : 1);
+        // (from kShrinkTallRows rows up the bf16 shrink takes any number of 64-direction column tiles)
+        const int32_t per_launch = (d->dt == CWL_F32 || d->n_rows >= kShrinkTallRows) ? n_proj
+                                   : (256 / P.R > 0 ? 256 / P.R : 1);
         for (int32_t p0 = 0; p0 < n_proj && s == CWL_OK; p0 += per_launch) {
             const int32_t np = n_proj - p0 < per_launch ? n_proj - p0 : per_launch;
             GemmArgs g2 = sh;
@@ -631,7 +637,9 @@ cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void
             g2.N = (int64_t)np * P.R;
             g2.C = uhat + es * (size_t)p0 * (size_t)P.R;
             g2.gate_period = P.R;
-            s = d->dt == CWL_F32 ? launch_gemm_f32(g2, EPI_GATE, st) : launch_shrink_bf16(g2, st);
+            if (d->dt == CWL_F32) s = launch_gemm_f32(g2, EPI_GATE, st);
+            else if (shrink_wide_bf16_serves(g2)) s = launch_shrink_wide_bf16(g2, st);
+            else s = launch_shrink_bf16(g2, st);
         }
     }
     prof_end(CWL_PROF_SHRINK, st);

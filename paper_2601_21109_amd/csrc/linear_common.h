@@ -26,6 +26,7 @@ struct Ladder {
 };
 
 constexpr int kRankBlock = 64;    // rows per entry of the block-rank table
+constexpr int64_t kShrinkTallRows = 65536;   // from this many rows up the bf16 shrink uses 256-row tiles
 constexpr int kRankPad = 64;      // the stored rank dimension is padded to a multiple of this
 
 inline int32_t padded_rank(int32_t r_max) {
@@ -75,6 +76,10 @@ enum { EPI_STORE = 0, EPI_GATE = 1, EPI_PARTIAL = 2 };
 cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
+// shrink of several adapters side by side (a.N >= 192 directions, gate period a.gate_period) on
+// kShrinkTallRows rows or more, token order: the persistent 256 x 256 kernel with a gated epilogue
+bool shrink_wide_bf16_serves(const GemmArgs& a);
+cwl_status launch_shrink_wide_bf16(const GemmArgs& a, hipStream_t st);
 cwl_status launch_main_bf16_general(const GemmArgs& a, hipStream_t st);   // any a.perm
 cwl_status launch_main_bf16_tile128(const GemmArgs& a, hipStream_t st);   // 128 x 128 tiles
 cwl_status launch_main_bf16_tile256x128(const GemmArgs& a, hipStream_t st);

@@ -43,6 +43,8 @@ def check_against_oracle(y, pg, x, Ws, As, Bs, ranks, scales, blend_w, table, ro
     ([700, 500], 256, [520, 264], [0, 24, 100], 3, torch.bfloat16, TOL_BF16),              # mid-size tiles, padded rank 128
     ([2100, 900], 192, [1032, 512, 2056], [8, 16, 32, 64], 4, torch.bfloat16, TOL_BF16),   # persistent kernel per projection
     ([900, 400], 128, [256, 264, 8, 64, 72], [200], 2, torch.bfloat16, TOL_BF16),          # five adapters of 256 padded directions: five shrink passes
+    ([40000, 25637], 128, [72, 8, 136], [8, 16, 32, 64], 3, torch.bfloat16, TOL_BF16),     # tall: one shrink of 192 directions on the persistent kernel (ragged rows and columns)
+    ([65536], 192, [264, 64, 40], [0, 24, 100], 4, torch.bfloat16, TOL_BF16),              # tall: 384 directions, two column tiles, period 128
     ([77, 50], 100, [72, 33, 5], [3, 12], 2, torch.float32, TOL_F32),                      # fp32
     ([600], 64, [130, 70], [0, 4, 8, 16], 3, torch.float32, TOL_F32),
 ])
@@ -57,10 +59,13 @@ def test_grouped_projections_match_the_oracle_per_projection(seq_lens, d_in, d_o
     torch.cuda.synchronize()
     rows = None if n * d_in * sum(d_outs) <= 2e8 else np.unique(np.concatenate([np.arange(0, n, 31), [n - 1]]))
     check_against_oracle(y, pg, x, Ws, As, Bs, ranks, scales, w, table, rows, tol)
-    # every projection also agrees with its own single-projection call (sums may run in another order)
+    # every projection also agrees with its own single-projection call; the sums may run in another
+    # order (on tall inputs the grouped shrink is another kernel), so in bf16 an entry of the shrink
+    # output and then the output element itself can each land on the neighbouring value: two units
+    # of 2^-8 .. 2^-7 relative
     for yp, Wp, Ap, Bp in zip(pg.split(y), Ws, As, Bs):
         y1 = B.chunkwise_lora_linear(x, B.prepack_weights(Wp, Ap, Bp), None, None, ranks, scales, w, sod, tab, rid)
-        assert rel_err(host(yp), host(y1)) <= (2.0 ** -7 if dtype == torch.bfloat16 else 1e-5)
+        assert rel_err(host(yp), host(y1)) <= (2.0 ** -6 if dtype == torch.bfloat16 else 1e-5)
     y2 = B.chunkwise_lora_linear_grouped(x, pg, ranks, scales, w, sod, tab, rid)
     assert torch.equal(y, y2)
 

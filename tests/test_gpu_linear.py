@@ -94,6 +94,20 @@ def test_bf16_more_tiles_than_compute_units(d_in, ranks):
     assert rel_err(yh, ref) <= TOL_BF16
 
 
+@pytest.mark.parametrize("d_in,ranks,group_rows", [(128, [8, 16, 32, 64], 0), (192, [0, 24, 100], 0),
+                                                   (128, [40, 200], 0), (64, [8, 250], 0), (128, [40, 200], 1)])
+def test_bf16_tall_inputs(d_in, ranks, group_rows):
+    """65536 rows and more (ragged): the shrink runs on 256-row tiles with a rotated walk over the reduction
+    dimension, from 192 padded directions up on the persistent kernel with the gate in its epilogue; row
+    sample against the oracle."""
+    seq_lens = [30000, 35000, 700]
+    n = sum(seq_lens)
+    rows = np.unique(np.concatenate([np.arange(0, n, 97), np.arange(65530, 65545), np.arange(n - 40, n)]))
+    yh, ref, _ = run_case(3, seq_lens, d_in, 264, ranks, 3, torch.bfloat16, 23, l_min=8, l_max=90,
+                          packed=True, rows=rows, group_rows=group_rows)
+    assert rel_err(yh, ref) <= TOL_BF16
+
+
 @pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
     (1, [1], 64, 8, [16], 0),                         # one token, one slice
     (1, [1], 4096, 4096, [8, 16, 32, 64], 4),         # one decode row at the 7B shape
