@@ -432,7 +432,7 @@ def main():
             "note": "the main GEMM walks ceil(r_tile / 64) adapter stages per 256-row tile (r_tile = largest "
                     "effective rank in the tile) after d_in / 64 base stages, so what rank skipping can save "
                     "of the main GEMM is adapter_stage_share_of_main x (1 - adapter_stages_run_over_fixed_r_max); "
-                    "with one tile per compute unit (cfg1) the slowest tile sets the kernel time",
+                    "tiles are assigned to compute units statically, so the unit whose tiles skip least sets the kernel time",
             "lora_flop_share_at_r_max": wl.r_max * (d_in + d_out) / (d_in * d_out),
         }
 
