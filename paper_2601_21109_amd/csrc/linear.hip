@@ -217,6 +217,112 @@ group_rows_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff /* rank | bu
     }
 }
 
+// The same sort spread over the chip, for up to kParSortBlocks * kParSortRows rows: workgroup g owns
+// rows [2048 g, 2048 g + 2048), thread i of it eight consecutive rows.  First launch: bucket counts
+// per workgroup.  Second launch: every workgroup adds up, from all the counts, where its rows of
+// every bucket begin (buckets before it in all workgroups, its own bucket in the workgroups before
+// it), ranks its own rows by an exclusive scan over its threads, bucket by bucket, and writes them.
+// Order inside a bucket is row order, as in the one-workgroup kernel.
+constexpr int kParSortRows = 2048;
+constexpr int kParSortBlocks = 1024;
+
+__global__ void __launch_bounds__(256)
+sort_count_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, int32_t* __restrict__ counts /* [blocks][kBuckets] */) {
+    __shared__ int32_t wave_tot[kBuckets][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t i0 = (int64_t)blockIdx.x * kParSortRows + tid * 8;
+    int32_t cnt[kBuckets];
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) cnt[b] = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int32_t bkt = (i0 + u < n_rows) ? (r_eff[i0 + u] >> 16) : -1;
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) cnt[b] += (b == bkt) ? 1 : 0;
+    }
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) {
+        int32_t v = cnt[b];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+        if (lane == 0) wave_tot[b][wave] = v;
+    }
+    __syncthreads();
+    if (tid < kBuckets)
+        counts[(int64_t)blockIdx.x * kBuckets + tid] = wave_tot[tid][0] + wave_tot[tid][1] + wave_tot[tid][2] + wave_tot[tid][3];
+}
+
+__global__ void __launch_bounds__(256)
+sort_scatter_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32_t* __restrict__ counts,
+                    int32_t n_blocks, int32_t* __restrict__ perm) {
+    __shared__ int32_t wave_tot[kBuckets][4];
+    __shared__ int32_t base_sh[kBuckets];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int32_t me = (int32_t)blockIdx.x;
+    // first slot of every bucket's rows of this workgroup
+    int32_t before[kBuckets];
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) before[b] = 0;
+    const int32_t n_entries = n_blocks * kBuckets;
+    for (int32_t e = tid; e < n_entries; e += 256) {
+        const int32_t blk = e / kBuckets, bb = e - blk * kBuckets;
+        const int32_t c = counts[e];
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) before[b] += (bb < b || (bb == b && blk < me)) ? c : 0;
+    }
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) {
+        int32_t v = before[b];
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+        if (lane == 0) wave_tot[b][wave] = v;
+    }
+    __syncthreads();
+    if (tid < kBuckets) base_sh[tid] = wave_tot[tid][0] + wave_tot[tid][1] + wave_tot[tid][2] + wave_tot[tid][3];
+    __syncthreads();
+    // this thread's rows, their buckets, and its counts
+    const int64_t i0 = (int64_t)me * kParSortRows + tid * 8;
+    int32_t bkt[8];
+    int32_t cnt[kBuckets];
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) cnt[b] = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        bkt[u] = (i0 + u < n_rows) ? (r_eff[i0 + u] >> 16) : -1;
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b) cnt[b] += (b == bkt[u]) ? 1 : 0;
+    }
+    // exclusive scan over the threads, bucket by bucket
+    int32_t pos[kBuckets];
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) {
+        int32_t v = cnt[b];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int32_t o = __shfl_up(v, off);
+            if (lane >= off) v += o;
+        }
+        pos[b] = v - cnt[b];
+        if (lane == 63) wave_tot[b][wave] = v;     // (read above before the last barrier)
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < kBuckets; ++b) {
+        int32_t run = base_sh[b];
+        for (int w = 0; w < wave; ++w) run += wave_tot[b][w];
+        pos[b] += run;
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        if (bkt[u] < 0) continue;
+        int32_t p = 0;
+#pragma unroll
+        for (int b = 0; b < kBuckets; ++b)
+            if (b == bkt[u]) { p = pos[b]; pos[b] = p + 1; }
+        perm[p] = (int32_t)(i0 + u);
+    }
+}
+
 __global__ void __launch_bounds__(256)
 block_rank_kernel(int64_t n_rows, const int32_t* __restrict__ r_eff, const int32_t* __restrict__ perm,
                   int32_t* __restrict__ blk_r) {
@@ -555,7 +661,17 @@ cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void
             grouped ? r_eff : nullptr);
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (grouped) {
-        group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, perm);
+        const int64_t sort_blocks = (d->n_rows + kParSortRows - 1) / kParSortRows;
+        if (sort_blocks > 1 && sort_blocks <= kParSortBlocks) {
+            // (the counts live in uhat, which the shrink only writes later: 68 bytes per 2048 rows)
+            int32_t* counts = reinterpret_cast<int32_t*>(uhat);
+            sort_count_kernel<<<dim3((unsigned)sort_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, counts);
+            CWL_RETURN_IF_LAUNCH_FAILED();
+            sort_scatter_kernel<<<dim3((unsigned)sort_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, counts,
+                                                                                  (int32_t)sort_blocks, perm);
+        } else {
+            group_rows_kernel<<<dim3(1), dim3(kSortThreads), 0, st>>>(d->n_rows, r_eff, perm);
+        }
         CWL_RETURN_IF_LAUNCH_FAILED();
         block_rank_kernel<<<dim3(meta_blocks), dim3(256), 0, st>>>(d->n_rows, r_eff, perm, blk_r);
         CWL_RETURN_IF_LAUNCH_FAILED();
