@@ -297,6 +297,42 @@ cwl_status cwl_chunkwise_lora_linear_packed(const cwl_linear_desc* d, const void
                                             void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The layer in two phases (Sec. III-C: the rank slice is an index operation over the stored
+ * factors, so the product with all stored directions does not depend on the scheduler's decisions).
+ *
+ *   cwl_lora_shrink_packed                    u = x A, every stored direction, fp32, no gate.  It
+ *                                             reads x and the packed adapter only, NOT the chunk
+ *                                             table: it may be enqueued before the scores exist, or
+ *                                             on a second stream beside cwl_partition_chunks and
+ *                                             cwl_select_ranks, which occupy a few compute units.
+ *   cwl_chunkwise_lora_linear_packed_shrunk   the rest of cwl_chunkwise_lora_linear_packed: the
+ *                                             gate of the chunk table applied to u (rounded to the
+ *                                             element type once, as the one-call form rounds it),
+ *                                             then y = x W + uhat B.
+ *
+ * Together they compute what cwl_chunkwise_lora_linear_packed computes, with the same kernels in the
+ * same order of summation (bit for bit the same y; a direction that the one-call form skips because
+ * no row of its block uses it is computed here and multiplied by a zero gate).  `u` is an opaque
+ * device buffer of cwl_lora_shrink_bytes(d) bytes, 256-byte aligned, written by the first call and
+ * read by the second; the caller orders the two (same stream, or an event) and must not change x in
+ * between.  Both calls take the same descriptor.  group_rows must be 0 (CWL_ERR_UNSUPPORTED).
+ * Up to 512 rows the whole layer is one product, the first call enqueues nothing and the second is
+ * the one-call form.
+ * ------------------------------------------------------------------------------------------- */
+size_t cwl_lora_shrink_bytes(const cwl_linear_desc* d);      /* 0: descriptor rejected */
+
+cwl_status cwl_lora_shrink_packed(const cwl_linear_desc* d, const void* x, const void* packed,
+                                  void* u, size_t u_bytes, void* stream);
+
+cwl_status cwl_chunkwise_lora_linear_packed_shrunk(const cwl_linear_desc* d, const void* x,
+                                                   const void* packed, const void* u, size_t u_bytes,
+                                                   const int32_t* seq_offsets, int32_t n_seqs,
+                                                   const int32_t* chunk_offsets, const int32_t* chunk_start,
+                                                   const int32_t* chunk_len, const int32_t* rank_idx,
+                                                   int32_t chunk_cap, void* y, void* workspace,
+                                                   size_t workspace_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * cwl_chunkwise_lora_linear_packed_static -- cwl_chunkwise_lora_linear_packed for callers that
  * cannot allocate device memory and have no workspace to hand over: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same

@@ -27,6 +27,7 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_packed_weights_bytes", "cwl_prepack_weights", "cwl_linear_workspace_bytes",
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_chunkwise_lora_linear_packed_static",
+           "cwl_lora_shrink_bytes", "cwl_lora_shrink_packed", "cwl_chunkwise_lora_linear_packed_shrunk",
            "cwl_stream_step", "cwl_stream_step_aligned",
            "cwl_gated_lora_linear_packed", "cwl_packed_weights_grouped_bytes",
            "cwl_linear_grouped_workspace_bytes", "cwl_prepack_weights_grouped",
@@ -100,7 +101,7 @@ def lib():
                                                i32, P, P, sz, P]
     dp = ctypes.POINTER(LinearDesc)
     for name in ("cwl_packed_weights_bytes", "cwl_linear_workspace_bytes",
-                 "cwl_linear_packed_workspace_bytes"):
+                 "cwl_linear_packed_workspace_bytes", "cwl_lora_shrink_bytes"):
         getattr(L, name).argtypes = [dp]
         getattr(L, name).restype = sz
     L.cwl_prepack_weights.argtypes = [dp, P, P, P, P, sz, P]
@@ -125,6 +126,8 @@ def lib():
     L.cwl_chunkwise_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, i32, P, P, P, P, i32, P, P, sz, P]
     L.cwl_gated_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_static.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P]
+    L.cwl_lora_shrink_packed.argtypes = [dp, P, P, P, sz, P]
+    L.cwl_chunkwise_lora_linear_packed_shrunk.argtypes = [dp, P, P, P, sz, P, i32, P, P, P, P, i32, P, P, sz, P]
     # return types: byte counts are size_t, everything else but the two informational calls a status
     for name in EXPORTS:
         if name.endswith("_bytes"):
@@ -413,6 +416,39 @@ def chunkwise_lora_linear_static(x, packed, ranks, scales, blend_w, seq_offsets,
         d.ref(), _ptr(x), _ptr(packed.blob), _ptr(seq_offsets), seq_offsets.numel() - 1,
         _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
         table["cap"], _ptr(out), _stream()), "cwl_chunkwise_lora_linear_packed_static")
+    return out
+
+
+def lora_shrink(x, packed, ranks, scales, blend_w, out=None):
+    """First phase of the two-phase layer: u = x A (every stored direction, fp32, no gate) into an opaque
+    uint8 buffer, which chunkwise_lora_linear_shrunk takes.  Needs no chunk table."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(packed, PackedWeights)
+    assert packed.dtype == x.dtype and packed.d_in == x.shape[1]
+    dummy_y = torch.empty((0, packed.d_out), dtype=x.dtype, device=x.device)
+    d = _desc_for(x, packed.d_out, packed.r_max, ranks, scales, blend_w, dummy_y)
+    d.c.ldy = packed.d_out
+    need = lib().cwl_lora_shrink_bytes(d.ref())
+    if out is None:
+        out = _ws(need, x.device)
+    _check(lib().cwl_lora_shrink_packed(d.ref(), _ptr(x), _ptr(packed.blob), _ptr(out), out.numel(), _stream()),
+           "cwl_lora_shrink_packed")
+    return out
+
+
+def chunkwise_lora_linear_shrunk(x, packed, u, ranks, scales, blend_w, seq_offsets, table, rank_idx, out=None,
+                                 workspace=None):
+    """Second phase: the chunk table's gate on `u` (from lora_shrink on the same x), then y = x W + uhat B."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(packed, PackedWeights)
+    assert packed.dtype == x.dtype and packed.d_in == x.shape[1]
+    if out is None:
+        out = torch.empty((x.shape[0], packed.d_out), dtype=x.dtype, device=x.device)
+    d = _desc_for(x, packed.d_out, packed.r_max, ranks, scales, blend_w, out)
+    need = lib().cwl_linear_packed_workspace_bytes(d.ref())
+    ws = workspace if workspace is not None else _ws(max(need, 256), x.device)
+    _check(lib().cwl_chunkwise_lora_linear_packed_shrunk(
+        d.ref(), _ptr(x), _ptr(packed.blob), _ptr(u), u.numel(), _ptr(seq_offsets), seq_offsets.numel() - 1,
+        _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
+        table["cap"], _ptr(out), _ptr(ws), ws.numel(), _stream()), "cwl_chunkwise_lora_linear_packed_shrunk")
     return out
 
 

@@ -116,7 +116,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
     // same columns of x at the same time, rows one leading dimension apart, which a few memory
     // channels then serve (3.8 TB/s); tile bm starts its walk at stage bm % KS and wraps around
     // instead (4.5 TB/s).  The fp32 sums of a row then run in a rotated order.
-    if (EPI == EPI_GATE && BM == 256 && !a.perm && KS > 1) {
+    if ((EPI == EPI_GATE || EPI == EPI_RAW) && BM == 256 && !a.perm && KS > 1) {
         k_first = bm % KS;
         k_wrap = KS - k_first;
     }
@@ -174,7 +174,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
             gp[i] += BK;
         }
         ++issued;
-        if (EPI == EPI_GATE && issued == k_wrap) {
+        if ((EPI == EPI_GATE || EPI == EPI_RAW) && issued == k_wrap) {
 #pragma unroll
             for (int i = 0; i < LOADS; ++i) gp[i] -= a.K1;
         }
@@ -295,7 +295,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
     for (int mi = 0; mi < MI; ++mi) {
         const int64_t g = m0 + wm * TM + mi * 32 + l32;
         if (g >= a.M) continue;
-        if (EPI == EPI_PARTIAL) {
+        if (EPI == EPI_PARTIAL || EPI == EPI_RAW) {
             float* prow = a.partial + split * a.partial_stride + g * a.ldp;
 #pragma unroll
             for (int ni = 0; ni < NI; ++ni)
@@ -436,6 +436,23 @@ cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st) {
         case 128: return launch_cfg<64, 128, 2, 2, 4, EPI_GATE, 64>(a, st);
         case 192: return launch_cfg<64, 192, 2, 2, 4, EPI_GATE, 64>(a, st);
         case 256: return launch_cfg<64, 256, 2, 2, 3, EPI_GATE, 64>(a, st);
+        default: return CWL_ERR_UNSUPPORTED;
+    }
+}
+
+// The shrink without its gate: x A in fp32, every direction, the same tiles, rings and order of
+// summation as launch_shrink_bf16 (a.partial [M, a.ldp] receives it; token order only).
+cwl_status launch_shrink_raw_bf16(const GemmArgs& a, hipStream_t st) {
+    if (a.perm || !a.partial) return CWL_ERR_INVALID_ARG;
+    if (a.M >= kShrinkTallRows) {
+        if (a.N % 128 == 0) return launch_cfg<256, 128, 2, 2, 3, EPI_RAW, 64>(a, st);
+        if (a.N % 64 == 0) return launch_cfg<256, 64, 2, 2, 4, EPI_RAW, 64>(a, st);
+    }
+    switch (a.N) {
+        case 64: return launch_cfg<64, 64, 2, 2, 6, EPI_RAW, 64>(a, st);
+        case 128: return launch_cfg<64, 128, 2, 2, 4, EPI_RAW, 64>(a, st);
+        case 192: return launch_cfg<64, 192, 2, 2, 4, EPI_RAW, 64>(a, st);
+        case 256: return launch_cfg<64, 256, 2, 2, 3, EPI_RAW, 64>(a, st);
         default: return CWL_ERR_UNSUPPORTED;
     }
 }

@@ -412,6 +412,109 @@ cwl_status launch_shrink_fixup(int64_t n_rows, int32_t R, const float* partial, 
     return CWL_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// Second phase of the two-phase call: the gate of Sec. III-C / III-D applied to a product x A that
+// an earlier launch left in fp32 (one slice, or the slices of a split reduction, added here in slice
+// order).  A workgroup owns one rank block of 64 rows: wavefront 0 looks up the rows' gate entries
+// (one row per lane, a chain of dependent loads) and their largest effective rank, meanwhile all
+// four wavefronts have their first 64 directions of the product in flight; then every thread gates
+// four consecutive directions of a row at a time and writes uhat in the layer's element type, rounded
+// once as the one-pass shrink rounds it.  The grid covers whole groups of 256 rows, so blk_r gets its
+// four entries per started group (0 past the last row).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ void store_gated4(__bf16* dst, const f32x4_t& v) {
+    bf16x4_t o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (__bf16)v[e];
+    *reinterpret_cast<bf16x4_t*>(dst) = o;
+}
+__device__ __forceinline__ void store_gated4(float* dst, const f32x4_t& v) { *reinterpret_cast<f32x4_t*>(dst) = v; }
+
+template <int SP, typename OutT>
+__global__ void __launch_bounds__(256)
+gate_product_kernel(int64_t n_rows, int32_t R, const float* __restrict__ u, int32_t splits, int64_t pstride,
+                    const int32_t* __restrict__ seq_offsets, int32_t n_seqs,
+                    const int32_t* __restrict__ chunk_offsets, const int32_t* __restrict__ chunk_start,
+                    const int32_t* __restrict__ chunk_len, const int32_t* __restrict__ rank_idx,
+                    int32_t chunk_cap, Ladder lad, int32_t blend_w, OutT* __restrict__ uhat,
+                    int32_t* __restrict__ blk_r) {
+    __shared__ int32_t lad_ranks[CWL_MAX_LADDER];
+    __shared__ float lad_scales[CWL_MAX_LADDER];
+    __shared__ TokMeta sm[kRankBlock];
+    const int tid = threadIdx.x;
+    const int64_t row0 = (int64_t)blockIdx.x * kRankBlock;
+    // pass p covers directions [64 p, 64 p + 64) of the 64 rows: 1024 groups of four, four per thread
+    auto load_pass = [&](int pass, f32x4_t (&v)[4][SP]) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int f = j * 256 + tid;
+            int64_t g = row0 + f / 16;
+            if (g > n_rows - 1) g = n_rows - 1;
+            const float* p = u + g * R + pass * 64 + (f % 16) * 4;
+#pragma unroll
+            for (int sl = 0; sl < SP; ++sl)
+                v[j][sl] = *reinterpret_cast<const f32x4_t*>(p + (sl < splits ? sl : 0) * pstride);
+        }
+    };
+    f32x4_t v[4][SP];
+    if (row0 < n_rows) load_pass(0, v);
+    ladder_to_lds(lad, lad_ranks, lad_scales);
+    __syncthreads();
+    if (tid < kRankBlock) {
+        const int64_t t = row0 + tid;
+        TokMeta m = {0, 0, 0.0f, 0.0f};
+        if (t < n_rows)
+            m = token_meta_of(t, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap,
+                              lad.K, lad_ranks, lad_scales, blend_w);
+        sm[tid] = m;
+        int32_t r_eff = m.r_cur > m.r_prev ? m.r_cur : m.r_prev;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int32_t o = __shfl_xor(r_eff, off);
+            r_eff = o > r_eff ? o : r_eff;
+        }
+        if (tid == 0) blk_r[blockIdx.x] = r_eff;
+    }
+    __syncthreads();
+    if (row0 >= n_rows) return;
+    const int passes = R / 64;
+    for (int pass = 0; pass < passes; ++pass) {
+        if (pass > 0) load_pass(pass, v);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int f = j * 256 + tid;
+            const int64_t g = row0 + f / 16;
+            const int i0 = pass * 64 + (f % 16) * 4;
+            const TokMeta mt = sm[f / 16];
+            f32x4_t acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int sl = 0; sl < SP; ++sl)
+                if (sl < splits) acc += v[j][sl];
+            f32x4_t o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = i0 + e;
+                const float gate = (i < mt.r_prev ? mt.g_prev : 0.0f) + (i < mt.r_cur ? mt.g_cur : 0.0f);
+                o[e] = acc[e] * gate;
+            }
+            if (g < n_rows) store_gated4(uhat + g * R + i0, o);
+        }
+    }
+}
+
+template <int SP, typename OutT>
+cwl_status launch_gate_product(const cwl_linear_desc* d, int32_t R, const float* u, int32_t splits, int64_t pstride,
+                               const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
+                               const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+                               int32_t chunk_cap, const Ladder& lad, void* uhat, int32_t* blk_r, hipStream_t st) {
+    const unsigned blocks = (unsigned)((d->n_rows + 255) / 256 * 4);
+    gate_product_kernel<SP, OutT><<<dim3(blocks), dim3(256), 0, st>>>(
+        d->n_rows, R, u, splits, pstride, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+        chunk_cap, lad, d->blend_w, static_cast<OutT*>(uhat), blk_r);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}
+
 // slices of the reduction dimension for the split shrink; splits < 2: keep the one-pass shrink
 // (rows gathered through a permutation are read through it; the gate table is then made first)
 SmallPlan shrink_split_plan(const cwl_linear_desc* d) {
@@ -794,6 +897,95 @@ cwl_status check_call(const cwl_linear_desc* d, const void* x, const int32_t* se
     return CWL_OK;
 }
 
+// ---- the two-phase call: x A first (no chunk table needed), gate + main GEMM later -----------------
+// What the first phase leaves for the second: nothing up to kSmallRows rows (there the whole layer is
+// one product and the second phase is the ordinary call), the fp32 slices of the split shrink below
+// 16384 rows, else x A [n_rows, padded rank] in fp32.
+size_t shrunk_bytes(const cwl_linear_desc* d) {
+    if (small_rows_path(d, packed_layout(d))) return 256;
+    const SmallPlan split = shrink_split_plan(d);
+    if (split.splits >= 2) return align_up(split.partial_bytes, 256);
+    return align_up(sizeof(float) * (size_t)d->n_rows * (size_t)padded_rank(d->r_max), 256);
+}
+
+cwl_status run_shrink_phase(const cwl_linear_desc* d, const void* x, const char* packed, float* u, hipStream_t st) {
+    const PackedLayout P = packed_layout(d);
+    if (small_rows_path(d, P)) return CWL_OK;
+    GemmArgs sh = {};
+    sh.A1 = x;             sh.lda1 = d->ldx;
+    sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
+    sh.K1 = (int32_t)d->d_in;
+    sh.M = d->n_rows;      sh.N = P.R;
+    cwl_status s = CWL_OK;
+    prof_begin(CWL_PROF_SHRINK, st);
+    const SmallPlan split = shrink_split_plan(d);
+    if (d->dt == CWL_F32) {
+        sh.C = u;          sh.ldc = P.R;
+        s = launch_gemm_f32(sh, EPI_STORE, st);
+    } else if (split.splits >= 2) {
+        sh.N_tile = split.n_tile;
+        sh.splits = split.splits;
+        sh.ks_per_split = split.ks_per_split;
+        sh.partial = u;
+        sh.ldp = split.ldp;
+        sh.partial_stride = split.partial_stride;
+        MetaJob job = {};
+        s = launch_partial_bf16(sh, job, st);
+    } else {
+        sh.partial = u;    sh.ldp = P.R;
+        s = launch_shrink_raw_bf16(sh, st);
+    }
+    prof_end(CWL_PROF_SHRINK, st);
+    return s;
+}
+
+cwl_status run_shrunk(const cwl_linear_desc* d, const void* x, const char* packed, const float* u,
+                      const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
+                      const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+                      int32_t chunk_cap, void* y, char* ws, hipStream_t st) {
+    const PackedLayout P = packed_layout(d);
+    if (small_rows_path(d, P))
+        return run_packed(d, group_cols(d, nullptr), x, packed, seq_offsets, n_seqs, chunk_offsets, chunk_start,
+                          chunk_len, rank_idx, chunk_cap, nullptr, y, ws, st);
+    const WsLayout L = ws_layout(d);
+    int32_t* blk_r = reinterpret_cast<int32_t*>(ws + L.blk_r);
+    char* uhat = ws + L.uhat;
+    Ladder lad = {};
+    lad.K = d->K;
+    for (int32_t k = 0; k < d->K; ++k) {
+        lad.ranks[k] = d->ranks[k];
+        lad.scales[k] = d->scales[k];
+    }
+    SmallPlan split = shrink_split_plan(d);
+    int32_t splits = split.splits >= 2 ? split.splits : 1;
+    const int64_t pstride = split.splits >= 2 ? split.partial_stride : 0;
+#define CWL_GATE_ARGS d, P.R, u, splits, pstride, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, lad, uhat, blk_r, st
+    cwl_status s;
+    prof_begin(CWL_PROF_META, st);
+    if (d->dt == CWL_F32) s = launch_gate_product<1, float>(CWL_GATE_ARGS);
+    else if (splits <= 1) s = launch_gate_product<1, __bf16>(CWL_GATE_ARGS);
+    else if (splits <= 4) s = launch_gate_product<4, __bf16>(CWL_GATE_ARGS);
+    else if (splits <= 8) s = launch_gate_product<8, __bf16>(CWL_GATE_ARGS);
+    else if (splits <= 16) s = launch_gate_product<16, __bf16>(CWL_GATE_ARGS);
+    else s = launch_gate_product<32, __bf16>(CWL_GATE_ARGS);
+#undef CWL_GATE_ARGS
+    prof_end(CWL_PROF_META, st);
+    if (s != CWL_OK) return s;
+    GemmArgs mn = {};
+    mn.A1 = x;             mn.lda1 = d->ldx;
+    mn.B1 = packed + P.wt; mn.ldb1 = d->d_in;
+    mn.K1 = (int32_t)d->d_in;
+    mn.A2 = uhat;          mn.lda2 = P.R;
+    mn.B2 = packed + P.bt; mn.ldb2 = P.R;
+    mn.blk_r = blk_r;
+    mn.M = d->n_rows;      mn.N = d->d_out;
+    mn.C = y;              mn.ldc = d->ldy;
+    prof_begin(CWL_PROF_MAIN, st);
+    s = d->dt == CWL_F32 ? launch_gemm_f32(mn, EPI_STORE, st) : launch_main_bf16(mn, st);
+    prof_end(CWL_PROF_MAIN, st);
+    return s;
+}
+
 // Address of the static scratch array on the current device, looked up once per device (each GPU
 // holds its own copy of the array at its own address).
 void* g_scratch_ptr[kMaxDevices] = {};
@@ -886,6 +1078,47 @@ extern "C" cwl_status cwl_chunkwise_lora_linear_packed_static(
     return run_packed(d, group_cols(d, nullptr), x, static_cast<const char*>(packed), seq_offsets, n_seqs,
                       chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, nullptr, y, ws,
                       static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t cwl_lora_shrink_bytes(const cwl_linear_desc* d) {
+    if (check_desc(d) != CWL_OK || d->group_rows != 0) return 0;
+    return shrunk_bytes(d);
+}
+
+extern "C" cwl_status cwl_lora_shrink_packed(const cwl_linear_desc* d, const void* x, const void* packed,
+                                             void* u, size_t u_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!x || !packed || !u) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(u) % 256) return CWL_ERR_INVALID_ARG;
+    if (d->dt == CWL_BF16 && reinterpret_cast<uintptr_t>(x) % 16) return CWL_ERR_UNSUPPORTED;
+    if (d->dt == CWL_F32 && reinterpret_cast<uintptr_t>(x) % 4) return CWL_ERR_INVALID_ARG;
+    if (u_bytes < shrunk_bytes(d)) return CWL_ERR_CAPACITY;
+    return run_shrink_phase(d, x, static_cast<const char*>(packed), static_cast<float*>(u),
+                            static_cast<hipStream_t>(stream));
+}
+
+extern "C" cwl_status cwl_chunkwise_lora_linear_packed_shrunk(
+    const cwl_linear_desc* d, const void* x, const void* packed, const void* u, size_t u_bytes,
+    const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets, const int32_t* chunk_start,
+    const int32_t* chunk_len, const int32_t* rank_idx, int32_t chunk_cap, void* y, void* workspace,
+    size_t workspace_bytes, void* stream) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
+    s = check_call(d, x, seq_offsets, n_seqs, chunk_offsets, chunk_start, chunk_len, rank_idx,
+                   chunk_cap, y, workspace);
+    if (s != CWL_OK) return s;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!packed || !u) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(u) % 256) return CWL_ERR_INVALID_ARG;
+    if (u_bytes < shrunk_bytes(d)) return CWL_ERR_CAPACITY;
+    if (workspace_bytes < ws_layout(d).total) return CWL_ERR_CAPACITY;
+    return run_shrunk(d, x, static_cast<const char*>(packed), static_cast<const float*>(u), seq_offsets, n_seqs,
+                      chunk_offsets, chunk_start, chunk_len, rank_idx, chunk_cap, y,
+                      static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
 }
 
 extern "C" cwl_status cwl_chunkwise_lora_linear(

@@ -71,10 +71,12 @@ struct GemmArgs {
 
 // EPI_STORE: C = result in the launch's element type.  EPI_GATE: C[g, n] = result * G[perm[g], n].
 // EPI_PARTIAL: fp32 partial sums of a slice of the reduction dimension (see GemmArgs).
-enum { EPI_STORE = 0, EPI_GATE = 1, EPI_PARTIAL = 2 };
+// EPI_RAW: the product in fp32 at partial[m * ldp + n], no gate (the first phase of the two-phase call).
+enum { EPI_STORE = 0, EPI_GATE = 1, EPI_PARTIAL = 2, EPI_RAW = 3 };
 
 cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
+cwl_status launch_shrink_raw_bf16(const GemmArgs& a, hipStream_t st);   // x A in fp32, ungated (EPI_RAW)
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
 // shrink of several adapters side by side (a.N >= 192 directions, gate period a.gate_period) on
 // kShrinkTallRows rows or more, token order: the persistent 256 x 256 kernel with a gated epilogue

@@ -1,0 +1,139 @@
+"""GPU parity of the layer in two phases (cwl_lora_shrink_packed, then
+cwl_chunkwise_lora_linear_packed_shrunk) against the CPU oracle and, bit for bit, against the
+one-call form (Sec. III-C / III-D)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from helpers import TOL_BF16, TOL_F32, host, rel_err
+from paper_2601_21109_amd import binding as B
+from paper_2601_21109_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def operands(n, d_in, d_out, r_max, dtype, seed):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    x = torch.randn((n, d_in), generator=g, device=DEV).to(dtype)
+    Wm = (torch.randn((d_in, d_out), generator=g, device=DEV) / math.sqrt(d_in)).to(dtype)
+    A = (torch.randn((d_in, r_max), generator=g, device=DEV) / math.sqrt(d_in)).to(dtype)
+    Bm = (torch.randn((r_max, d_out), generator=g, device=DEV) / math.sqrt(max(r_max, 1))).to(dtype)
+    return x, Wm, A, Bm
+
+
+def both_forms(n_seqs, seq_lens, d_in, d_out, ranks, blend_w, dtype, seed, l_min=8, l_max=90, rows=None,
+               side_stream=False):
+    r_max = max(max(ranks), 1)
+    scales = [16.0 / r if r > 0 else 0.0 for r in ranks]
+    n = int(np.sum(seq_lens))
+    x, Wm, A, Bm = operands(n, d_in, d_out, r_max, dtype, seed)
+    so, co, cs, cl, ri = W.random_chunk_table(n_seqs, seq_lens, l_min, l_max, len(ranks), seed + 1)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    pw = B.prepack_weights(Wm, A, Bm)
+    y1 = B.chunkwise_lora_linear(x, pw, None, None, ranks, scales, blend_w, sod, tab, rid)
+    torch.cuda.synchronize()
+    if side_stream:
+        # the first phase on a second stream, ordered against the second phase by an event
+        side = torch.cuda.Stream()
+        done = torch.cuda.Event()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            u = B.lora_shrink(x, pw, ranks, scales, blend_w)
+            done.record(side)
+        torch.cuda.current_stream().wait_event(done)
+    else:
+        u = B.lora_shrink(x, pw, ranks, scales, blend_w)
+    y2 = B.chunkwise_lora_linear_shrunk(x, pw, u, ranks, scales, blend_w, sod, tab, rid)
+    torch.cuda.synchronize()
+    ref = O.linear(host(x), host(Wm), host(A), host(Bm), ranks, scales, blend_w, so, co, cs, cl, ri, rows=rows)
+    y1h, y2h = host(y1), host(y2)
+    return y1h, y2h, (y2h if rows is None else y2h[rows]), ref
+
+
+def same_bits(a, b):
+    # equal as numbers (a zero may carry either sign: a skipped direction against one times a zero gate)
+    return bool(np.array_equal(a, b))
+
+
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [128], 256, 256, [4, 8, 16], 2),
+    (3, [50, 1, 200], 64, 130, [0, 4, 8, 16], 3),
+    (4, [9, 9, 9, 300], 48, 200, [1, 2, 70], 4),
+])
+def test_fp32(n_seqs, seq_lens, d_in, d_out, ranks, w):
+    y1, y2, y2s, ref = both_forms(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.float32, 5, l_min=4, l_max=40)
+    assert rel_err(y2s, ref) <= TOL_F32
+    assert same_bits(y1, y2)
+
+
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [5], 64, 8, [16], 0),                                  # few rows: the first phase is empty
+    (2, [256, 256], 1024, 256, [4, 8, 16, 32, 64, 128], 4),    # 512 rows: still the few-row path
+    (1, [600], 256, 512, [8, 16, 32, 64], 4),                  # split shrink, ragged row tile
+    (3, [300, 41, 700], 512, 520, [8, 16, 32, 64], 4),         # split shrink, several sequences
+    (1, [1000], 128, 264, [0, 8, 24, 40], 2),                  # two stages only: no split
+    (1, [3000], 4096, 264, [200], 3),                          # padded rank 256, many slices
+    (2, [1300, 800], 320, 8200, [8, 16, 32, 64], 3),           # persistent main kernel, short reduction
+])
+def test_bf16_shapes(n_seqs, seq_lens, d_in, d_out, ranks, w):
+    y1, y2, y2s, ref = both_forms(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 11)
+    assert rel_err(y2s, ref) <= TOL_BF16
+    assert same_bits(y1, y2)
+
+
+@pytest.mark.parametrize("d_in,ranks,side", [(512, [8, 16, 32, 64], False), (256, [0, 24, 100], True),
+                                              (128, [40, 200], False)])
+def test_bf16_one_pass_shrink(d_in, ranks, side):
+    """16384 rows and more: the first phase is the one-pass shrink kernel without its gate (64-row tiles,
+    every padded direction); ragged last tile; row sample against the oracle."""
+    seq_lens = [9000, 7000, 1111]
+    n = sum(seq_lens)
+    rows = np.unique(np.concatenate([np.arange(0, n, 61), np.arange(16380, 16390), np.arange(n - 70, n)]))
+    y1, y2, y2s, ref = both_forms(3, seq_lens, d_in, 264, ranks, 3, torch.bfloat16, 23, rows=rows, side_stream=side)
+    assert rel_err(y2s, ref) <= TOL_BF16
+    assert same_bits(y1, y2)
+
+
+def test_bf16_tall_input():
+    """65536 rows and more: 256-row shrink tiles with the rotated walk, in both forms alike."""
+    seq_lens = [30000, 35000, 700]
+    n = sum(seq_lens)
+    rows = np.unique(np.concatenate([np.arange(0, n, 97), np.arange(65530, 65545), np.arange(n - 40, n)]))
+    y1, y2, y2s, ref = both_forms(3, seq_lens, 128, 264, [8, 16, 32, 64], 3, torch.bfloat16, 29, rows=rows)
+    assert rel_err(y2s, ref) <= TOL_BF16
+    assert same_bits(y1, y2)
+
+
+def test_second_phase_repeats_on_a_new_table():
+    """One first phase serves any number of second phases: the product does not depend on the chunk table."""
+    ranks, scales = [8, 16, 32, 64], [2.0, 1.0, 0.5, 0.25]
+    n, d_in, d_out = 20000, 256, 264
+    x, Wm, A, Bm = operands(n, d_in, d_out, 64, torch.bfloat16, 31)
+    pw = B.prepack_weights(Wm, A, Bm)
+    u = B.lora_shrink(x, pw, ranks, scales, 4)
+    for seed in (1, 2):
+        so, co, cs, cl, ri = W.random_chunk_table(2, [12000, 8000], 8, 90, 4, seed)
+        sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+        y1 = B.chunkwise_lora_linear(x, pw, None, None, ranks, scales, 4, sod, tab, rid)
+        y2 = B.chunkwise_lora_linear_shrunk(x, pw, u, ranks, scales, 4, sod, tab, rid)
+        torch.cuda.synchronize()
+        assert same_bits(host(y1), host(y2))
+
+
+def test_argument_errors():
+    ranks, scales = [8, 64], [2.0, 0.25]
+    x, Wm, A, Bm = operands(700, 128, 64, 64, torch.bfloat16, 3)
+    pw = B.prepack_weights(Wm, A, Bm)
+    so, co, cs, cl, ri = W.random_chunk_table(1, [700], 8, 90, 2, 1)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.CwlError) as e:
+        B.lora_shrink(x, pw, ranks, scales, 2, out=small)
+    assert e.value.status == B.ERR_CAPACITY
+    with pytest.raises(B.CwlError) as e:
+        B.chunkwise_lora_linear_shrunk(x, pw, small, ranks, scales, 2, sod, tab, rid)
+    assert e.value.status == B.ERR_CAPACITY
