@@ -333,6 +333,29 @@ cwl_status cwl_chunkwise_lora_linear_packed_shrunk(const cwl_linear_desc* d, con
                                                    size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_schedule_chunks -- the scheduler as one call: cwl_partition_chunks (Sec. III-B, IV-B) and
+ * cwl_select_ranks (Sec. III-C, IV-C) with the same arguments and the same table and rungs, bit for
+ * bit; a chunk's rung is decided by the kernel that writes its record.  When `shrink` is not NULL
+ * the call also does what cwl_lora_shrink_packed(shrink, x, packed, u, u_bytes) does, and where the
+ * shapes allow it (sequences of 4096 tokens or fewer on average, bf16, 16384 .. 65535 rows, r_max
+ * <= 128) the product's workgroups ride in the chunker's launch: the chunk walk is a chain of
+ * dependent look-ups that keeps one wavefront per sequence busy, the product streams x from HBM and
+ * needs nothing the chunker writes, so the two cost little more than the longer of them.  Elsewhere
+ * the product is launched behind the chunker; the results are the same either way.
+ *
+ *   the chunker's and the selector's arguments as in cwl_partition_chunks / cwl_select_ranks
+ *   (rank_idx [cap] written);  shrink, x, packed, u, u_bytes as in cwl_lora_shrink_packed, or
+ *   shrink == NULL: the scheduler alone.
+ * ------------------------------------------------------------------------------------------- */
+cwl_status cwl_schedule_chunks(const float* entropy, int64_t n_rows, const int32_t* seq_offsets,
+                               int32_t n_seqs, const cwl_chunk_params* p /*host*/,
+                               const float* thresholds /*host*/, int32_t K, int32_t* chunk_offsets,
+                               int32_t* chunk_start, int32_t* chunk_len, int64_t* chunk_sum,
+                               int32_t* rank_idx, int32_t cap, int32_t* status_word, void* workspace,
+                               size_t workspace_bytes, const cwl_linear_desc* shrink /*host, may be NULL*/,
+                               const void* x, const void* packed, void* u, size_t u_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * cwl_chunkwise_lora_linear_packed_static -- cwl_chunkwise_lora_linear_packed for callers that
  * cannot allocate device memory and have no workspace to hand over: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and the same

@@ -28,6 +28,7 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_chunkwise_lora_linear_packed_static",
            "cwl_lora_shrink_bytes", "cwl_lora_shrink_packed", "cwl_chunkwise_lora_linear_packed_shrunk",
+           "cwl_schedule_chunks",
            "cwl_stream_step", "cwl_stream_step_aligned",
            "cwl_gated_lora_linear_packed", "cwl_packed_weights_grouped_bytes",
            "cwl_linear_grouped_workspace_bytes", "cwl_prepack_weights_grouped",
@@ -127,6 +128,8 @@ def lib():
     L.cwl_gated_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_static.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P]
     L.cwl_lora_shrink_packed.argtypes = [dp, P, P, P, sz, P]
+    L.cwl_schedule_chunks.argtypes = [P, i64, P, i32, ctypes.POINTER(ChunkParams), ctypes.POINTER(ctypes.c_float), i32,
+                                      P, P, P, P, P, i32, P, P, sz, dp, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_shrunk.argtypes = [dp, P, P, P, sz, P, i32, P, P, P, P, i32, P, P, sz, P]
     # return types: byte counts are size_t, everything else but the two informational calls a status
     for name in EXPORTS:
@@ -417,6 +420,51 @@ def chunkwise_lora_linear_static(x, packed, ranks, scales, blend_w, seq_offsets,
         _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
         table["cap"], _ptr(out), _stream()), "cwl_chunkwise_lora_linear_packed_static")
     return out
+
+
+def schedule_chunks(entropy, seq_offsets, l_min, l_max, theta_hard, delta_dev, thresholds, K, cap=None, out=None,
+                    rank_idx=None, shrink=None):
+    """partition_chunks and select_ranks as one call; returns (table, rank_idx).  `shrink`, when given, is
+    (x, packed, ranks, scales, blend_w, u): the call then also does lora_shrink(x, packed, ..., out=u), in the
+    chunker's own launch where the shapes allow it (u from an earlier lora_shrink of the same shapes, or a uint8
+    tensor of cwl_lora_shrink_bytes bytes)."""
+    assert entropy.is_cuda and entropy.dtype == torch.float32 and entropy.is_contiguous()
+    assert seq_offsets.is_cuda and seq_offsets.dtype == torch.int32
+    dev = entropy.device
+    n_rows, n_seqs = entropy.numel(), seq_offsets.numel() - 1
+    p = ChunkParams(int(l_min), int(l_max), float(theta_hard), float(delta_dev))
+    if out is not None:
+        cap = out["cap"]
+    elif cap is None:
+        cap = n_rows // max(int(l_min), 1) + n_seqs + 1
+    nbytes = lib().cwl_partition_workspace_bytes(n_rows, n_seqs, ctypes.byref(p))
+    out = out if out is not None else {
+        "chunk_offsets": torch.empty(n_seqs + 1, dtype=torch.int32, device=dev),
+        "chunk_start": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_len": torch.empty(max(cap, 1), dtype=torch.int32, device=dev),
+        "chunk_sum": torch.empty(max(cap, 1), dtype=torch.int64, device=dev),
+        "status_word": torch.empty(1, dtype=torch.int32, device=dev),
+        "cap": int(cap),
+        "_workspace": _ws(nbytes, dev),
+    }
+    if rank_idx is None:
+        rank_idx = torch.zeros(max(cap, 1), dtype=torch.int32, device=dev)
+    th = (ctypes.c_float * max(K - 1, 1))(*[float(t) for t in thresholds])
+    ws = out["_workspace"]
+    if shrink is not None:
+        x, packed, ranks, scales, blend_w, u = shrink
+        assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and isinstance(packed, PackedWeights)
+        dummy_y = torch.empty((0, packed.d_out), dtype=x.dtype, device=dev)
+        d = _desc_for(x, packed.d_out, packed.r_max, ranks, scales, blend_w, dummy_y)
+        d.c.ldy = packed.d_out
+        tail = (d.ref(), _ptr(x), _ptr(packed.blob), _ptr(u), u.numel())
+    else:
+        tail = (None, None, None, None, 0)
+    _check(lib().cwl_schedule_chunks(_ptr(entropy), n_rows, _ptr(seq_offsets), n_seqs, ctypes.byref(p), th, int(K),
+                                     _ptr(out["chunk_offsets"]), _ptr(out["chunk_start"]), _ptr(out["chunk_len"]),
+                                     _ptr(out["chunk_sum"]), _ptr(rank_idx), int(cap), _ptr(out["status_word"]),
+                                     _ptr(ws), ws.numel(), *tail, _stream()), "cwl_schedule_chunks")
+    return out, rank_idx
 
 
 def lora_shrink(x, packed, ranks, scales, blend_w, out=None):

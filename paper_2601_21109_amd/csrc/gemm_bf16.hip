@@ -21,6 +21,7 @@
 //     fragment reads of the stage are in registers and its loads of the next stage have landed.
 #include "mfma_util.h"
 #include "token_meta.h"
+#include "partition_seq.h"
 
 namespace cwl {
 namespace {
@@ -65,7 +66,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
         if (tile >= a.tiles_m * a.tiles_n) return;
         bm = tile % a.tiles_m;
         bn = tile / a.tiles_m;
-    } else if (!tile_coords(a.tiles_m, a.tiles_n, &bm, &bn)) {
+    } else if (!tile_coords(vid, a.tiles_m, a.tiles_n, &bm, &bn)) {
         return;
     }
     const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
@@ -397,6 +398,41 @@ cwl_status launch_partial_cfg(GemmArgs a, const MetaJob& job, hipStream_t st) {
     return CWL_OK;
 }
 
+// The short-sequence chunker and the ungated shrink in one launch: workgroups 0 .. n_seqs - 1 chunk
+// one sequence each (a chain of dependent look-ups on one wavefront: 20-odd microseconds during which
+// the chip would otherwise idle), the workgroups behind them compute x A, which needs the memory
+// bandwidth and nothing the chunker produces.  Both parts use the launch's dynamic LDS from its start.
+template <int BM, int BN, int WM, int WN, int NST>
+__global__ void __launch_bounds__(WM * WN * 64) seq_shrink_raw_kernel(GemmArgs a, part::SeqJob job) {
+    static_assert(WM * WN * 64 == part::kThreads, "the chunker's workgroup");
+    if ((int)blockIdx.x < job.n_seqs) {
+        extern __shared__ __attribute__((aligned(1024))) char smem[];
+        part::partition_seq_body(job, (int32_t)blockIdx.x, smem);
+        return;
+    }
+    gemm_bf16_tn_body<BM, BN, WM, WN, NST, EPI_RAW, 64>(a, (int)blockIdx.x - job.n_seqs);
+}
+
+template <int BM, int BN, int WM, int WN, int NST>
+cwl_status launch_seq_shrink_cfg(part::SeqJob job, GemmArgs a, hipStream_t st) {
+    constexpr int BK = 64;
+    constexpr int smem_bytes = NST * (BM + BN) * BK * 2;
+    static_assert(2 * smem_bytes <= 160 * 1024, "two workgroups per compute unit, so that the chunker's fit beside the product's");
+    if (a.K1 % BK != 0) return CWL_ERR_UNSUPPORTED;
+    auto kern = seq_shrink_raw_kernel<BM, BN, WM, WN, NST>;
+    static PerDeviceFlag lds_set;
+    if (ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem_bytes, lds_set) != CWL_OK) return CWL_ERR_DEVICE;
+    job.lds_tokens = (int32_t)(smem_bytes / part::kSeqLdsPerToken);
+    a.tiles_m = (int32_t)((a.M + BM - 1) / BM);
+    a.tiles_n = (int32_t)((a.N + BN - 1) / BN);
+    const int64_t n_tiles = (int64_t)a.tiles_m * a.tiles_n;
+    const int64_t grid = (n_tiles + 7) / 8 * 8 + job.n_seqs;
+    if (grid >= (int64_t)1 << 31) return CWL_ERR_UNSUPPORTED;
+    kern<<<dim3((unsigned)grid), dim3(WM * WN * 64), smem_bytes, st>>>(a, job);
+    CWL_RETURN_IF_LAUNCH_FAILED();
+    return CWL_OK;
+}
+
 template <int BM, int BN, int WM, int WN, int NST, int EPI, int BK = 32>
 cwl_status launch_cfg(GemmArgs a, hipStream_t st) {
     constexpr int smem_bytes = NST * (BM + BN) * BK * 2;
@@ -455,6 +491,14 @@ cwl_status launch_shrink_raw_bf16(const GemmArgs& a, hipStream_t st) {
         case 256: return launch_cfg<64, 256, 2, 2, 3, EPI_RAW, 64>(a, st);
         default: return CWL_ERR_UNSUPPORTED;
     }
+}
+
+cwl_status launch_seq_shrink_raw_bf16(const part::SeqJob& job, const GemmArgs& a, hipStream_t st) {
+    if (a.perm || !a.partial || a.M >= kShrinkTallRows || job.n_seqs < 1) return CWL_ERR_UNSUPPORTED;
+    // rings of 64 and 72 KiB (the one-pass shrink's own are deeper; its stream runs as fast on these)
+    if (a.N == 64) return launch_seq_shrink_cfg<64, 64, 2, 2, 4>(job, a, st);
+    if (a.N == 128) return launch_seq_shrink_cfg<64, 128, 2, 2, 3>(job, a, st);
+    return CWL_ERR_UNSUPPORTED;
 }
 
 // fp32 partial products over slices of the reduction dimension, for a few hundred rows: tiles of 64

@@ -3,6 +3,7 @@
 // formulation is described in linear_common.h.  (Sec. III-C / III-D of arxiv 2601.21109.)
 #include "linear_common.h"
 #include "token_meta.h"
+#include "partition_seq.h"
 
 // Scratch memory of cwl_chunkwise_lora_linear_packed_static: held in every GPU's memory from the
 // moment the library is loaded there.  In host code this name is only a handle for
@@ -908,37 +909,6 @@ size_t shrunk_bytes(const cwl_linear_desc* d) {
     return align_up(sizeof(float) * (size_t)d->n_rows * (size_t)padded_rank(d->r_max), 256);
 }
 
-cwl_status run_shrink_phase(const cwl_linear_desc* d, const void* x, const char* packed, float* u, hipStream_t st) {
-    const PackedLayout P = packed_layout(d);
-    if (small_rows_path(d, P)) return CWL_OK;
-    GemmArgs sh = {};
-    sh.A1 = x;             sh.lda1 = d->ldx;
-    sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
-    sh.K1 = (int32_t)d->d_in;
-    sh.M = d->n_rows;      sh.N = P.R;
-    cwl_status s = CWL_OK;
-    prof_begin(CWL_PROF_SHRINK, st);
-    const SmallPlan split = shrink_split_plan(d);
-    if (d->dt == CWL_F32) {
-        sh.C = u;          sh.ldc = P.R;
-        s = launch_gemm_f32(sh, EPI_STORE, st);
-    } else if (split.splits >= 2) {
-        sh.N_tile = split.n_tile;
-        sh.splits = split.splits;
-        sh.ks_per_split = split.ks_per_split;
-        sh.partial = u;
-        sh.ldp = split.ldp;
-        sh.partial_stride = split.partial_stride;
-        MetaJob job = {};
-        s = launch_partial_bf16(sh, job, st);
-    } else {
-        sh.partial = u;    sh.ldp = P.R;
-        s = launch_shrink_raw_bf16(sh, st);
-    }
-    prof_end(CWL_PROF_SHRINK, st);
-    return s;
-}
-
 cwl_status run_shrunk(const cwl_linear_desc* d, const void* x, const char* packed, const float* u,
                       const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                       const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
@@ -1004,6 +974,70 @@ cwl_status static_scratch(char** out) {
 }
 
 }  // namespace
+
+// ---- the first phase as the chunker's call sees it (declared in partition_seq.h) ----
+cwl_status check_shrink_phase(const cwl_linear_desc* d, const void* x, const void* packed, const void* u,
+                              size_t u_bytes) {
+    cwl_status s = check_desc(d);
+    if (s != CWL_OK) return s;
+    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
+    if (d->n_rows == 0) return CWL_OK;
+    if (!x || !packed || !u) return CWL_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(u) % 256) return CWL_ERR_INVALID_ARG;
+    if (d->dt == CWL_BF16 && reinterpret_cast<uintptr_t>(x) % 16) return CWL_ERR_UNSUPPORTED;
+    if (d->dt == CWL_F32 && reinterpret_cast<uintptr_t>(x) % 4) return CWL_ERR_INVALID_ARG;
+    if (u_bytes < shrunk_bytes(d)) return CWL_ERR_CAPACITY;
+    return CWL_OK;
+}
+
+cwl_status run_shrink_phase(const cwl_linear_desc* d, const void* x, const char* packed, float* u, hipStream_t st) {
+    const PackedLayout P = packed_layout(d);
+    if (small_rows_path(d, P)) return CWL_OK;
+    GemmArgs sh = {};
+    sh.A1 = x;             sh.lda1 = d->ldx;
+    sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
+    sh.K1 = (int32_t)d->d_in;
+    sh.M = d->n_rows;      sh.N = P.R;
+    cwl_status s = CWL_OK;
+    prof_begin(CWL_PROF_SHRINK, st);
+    const SmallPlan split = shrink_split_plan(d);
+    if (d->dt == CWL_F32) {
+        sh.C = u;          sh.ldc = P.R;
+        s = launch_gemm_f32(sh, EPI_STORE, st);
+    } else if (split.splits >= 2) {
+        sh.N_tile = split.n_tile;
+        sh.splits = split.splits;
+        sh.ks_per_split = split.ks_per_split;
+        sh.partial = u;
+        sh.ldp = split.ldp;
+        sh.partial_stride = split.partial_stride;
+        MetaJob job = {};
+        s = launch_partial_bf16(sh, job, st);
+    } else {
+        sh.partial = u;    sh.ldp = P.R;
+        s = launch_shrink_raw_bf16(sh, st);
+    }
+    prof_end(CWL_PROF_SHRINK, st);
+    return s;
+}
+
+// One launch for the short-sequence chunker and the product: only where the product is the one-pass
+// kernel on 64-row tiles with a ring small enough for two workgroups per compute unit.
+cwl_status launch_seq_with_shrink(const part::SeqJob& job, const cwl_linear_desc* d, const void* x,
+                                  const char* packed, float* u, hipStream_t st) {
+    const PackedLayout P = packed_layout(d);
+    if (d->dt != CWL_BF16 || small_rows_path(d, P) || shrink_split_plan(d).splits >= 2 ||
+        d->n_rows >= kShrinkTallRows || (P.R != 64 && P.R != 128))
+        return CWL_ERR_UNSUPPORTED;
+    GemmArgs sh = {};
+    sh.A1 = x;             sh.lda1 = d->ldx;
+    sh.B1 = packed + P.at; sh.ldb1 = d->d_in;
+    sh.K1 = (int32_t)d->d_in;
+    sh.M = d->n_rows;      sh.N = P.R;
+    sh.partial = u;        sh.ldp = P.R;
+    return launch_seq_shrink_raw_bf16(job, sh, st);
+}
+
 }  // namespace cwl
 
 using namespace cwl;
@@ -1087,15 +1121,9 @@ extern "C" size_t cwl_lora_shrink_bytes(const cwl_linear_desc* d) {
 
 extern "C" cwl_status cwl_lora_shrink_packed(const cwl_linear_desc* d, const void* x, const void* packed,
                                              void* u, size_t u_bytes, void* stream) {
-    cwl_status s = check_desc(d);
+    const cwl_status s = check_shrink_phase(d, x, packed, u, u_bytes);
     if (s != CWL_OK) return s;
-    if (d->group_rows != 0) return CWL_ERR_UNSUPPORTED;
     if (d->n_rows == 0) return CWL_OK;
-    if (!x || !packed || !u) return CWL_ERR_NULL;
-    if (reinterpret_cast<uintptr_t>(packed) % 256 || reinterpret_cast<uintptr_t>(u) % 256) return CWL_ERR_INVALID_ARG;
-    if (d->dt == CWL_BF16 && reinterpret_cast<uintptr_t>(x) % 16) return CWL_ERR_UNSUPPORTED;
-    if (d->dt == CWL_F32 && reinterpret_cast<uintptr_t>(x) % 4) return CWL_ERR_INVALID_ARG;
-    if (u_bytes < shrunk_bytes(d)) return CWL_ERR_CAPACITY;
     return run_shrink_phase(d, x, static_cast<const char*>(packed), static_cast<float*>(u),
                             static_cast<hipStream_t>(stream));
 }

@@ -77,6 +77,10 @@ enum { EPI_STORE = 0, EPI_GATE = 1, EPI_PARTIAL = 2, EPI_RAW = 3 };
 cwl_status launch_gemm_f32(const GemmArgs& a, int epi, hipStream_t st);
 cwl_status launch_shrink_bf16(const GemmArgs& a, hipStream_t st);   // a.N = padded rank
 cwl_status launch_shrink_raw_bf16(const GemmArgs& a, hipStream_t st);   // x A in fp32, ungated (EPI_RAW)
+// the same product (64-row tiles, a.N = 64 or 128) behind the job.n_seqs workgroups of the short-sequence
+// chunker in one launch; CWL_ERR_UNSUPPORTED for other shapes
+namespace part { struct SeqJob; }
+cwl_status launch_seq_shrink_raw_bf16(const part::SeqJob& job, const GemmArgs& a, hipStream_t st);
 cwl_status launch_main_bf16(const GemmArgs& a, hipStream_t st);
 // shrink of several adapters side by side (a.N >= 192 directions, gate period a.gate_period) on
 // kShrinkTallRows rows or more, token order: the persistent 256 x 256 kernel with a gated epilogue

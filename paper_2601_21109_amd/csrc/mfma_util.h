@@ -29,11 +29,11 @@ __device__ __forceinline__ void wait_cnt() {
 // XCDs, each with its own L2, so XCD x is given the x-th contiguous eighth of a tile order in
 // which GROUP_M row tiles sweep all column tiles before moving on: the 32 tiles in flight on one
 // XCD form an 8 x 4 patch that shares 8 x panels and 4 weight panels.
-__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* bm, int* bn) {
+// (wg: the workgroup's index among those of the GEMM; a launch may carry other workgroups in front)
+__device__ __forceinline__ bool tile_coords(int64_t wg, int tiles_m, int tiles_n, int* bm, int* bn) {
     constexpr int kXcd = 8, GROUP_M = 8;
     const int64_t n_tiles = (int64_t)tiles_m * tiles_n;
     const int64_t per_xcd = (n_tiles + kXcd - 1) / kXcd;
-    const int64_t wg = blockIdx.x;
     const int64_t tile = (wg % kXcd) * per_xcd + wg / kXcd;
     if (tile >= n_tiles) return false;
     const int64_t band_size = (int64_t)GROUP_M * tiles_n;

@@ -137,3 +137,102 @@ def test_argument_errors():
     with pytest.raises(B.CwlError) as e:
         B.chunkwise_lora_linear_shrunk(x, pw, small, ranks, scales, 2, sod, tab, rid)
     assert e.value.status == B.ERR_CAPACITY
+
+
+# ---- the scheduler as one call, with the first phase in the chunker's launch -------------------------
+def _tables_equal(t1, r1, t2, r2):
+    n = int(t1["chunk_offsets"][-1].item())
+    assert torch.equal(t1["chunk_offsets"], t2["chunk_offsets"])
+    for k in ("chunk_start", "chunk_len", "chunk_sum"):
+        assert torch.equal(t1[k][:n], t2[k][:n]), k
+    assert torch.equal(r1[:n], r2[:n])
+    assert int(t1["status_word"].item()) == int(t2["status_word"].item())
+
+
+@pytest.mark.parametrize("seq_lens,l_min,l_max", [([2048] * 8, 32, 512), ([700, 1, 0, 5000, 33], 4, 40),
+                                                  ([40000], 8, 90), ([9000, 100], 8, 64)])
+def test_schedule_alone_equals_partition_then_select(seq_lens, l_min, l_max):
+    wl = W.WORKLOADS["cfg1"]
+    n = sum(seq_lens)
+    g = torch.Generator(device=DEV).manual_seed(41)
+    h = (torch.rand(n, generator=g, device=DEV) * math.log(wl.vocab)).float()
+    h[::97] = float("nan")                 # status bits travel through the fused kernel too
+    so = torch.tensor(np.concatenate([[0], np.cumsum(seq_lens)]), dtype=torch.int32, device=DEV)
+    t1 = B.partition_chunks(h, so, l_min, l_max, wl.theta(), wl.delta())
+    r1 = B.select_ranks(t1, wl.taus(), 4)
+    t2, r2 = B.schedule_chunks(h, so, l_min, l_max, wl.theta(), wl.delta(), wl.taus(), 4)
+    torch.cuda.synchronize()
+    _tables_equal(t1, r1, t2, r2)
+    # a table too small for the chunks: same status bit, same first `cap` records
+    t3 = B.partition_chunks(h, so, l_min, l_max, wl.theta(), wl.delta(), cap=5)
+    r3 = B.select_ranks(t3, wl.taus(), 4)
+    t4, r4 = B.schedule_chunks(h, so, l_min, l_max, wl.theta(), wl.delta(), wl.taus(), 4, cap=5)
+    torch.cuda.synchronize()
+    assert int(t3["status_word"].item()) == int(t4["status_word"].item())
+    assert torch.equal(t3["chunk_offsets"], t4["chunk_offsets"])
+    assert torch.equal(t3["chunk_start"][:5], t4["chunk_start"][:5]) and torch.equal(r3[:5], r4[:5])
+
+
+@pytest.mark.parametrize("seq_lens,d_in,ranks", [
+    ([2048] * 8, 512, [8, 16, 32, 64]),        # one launch: 8 chunker workgroups in front of 256 product tiles
+    ([3000, 9000, 4100, 5], 256, [0, 24, 100]),   # padded rank 128; a sequence beyond the fused launch's LDS (4608 tokens)
+    ([20000], 128, [8, 16, 32, 64]),           # long-sequence chunker: the product is launched behind it
+    ([700, 900], 256, [8, 16, 32, 64]),        # few rows: split shrink behind the chunker
+    ([100, 200], 128, [8, 64]),                # up to 512 rows: nothing to do in the first phase
+    ([9000, 9000], 192, [40, 200]),            # padded rank 256: separate launches
+])
+def test_schedule_with_shrink(seq_lens, d_in, ranks):
+    """Whole path in the fused form against the calls one by one: same table, same rungs, same y (bit for bit),
+    and y against the oracle on a row sample."""
+    wl = W.WORKLOADS["cfg1"]
+    K, d_out, w = len(ranks), 264, 3
+    scales = [16.0 / r if r > 0 else 0.0 for r in ranks]
+    taus = wl.taus()[:K - 1]
+    n = sum(seq_lens)
+    g = torch.Generator(device=DEV).manual_seed(43)
+    h = (torch.rand(n, generator=g, device=DEV) * math.log(wl.vocab)).float()
+    so_h = np.concatenate([[0], np.cumsum(seq_lens)]).astype(np.int32)
+    so = torch.from_numpy(so_h).to(DEV)
+    x, Wm, A, Bm = operands(n, d_in, d_out, max(ranks), torch.bfloat16, 47)
+    pw = B.prepack_weights(Wm, A, Bm)
+    t1 = B.partition_chunks(h, so, 8, 90, wl.theta(), wl.delta())
+    r1 = B.select_ranks(t1, taus, K)
+    y1 = B.chunkwise_lora_linear(x, pw, None, None, ranks, scales, w, so, t1, r1)
+    u = B.lora_shrink(x, pw, ranks, scales, w)
+    u.zero_()
+    t2, r2 = B.schedule_chunks(h, so, 8, 90, wl.theta(), wl.delta(), taus, K, shrink=(x, pw, ranks, scales, w, u))
+    y2 = B.chunkwise_lora_linear_shrunk(x, pw, u, ranks, scales, w, so, t2, r2)
+    torch.cuda.synchronize()
+    _tables_equal(t1, r1, t2, r2)
+    assert same_bits(host(y1), host(y2))
+    nc = int(t1["chunk_offsets"][-1].item())
+    rows = np.unique(np.concatenate([np.arange(0, n, 53), np.arange(max(n - 70, 0), n)]))
+    ref = O.linear(host(x), host(Wm), host(A), host(Bm), ranks, scales, w, so_h, t1["chunk_offsets"].cpu().numpy(),
+                   t1["chunk_start"][:nc].cpu().numpy(), t1["chunk_len"][:nc].cpu().numpy(), r1[:nc].cpu().numpy(),
+                   rows=rows)
+    assert rel_err(host(y2)[rows], ref) <= TOL_BF16
+
+
+def test_schedule_with_shrink_repeats():
+    """The fused launch twice in a row on the same buffers, then with other scores: nothing carries over."""
+    wl = W.WORKLOADS["cfg1"]
+    ranks, scales, w = [8, 16, 32, 64], [2.0, 1.0, 0.5, 0.25], 4
+    seq_lens = [2048] * 8
+    n = sum(seq_lens)
+    so = torch.tensor(np.concatenate([[0], np.cumsum(seq_lens)]), dtype=torch.int32, device=DEV)
+    x, Wm, A, Bm = operands(n, 256, 264, 64, torch.bfloat16, 51)
+    pw = B.prepack_weights(Wm, A, Bm)
+    u = B.lora_shrink(x, pw, ranks, scales, w)
+    tab, ri = None, None
+    for seed in (1, 1, 2):
+        g = torch.Generator(device=DEV).manual_seed(seed)
+        h = (torch.rand(n, generator=g, device=DEV) * math.log(wl.vocab)).float()
+        tab, ri = B.schedule_chunks(h, so, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), 4, out=tab,
+                                    rank_idx=ri, shrink=(x, pw, ranks, scales, w, u))
+        y2 = B.chunkwise_lora_linear_shrunk(x, pw, u, ranks, scales, w, so, tab, ri)
+        t1 = B.partition_chunks(h, so, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+        r1 = B.select_ranks(t1, wl.taus(), 4)
+        y1 = B.chunkwise_lora_linear(x, pw, None, None, ranks, scales, w, so, t1, r1)
+        torch.cuda.synchronize()
+        _tables_equal(t1, r1, tab, ri)
+        assert same_bits(host(y1), host(y2))
