@@ -34,6 +34,11 @@ def parse():
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--proj", type=int, default=0)
     ap.add_argument("--group-rows", type=int, default=0)
+    ap.add_argument("--form", choices=("two_phase", "calls"), default="two_phase",
+                    help="two_phase (default): score_tokens, cwl_schedule_chunks (chunker + selector in one call, "
+                         "with x A riding in the chunker's launch), cwl_chunkwise_lora_linear_packed_shrunk (gate + "
+                         "main GEMM): five launches.  calls: the four calls of the boundary one after the other "
+                         "(seven launches).  Same results bit for bit; --group-rows 1 needs 'calls'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--all-projections", action="store_true",
@@ -258,12 +263,26 @@ def main():
     ri = B.select_ranks(table, wl.taus(), K)
     torch.cuda.synchronize()
 
-    def step():
+    def step_calls():
         B.score_tokens(logits, out=h)
         B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), out=table)
         B.select_ranks(table, wl.taus(), K, out=ri)
         B.chunkwise_lora_linear(x, packed, None, None, wl.ladder, wl.scales, wl.blend_w, sod, table, ri,
                                 out=y, group_rows=args.group_rows, workspace=ws)
+
+    two_phase = args.form == "two_phase" and args.group_rows == 0
+    u = B.lora_shrink(x, packed, wl.ladder, wl.scales, wl.blend_w) if two_phase else None
+
+    def step_two_phase():
+        # x A needs no chunk table: it rides in the chunker's launch, whose chain of look-ups occupies one
+        # wavefront per sequence; the linear call is then the gate on that product and the main GEMM
+        B.score_tokens(logits, out=h)
+        B.schedule_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), K, out=table, rank_idx=ri,
+                          shrink=(x, packed, wl.ladder, wl.scales, wl.blend_w, u))
+        B.chunkwise_lora_linear_shrunk(x, packed, u, wl.ladder, wl.scales, wl.blend_w, sod, table, ri, out=y,
+                                       workspace=ws)
+
+    step = step_two_phase if two_phase else step_calls
 
     def timed(fn, steps, warmup):
         for _ in range(warmup):
@@ -314,6 +333,24 @@ def main():
     for k, v in timed_prof.items():                   # the roofline kernels: from the timed region
         if v[1]:
             kern_ms[k] = v[0] / v[1]
+    # the other form of the step, same region length, and its kernels (the one-call linear is what the
+    # whole-call roofline figure is stated on)
+    ms_calls, calls_ms = None, None
+    if two_phase:
+        for _ in range(args.warmup):
+            step_calls()
+        torch.cuda.synchronize()
+        ms_calls, _ = timed(step_calls, args.steps, 0)
+        B.profile_enable((B.PROF_MAIN,))
+        timed(step_calls, args.steps, 0)
+        main_calls = B.profile_read(B.PROF_MAIN)
+        B.profile_enable(True)
+        timed(step_calls, args.steps, 0)
+        calls_prof = {name: B.profile_read(slot) for name, slot in slots}
+        B.profile_enable(False)
+        calls_ms = {k: (v[0] / v[1] if v[1] else None) for k, v in calls_prof.items()}
+        if main_calls[1]:
+            calls_ms["main"] = main_calls[0] / main_calls[1]
 
     # ---- chunk statistics and algorithmic work --------------------------------------------------
     n_chunks = int(table["chunk_offsets"][-1].item())
@@ -353,9 +390,14 @@ def main():
                    "seq_len": wl.seq_len, "vocab": wl.vocab, "d_in": d_in, "d_out": d_out,
                    "ladder": wl.ladder, "l_min": wl.l_min, "l_max": wl.l_max, "blend_w": wl.blend_w,
                    "group_rows": args.group_rows, "weights": "prepacked"},
+        "form": ("two_phase: score_tokens, schedule_chunks (chunker + x A in one launch, compact + selector in a "
+                 "second), chunkwise_lora_linear_packed_shrunk (gate, main GEMM): 5 launches" if two_phase else
+                 "calls: score_tokens, partition_chunks, select_ranks, chunkwise_lora_linear_packed: 7 launches"),
         "kernel_ms": kern_ms,
         "kernel_ms_note": "main and score: HIP events in the timed region; the rest: a second pass of the same "
-                          "steps with events around every kernel",
+                          "steps with events around every kernel" + (
+                              "; two_phase form: 'partition' = the chunker's launch with x A in it + compact/selector, "
+                              "'meta' = the gate kernel, 'shrink' and 'select' have no launch of their own" if two_phase else ""),
         "kernel_ms_all_events_pass": breakdown_ms,
         "chunks": {"count": n_chunks, "mean_len": float(cl.mean()) if n_chunks else 0.0,
                    "tokens_by_rank": {str(r): int(cl[rk == r].sum()) for r in wl.ladder},
@@ -376,13 +418,33 @@ def main():
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                                         "traffic": traffic.get("score"), "avg_launch_ms": kern_ms["score"],
                                         "bytes_per_launch": bytes_score}
-    lin_ms = sum(kern_ms[k] or 0.0 for k in ("meta", "shrink", "main"))
+    if two_phase:
+        out["calls_form"] = {"note": "the same step as the four calls of the boundary one after the other "
+                                     "(7 launches), same run", "ms_per_step": ms_calls,
+                             "value": N / (ms_calls * 1e-3), "kernel_ms": calls_ms}
+    lin_src = calls_ms if two_phase else kern_ms
+    lin_ms = sum(lin_src[k] or 0.0 for k in ("meta", "shrink", "main"))
     if lin_ms and "roofline" in out and bf16:
         # the benchmark spec's target is stated for the whole call: gate table + shrink + main GEMM, priced with
         # the whole layer's algorithmic flops
         out["roofline"]["whole_call"] = {"kernels": "token_meta + shrink + main", "ms": lin_ms,
                                          "flops": flops_alg, "achieved": flops_alg / (lin_ms * 1e-3) / 1e12,
                                          "frac": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        if two_phase and kern_ms["meta"] and kern_ms["main"]:
+            ms2 = kern_ms["meta"] + kern_ms["main"]
+            sched_alone = sum(calls_ms[k] or 0.0 for k in ("partition", "select"))
+            out["roofline"]["two_phase"] = {
+                "note": "the layer as cwl_lora_shrink_packed + cwl_chunkwise_lora_linear_packed_shrunk: x A runs in "
+                        "the chunker's launch, what is left on the step's critical path is the gate kernel and the "
+                        "main GEMM; 'frac' prices the whole layer's flops against that time plus what the chunker's "
+                        "launch grew by",
+                "second_phase_ms": ms2,
+                "schedule_with_product_ms": kern_ms["partition"],
+                "schedule_alone_ms": sched_alone,
+                "added_to_schedule_ms": max((kern_ms["partition"] or 0.0) - sched_alone, 0.0),
+                "flops": flops_alg,
+                "frac": flops_alg / ((ms2 + max((kern_ms["partition"] or 0.0) - sched_alone, 0.0)) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "frac_second_phase_alone": flops_alg / (ms2 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
     out["linear"] = {"ms": lin_ms, "tokens_per_s": N / (lin_ms * 1e-3) if lin_ms else None,
                      "effective_tflops": flops_alg / (lin_ms * 1e-3) / 1e12 if lin_ms else None,
                      "frac_of_bf16_peak": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS if lin_ms else None}
