@@ -25,4 +25,7 @@ from .reference import (  # noqa: F401
     num_threads,
     set_num_threads,
     bf16_round,
+    kv_quantise,
+    kv_dequantise,
+    SLOT_ABSENT,
 )

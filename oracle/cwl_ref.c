@@ -5,7 +5,8 @@
  * path computes.  It shares no code, header, table or helper with the HIP library; only the
  * tests, the smoke check and the bench's cpu_baseline leg may build or call it.
  *
- * All floating-point work is done in double.  Inputs are the exact fp32 values the device
+ * All floating-point work is done in double, with one exception: the INT8 codes of the KV-cache
+ * policy are decided in fp32, the precision the kernel decides them in.  Inputs are the exact fp32 values the device
  * sees (bf16 inputs are widened to fp32 by the caller, which is exact).
  *
  * Paper passages followed (arxiv 2601.21109):
@@ -24,6 +25,9 @@
  *     complexity-balanced micro-batches                                        -> cwl_ref_bucket_sequences
  *   - Sec. III-G chunk boundaries aligned inside a bucket                       -> cwl_ref_partition_aligned
  *   - the two above one token at a time, for a batch that is being decoded      -> cwl_ref_stream_step_aligned
+ *   - Sec. III-E / IV-F chunk difficulty toggles the KV-cache policy per chunk: INT8 on easy
+ *     chunks, full fidelity on hard ones                                        -> cwl_ref_kv_quantise
+ *     (its inverse, kv_dequantise, in reference.py)
  *   - Sec. III-C the ladder itself, one SVD of the adapter update: in reference.py (build_ladder),
  *     a float64 library SVD of the product written out
  *
@@ -734,5 +738,74 @@ int cwl_ref_stream_step_aligned(const int32_t* q_new, int32_t n_seqs, int32_t l_
         }
     }
     free(bclose);
+    return CWL_REF_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * KV-cache policy per chunk (Sec. III-E, the KV-cache policy controller; Sec. IV-F).  The paper
+ * lets chunk difficulty drive the memory policy: on easy spans selected heads may be stored in
+ * INT8, hard spans keep full fidelity, and the policy is toggled per chunk.  It gives no rule, no
+ * granularity of the scales and no layout.  Reading taken:
+ *   - a chunk is "easy" when its rung is below k_keep (0 <= rank_idx[c] < k_keep); a rung outside
+ *     the ladder's index range below zero counts as hard;
+ *   - every head of an easy chunk's rows is quantised (no head subset), symmetric, one scale per
+ *     (row, head): amax = max |x| over the head (NaN ignored), scale = amax / 127,
+ *     code = round-to-nearest-even(x * (127 / amax)) clamped to [-127, 127], all in fp32 (the
+ *     precision the kernel decides the integer in); amax = 0 gives scale 0 and codes 0; a NaN
+ *     element has code 0;
+ *   - layout: two pools.  Rows of easy chunks, in table order and row order inside a chunk, take the
+ *     next free row of the INT8 pool (codes [., H*D], scales [., H]); rows of the other chunks take
+ *     the next free row of the full-fidelity pool, copied bit for bit.  slot[t] >= 0: row of the INT8
+ *     pool; slot[t] <= -1: row -1 - slot[t] of the full pool; rows that no chunk covers are not
+ *     cached (slot = INT32_MIN).
+ * kv holds the exact bf16 values widened to fp32.  counts[0] / counts[1]: rows in the INT8 / full pool.
+ * ------------------------------------------------------------------------------------------------ */
+#define CWL_REF_SLOT_ABSENT INT32_MIN
+
+int cwl_ref_kv_quantise(const float* kv, int64_t n_rows, int32_t n_heads, int32_t head_dim,
+                        const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
+                        int64_t n_chunks, int32_t k_keep, int32_t* slot, int8_t* codes, float* scale,
+                        float* kept, int64_t* counts) {
+    if (n_rows < 0 || n_heads < 1 || head_dim < 1 || n_chunks < 0) return CWL_REF_ERR_INVALID;
+    const int64_t width = (int64_t)n_heads * head_dim;
+    for (int64_t t = 0; t < n_rows; ++t) slot[t] = CWL_REF_SLOT_ABSENT;
+    int64_t nq = 0, nf = 0;
+    for (int64_t c = 0; c < n_chunks; ++c) {
+        const int easy = rank_idx[c] >= 0 && rank_idx[c] < k_keep;
+        for (int32_t j = 0; j < chunk_len[c]; ++j) {
+            const int64_t t = (int64_t)chunk_start[c] + j;
+            if (t < 0 || t >= n_rows) return CWL_REF_ERR_INVALID;
+            const float* row = kv + t * width;
+            if (!easy) {
+                slot[t] = (int32_t)(-1 - nf);
+                memcpy(kept + nf * width, row, sizeof(float) * (size_t)width);
+                ++nf;
+                continue;
+            }
+            slot[t] = (int32_t)nq;
+            for (int32_t h = 0; h < n_heads; ++h) {
+                const float* x = row + (int64_t)h * head_dim;
+                float amax = 0.0f;
+                for (int32_t i = 0; i < head_dim; ++i) {
+                    const float a = fabsf(x[i]);
+                    if (a > amax) amax = a;          /* a NaN compares false: ignored */
+                }
+                const float inv = amax > 0.0f ? 127.0f / amax : 0.0f;
+                scale[nq * n_heads + h] = amax / 127.0f;
+                for (int32_t i = 0; i < head_dim; ++i) {
+                    const float v = x[i] * inv;
+                    int32_t code = 0;
+                    if (v == v) {
+                        const float r = rintf(v);        /* default rounding mode: nearest, ties to even */
+                        code = r > 127.0f ? 127 : (r < -127.0f ? -127 : (int32_t)r);
+                    }
+                    codes[nq * width + (int64_t)h * head_dim + i] = (int8_t)code;
+                }
+            }
+            ++nq;
+        }
+    }
+    counts[0] = nq;
+    counts[1] = nf;
     return CWL_REF_OK;
 }

@@ -68,6 +68,8 @@ def _load():
                                                 P, i32, P, P, i32, i32, P,
                                                 P, P, P, P, P, P, P, P, P, P, P, P]
     lib.cwl_ref_stream_step_aligned.restype = ctypes.c_int
+    lib.cwl_ref_kv_quantise.argtypes = [P, i64, i32, i32, P, P, P, i64, i32, P, P, P, P, P]
+    lib.cwl_ref_kv_quantise.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -364,6 +366,49 @@ def build_ladder(A, B):
     B2[:n, :] = root[:, None] * Vt[:n, :]
     sigma[:n] *= keep
     return A2, B2, sigma
+
+
+SLOT_ABSENT = -2 ** 31
+
+
+def kv_quantise(kv, n_heads, head_dim, chunk_start, chunk_len, rank_idx, k_keep):
+    """Chunk-level KV-cache policy (Sec. III-E, IV-F): rows of chunks whose rung is below ``k_keep`` go to an
+    INT8 pool (symmetric, one fp32 scale per row and head), the rows of the other chunks to a full-fidelity
+    pool.  ``kv``: [N, n_heads * head_dim] float32 holding exact bf16 values.  Returns a dict: slot int32 [N],
+    codes int8 [Nq, H*D], scale float32 [Nq, H], kept float32 [Nf, H*D]."""
+    x = _arr(kv, np.float32)
+    assert x.ndim == 2 and x.shape[1] == n_heads * head_dim
+    cs = _arr(chunk_start, np.int32).ravel()
+    cl = _arr(chunk_len, np.int32).ravel()
+    rk = _arr(rank_idx, np.int32).ravel()
+    n = x.shape[0]
+    slot = np.empty(n, dtype=np.int32)
+    codes = np.zeros((max(n, 1), x.shape[1]), dtype=np.int8)
+    scale = np.zeros((max(n, 1), n_heads), dtype=np.float32)
+    kept = np.zeros((max(n, 1), x.shape[1]), dtype=np.float32)
+    counts = np.zeros(2, dtype=np.int64)
+    st = _load().cwl_ref_kv_quantise(_ptr(x), n, int(n_heads), int(head_dim), _ptr(cs), _ptr(cl), _ptr(rk),
+                                     cs.shape[0], int(k_keep), _ptr(slot), _ptr(codes), _ptr(scale), _ptr(kept),
+                                     _ptr(counts))
+    assert st == OK, st
+    nq, nf = int(counts[0]), int(counts[1])
+    return {"slot": slot, "codes": codes[:nq].copy(), "scale": scale[:nq].copy(), "kept": kept[:nf].copy()}
+
+
+def kv_dequantise(slot, codes, scale, kept, n_heads, head_dim):
+    """The cache read back as bf16 values (float32 array [N, H*D]): a kept row as it was stored, an INT8 row as
+    code * scale formed in fp32 (the kernel's precision) and rounded to bf16 once, an absent row as zeros."""
+    slot = np.asarray(slot, dtype=np.int64)
+    out = np.zeros((slot.shape[0], n_heads * head_dim), dtype=np.float32)
+    for t, s in enumerate(slot):
+        if s == SLOT_ABSENT:
+            continue
+        if s < 0:
+            out[t] = kept[-1 - s]
+        else:
+            prod = codes[s].astype(np.float32).reshape(n_heads, head_dim) * scale[s].astype(np.float32)[:, None]
+            out[t] = bf16_round(prod.astype(np.float32).reshape(-1)).astype(np.float32)
+    return out
 
 
 def bf16_round(y):
