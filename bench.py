@@ -598,6 +598,40 @@ def main():
                                    "rate over both event-timed kernels (a few microseconds of launch gap included)",
                            "weight_bytes": w_bytes, **few}
 
+    # ---- chunk-level KV-cache policy: one of K / V of a layer with 32 heads x 128 on this batch, the lower half
+    #      of the ladder's rungs stored in INT8 (HBM-bound streaming; event-timed back-to-back calls) ----------
+    if not args.no_variants and bf16:
+        kv_h, kv_d, k_keep = 32, 128, max(K // 2, 1)
+        gk = torch.Generator(device=dev)
+        gk.manual_seed(77)
+        kv = torch.randn((N, kv_h * kv_d), generator=gk, device=dev).to(wl.dtype)
+        cache = B.kv_quantise_chunks(kv, kv_h, kv_d, k_keep, table, ri)
+        kv_back = B.kv_dequantise(cache, N)
+        torch.cuda.synchronize()
+        nq, nf = cache["counts"].cpu().tolist()
+        reps = max(args.steps, 10)
+        B.profile_enable((B.PROF_KV,))
+        for _ in range(reps):
+            B.kv_quantise_chunks(kv, kv_h, kv_d, k_keep, table, ri, out=cache)
+        torch.cuda.synchronize()
+        t_k, n_k = B.profile_read(B.PROF_KV)
+        B.profile_enable(False)
+        us_q = t_k / max(n_k, 1) * 1e3
+        us_d = timed(lambda: B.kv_dequantise(cache, N, out=kv_back), reps, 3)[0] * 1e3
+        wid = kv_h * kv_d
+        bytes_q = N * wid * 2.0 + nq * (wid + 4.0 * kv_h) + nf * wid * 2.0 + 4.0 * N
+        bytes_d = nq * (wid + 4.0 * kv_h) + nf * wid * 2.0 + 4.0 * N + N * wid * 2.0
+        out["kv_cache"] = {"note": "cwl_kv_quantise_chunks / cwl_kv_dequantise on one K (or V) tensor of the batch: rows of "
+                                   "chunks whose rung is below k_keep in INT8 (one fp32 scale per row and head), the rest "
+                                   "bf16; bytes = rows read + pools and slots written (quantise), the reverse (dequantise)",
+                           "n_heads": kv_h, "head_dim": kv_d, "k_keep": k_keep, "rows_int8": nq, "rows_full": nf,
+                           "cache_bytes_over_bf16": (nq * (wid + 4.0 * kv_h) + nf * wid * 2.0) / (N * wid * 2.0),
+                           "quantise_us": us_q, "quantise_GBps": bytes_q / (us_q * 1e-6) / 1e9,
+                           "quantise_frac_of_hbm_peak": bytes_q / (us_q * 1e-6) / 1e9 / PEAK_HBM_GBS,
+                           "dequantise_us": us_d, "dequantise_GBps": bytes_d / (us_d * 1e-6) / 1e9,
+                           "dequantise_frac_of_hbm_peak": bytes_d / (us_d * 1e-6) / 1e9 / PEAK_HBM_GBS}
+        del kv, cache, kv_back
+
     # ---- scheduler variants: budget of high-capacity chunks, percentile buckets, aligned chunker ---
     if not args.no_variants:
         n_b = max(1, min(4, wl.n_seqs // 2))

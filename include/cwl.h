@@ -551,6 +551,57 @@ cwl_status cwl_build_ladder(cwl_dtype dt, const void* A, int64_t lda, const void
                             size_t workspace_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * cwl_kv_quantise_chunks / cwl_kv_dequantise -- the chunk-level KV-cache policy (Sec. III-E: chunk
+ * difficulty drives the memory policy, easy spans may be stored in INT8, hard spans keep full
+ * fidelity, the policy is toggled per chunk; Sec. IV-F).  The paper gives no rule, scale granularity
+ * or layout; this call takes: a chunk is easy when its rung is below k_keep (0 <= rank_idx[c] <
+ * k_keep); every head of an easy chunk's rows is quantised symmetrically with one fp32 scale per
+ * (row, head): amax = max |x| over the head (a NaN element is ignored and gets code 0),
+ *      scale = amax / 127,     code = round-to-nearest-even(x * (127 / amax)) in [-127, 127]
+ * (fp32; amax == 0: scale 0, codes 0).  The cache is kept in two pools: rows of easy chunks take the
+ * next rows of the INT8 pool, rows of the other chunks the next rows of the full pool, copied bit for
+ * bit, both in table order and row order inside a chunk.  The sparsifying and windowing policies the
+ * paper also names need attention weights and are not part of this library.
+ *
+ *   kv          bf16 [n_rows, n_heads * head_dim], leading dimension ld (elements); one of K or V
+ *   chunk_offsets / chunk_start / chunk_len / rank_idx / chunk_cap   the chunk table as written by the
+ *               chunker and the selector (chunk starts ascending); n_seqs sequences
+ *   p           host: n_heads >= 1, head_dim in {32, 64, 128, 256, 512}, n_heads * head_dim <= 8192
+ *               (else CWL_ERR_UNSUPPORTED), k_keep >= 0 (0: nothing is quantised)
+ *   slot        [n_rows] written: >= 0 row of the INT8 pool; <= -1: row -1 - slot of the full pool;
+ *               CWL_KV_SLOT_ABSENT: not cached (no chunk covers the row, or its pool is full)
+ *   counts      [2] written: rows the INT8 pool / the full pool need for this table
+ *   q_codes     int8 [cap_q, n_heads * head_dim], q_scale fp32 [cap_q, n_heads]: the INT8 pool
+ *   f_pool      bf16 [cap_f, n_heads * head_dim]: the full pool; n_rows rows each always suffice
+ *   status_word one int32, written: 0, or CWL_STATUS_CAPACITY when a pool was too small
+ *   workspace   >= cwl_kv_workspace_bytes(chunk_cap) bytes, 256-byte aligned
+ * 16-byte aligned kv / f_pool, 8-byte aligned q_codes, ld % 8 == 0 (else CWL_ERR_UNSUPPORTED).
+ *
+ * cwl_kv_dequantise reads the cache back as bf16 [n_rows, n_heads * head_dim] (ld_out): a full-pool
+ * row as stored, an INT8 row as code * scale (fp32 product, rounded to bf16 once), an absent row as
+ * zeros -- the form exact attention kernels take.
+ * ------------------------------------------------------------------------------------------- */
+#define CWL_KV_SLOT_ABSENT (-2147483647 - 1)
+
+typedef struct {
+    int32_t n_heads, head_dim;
+    int32_t k_keep;
+} cwl_kv_params;
+
+size_t cwl_kv_workspace_bytes(int32_t chunk_cap);
+
+cwl_status cwl_kv_quantise_chunks(const void* kv, int64_t ld, int64_t n_rows, const int32_t* chunk_offsets,
+                                  int32_t n_seqs, const int32_t* chunk_start, const int32_t* chunk_len,
+                                  const int32_t* rank_idx, int32_t chunk_cap, const cwl_kv_params* p /*host*/,
+                                  int32_t* slot, int32_t* counts, int8_t* q_codes, float* q_scale,
+                                  int64_t cap_q, void* f_pool, int64_t cap_f, int32_t* status_word,
+                                  void* workspace, size_t workspace_bytes, void* stream);
+
+cwl_status cwl_kv_dequantise(const int32_t* slot, int64_t n_rows, const int8_t* q_codes,
+                             const float* q_scale, const void* f_pool, const cwl_kv_params* p /*host*/,
+                             void* out, int64_t ld_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Measurement aid (not part of the method): per-kernel durations from HIP events.
  * cwl_profile_enable(slot_mask), bit i standing for slot i, creates the events on first use (this
  * is the one place the library creates runtime objects), zeroes the counters and makes every
@@ -569,7 +620,8 @@ cwl_status cwl_build_ladder(cwl_dtype dt, const void* A, int64_t lda, const void
 #define CWL_PROF_SHRINK 4     /* shrink GEMM (x A, gated)                                */
 #define CWL_PROF_MAIN 5       /* main GEMM (x W + uhat B); with at most 512 rows: the     
                                  partial products x [W | A]                              */
-#define CWL_PROF_SLOTS 6
+#define CWL_PROF_KV 6         /* both kernels of cwl_kv_quantise_chunks                  */
+#define CWL_PROF_SLOTS 7
 
 cwl_status cwl_profile_enable(int32_t slot_mask);
 cwl_status cwl_profile_read(int32_t slot, double* total_ms /*host*/, int64_t* launches /*host*/);

@@ -406,7 +406,8 @@ def kv_dequantise(slot, codes, scale, kept, n_heads, head_dim):
         if s < 0:
             out[t] = kept[-1 - s]
         else:
-            prod = codes[s].astype(np.float32).reshape(n_heads, head_dim) * scale[s].astype(np.float32)[:, None]
+            with np.errstate(invalid="ignore"):          # code 0 times an infinite scale is NaN, as on the device
+                prod = codes[s].astype(np.float32).reshape(n_heads, head_dim) * scale[s].astype(np.float32)[:, None]
             out[t] = bf16_round(prod.astype(np.float32).reshape(-1)).astype(np.float32)
     return out
 

@@ -28,15 +28,16 @@ EXPORTS = ["cwl_status_string", "cwl_abi_version", "cwl_score_tokens", "cwl_comp
            "cwl_linear_packed_workspace_bytes", "cwl_chunkwise_lora_linear",
            "cwl_chunkwise_lora_linear_packed", "cwl_chunkwise_lora_linear_packed_static",
            "cwl_lora_shrink_bytes", "cwl_lora_shrink_packed", "cwl_chunkwise_lora_linear_packed_shrunk",
-           "cwl_schedule_chunks",
+           "cwl_schedule_chunks", "cwl_kv_workspace_bytes", "cwl_kv_quantise_chunks", "cwl_kv_dequantise",
            "cwl_stream_step", "cwl_stream_step_aligned",
            "cwl_gated_lora_linear_packed", "cwl_packed_weights_grouped_bytes",
            "cwl_linear_grouped_workspace_bytes", "cwl_prepack_weights_grouped",
            "cwl_chunkwise_lora_linear_grouped_packed", "cwl_gated_lora_linear_grouped_packed",
            "cwl_ladder_workspace_bytes", "cwl_build_ladder",
            "cwl_profile_enable", "cwl_profile_read"]
-PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN = range(6)
-PROF_SLOTS = 6
+PROF_SCORE, PROF_PARTITION, PROF_SELECT, PROF_META, PROF_SHRINK, PROF_MAIN, PROF_KV = range(7)
+PROF_SLOTS = 7
+KV_SLOT_ABSENT = -2 ** 31
 
 
 class ChunkParams(ctypes.Structure):
@@ -47,6 +48,10 @@ class ChunkParams(ctypes.Structure):
 class ScoreMix(ctypes.Structure):
     _fields_ = [("n", ctypes.c_int32), ("window", ctypes.c_int32), ("w_entropy", ctypes.c_float),
                 ("w_novelty", ctypes.c_float), ("w_prior", ctypes.c_float), ("prior_len", ctypes.c_float)]
+
+
+class KvParams(ctypes.Structure):
+    _fields_ = [("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("k_keep", ctypes.c_int32)]
 
 
 class LinearDesc(ctypes.Structure):
@@ -128,6 +133,10 @@ def lib():
     L.cwl_gated_lora_linear_grouped_packed.argtypes = [dp, gp, P, P, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_static.argtypes = [dp, P, P, P, i32, P, P, P, P, i32, P, P]
     L.cwl_lora_shrink_packed.argtypes = [dp, P, P, P, sz, P]
+    kp = ctypes.POINTER(KvParams)
+    L.cwl_kv_workspace_bytes.argtypes = [i32]
+    L.cwl_kv_quantise_chunks.argtypes = [P, i64, i64, P, i32, P, P, P, i32, kp, P, P, P, P, i64, P, i64, P, P, sz, P]
+    L.cwl_kv_dequantise.argtypes = [P, i64, P, P, P, kp, P, i64, P]
     L.cwl_schedule_chunks.argtypes = [P, i64, P, i32, ctypes.POINTER(ChunkParams), ctypes.POINTER(ctypes.c_float), i32,
                                       P, P, P, P, P, i32, P, P, sz, dp, P, P, P, sz, P]
     L.cwl_chunkwise_lora_linear_packed_shrunk.argtypes = [dp, P, P, P, sz, P, i32, P, P, P, P, i32, P, P, sz, P]
@@ -497,6 +506,49 @@ def chunkwise_lora_linear_shrunk(x, packed, u, ranks, scales, blend_w, seq_offse
         d.ref(), _ptr(x), _ptr(packed.blob), _ptr(u), u.numel(), _ptr(seq_offsets), seq_offsets.numel() - 1,
         _ptr(table["chunk_offsets"]), _ptr(table["chunk_start"]), _ptr(table["chunk_len"]), _ptr(rank_idx),
         table["cap"], _ptr(out), _ptr(ws), ws.numel(), _stream()), "cwl_chunkwise_lora_linear_packed_shrunk")
+    return out
+
+
+def kv_quantise_chunks(kv, n_heads, head_dim, k_keep, table, rank_idx, cap_q=None, cap_f=None, out=None):
+    """Chunk-level KV-cache policy: rows of chunks whose rung is below `k_keep` into an INT8 pool (one fp32 scale
+    per row and head), the other chunks' rows into a full-fidelity pool.  kv: bf16 [N, n_heads * head_dim].
+    Returns a dict of device tensors: slot, counts, q_codes, q_scale, f_pool, status_word (+ the shape)."""
+    assert kv.is_cuda and kv.dim() == 2 and kv.stride(1) == 1 and kv.dtype == torch.bfloat16
+    n, width = kv.shape
+    assert width == n_heads * head_dim
+    dev = kv.device
+    cap_q = n if cap_q is None else int(cap_q)
+    cap_f = n if cap_f is None else int(cap_f)
+    p = KvParams(int(n_heads), int(head_dim), int(k_keep))
+    if out is None:
+        out = {"slot": torch.empty(max(n, 1), dtype=torch.int32, device=dev),
+               "counts": torch.empty(2, dtype=torch.int32, device=dev),
+               "q_codes": torch.empty((max(cap_q, 1), width), dtype=torch.int8, device=dev),
+               "q_scale": torch.empty((max(cap_q, 1), n_heads), dtype=torch.float32, device=dev),
+               "f_pool": torch.empty((max(cap_f, 1), width), dtype=torch.bfloat16, device=dev),
+               "status_word": torch.empty(1, dtype=torch.int32, device=dev),
+               "_workspace": _ws(lib().cwl_kv_workspace_bytes(table["cap"]), dev),
+               "cap_q": cap_q, "cap_f": cap_f, "n_heads": int(n_heads), "head_dim": int(head_dim)}
+    ws = out["_workspace"]
+    n_seqs = table["chunk_offsets"].numel() - 1
+    _check(lib().cwl_kv_quantise_chunks(
+        _ptr(kv), kv.stride(0) if n > 1 else width, n, _ptr(table["chunk_offsets"]), n_seqs, _ptr(table["chunk_start"]),
+        _ptr(table["chunk_len"]), _ptr(rank_idx), table["cap"], ctypes.byref(p), _ptr(out["slot"]), _ptr(out["counts"]),
+        _ptr(out["q_codes"]), _ptr(out["q_scale"]), out["cap_q"], _ptr(out["f_pool"]), out["cap_f"],
+        _ptr(out["status_word"]), _ptr(ws), ws.numel(), _stream()), "cwl_kv_quantise_chunks")
+    return out
+
+
+def kv_dequantise(cache, n_rows, out=None):
+    """The cache written by kv_quantise_chunks read back as bf16 [n_rows, n_heads * head_dim]."""
+    width = cache["n_heads"] * cache["head_dim"]
+    dev = cache["slot"].device
+    if out is None:
+        out = torch.empty((n_rows, width), dtype=torch.bfloat16, device=dev)
+    p = KvParams(cache["n_heads"], cache["head_dim"], 0)
+    _check(lib().cwl_kv_dequantise(_ptr(cache["slot"]), int(n_rows), _ptr(cache["q_codes"]), _ptr(cache["q_scale"]),
+                                   _ptr(cache["f_pool"]), ctypes.byref(p), _ptr(out),
+                                   out.stride(0) if n_rows > 1 else width, _stream()), "cwl_kv_dequantise")
     return out
 
 
