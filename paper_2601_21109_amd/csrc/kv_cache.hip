@@ -5,9 +5,13 @@
 //
 //   kv_plan_kernel       one workgroup: per chunk its policy and its first row in its pool (two
 //                        exclusive scans over the chunk lengths, in table order), the pool totals
-//   kv_quantise_kernel   one wavefront per row: the row's chunk (binary search in the ascending chunk
-//                        starts), its slot, then the row itself: 16-byte loads, the maximum of a head
-//                        over the lanes that hold it, codes packed eight to a lane
+//   kv_slot_kernel       one thread per row: the row's chunk (binary search in the ascending chunk
+//                        starts) and with it its slot.  A kernel of its own because the search is a
+//                        chain of dependent look-ups: in front of every wavefront's stores it made the
+//                        streaming kernel wait 8 round trips per row (120 us for 16384 rows of 8 KB);
+//                        here all rows wait at once
+//   kv_quantise_kernel   one wavefront per row: 16-byte loads, the maximum of a head over the lanes
+//                        that hold it, codes packed eight to a lane
 //   kv_dequantise_kernel one wavefront per row: the row read back as bf16
 #include "common.h"
 
@@ -16,7 +20,7 @@ namespace {
 using cwl::kWave;
 
 constexpr int kPlanThreads = 1024;
-constexpr int kRowsPerBlock = 4;        // one wavefront per row
+constexpr int kRowsPerBlock = 4;        // wavefronts per workgroup (one per row, or per row segment)
 constexpr int kMaxPasses = 16;          // 512 elements per pass: rows of up to 8192 elements
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
@@ -113,25 +117,12 @@ __device__ __forceinline__ int32_t code_of(float x, float inv) {
     return r > 127.0f ? 127 : (r < -127.0f ? -127 : (int32_t)r);
 }
 
-__global__ void __launch_bounds__(kRowsPerBlock * 64)
-kv_quantise_kernel(const uint16_t* __restrict__ kv, int64_t ld, int64_t n_rows,
-                   const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_len,
-                   const int32_t* __restrict__ chunk_slot, const int32_t* __restrict__ n_chunks_p, KvShape sh,
-                   int32_t* __restrict__ slot, int8_t* __restrict__ q_codes, float* __restrict__ q_scale,
-                   int64_t cap_q, uint16_t* __restrict__ f_pool, int64_t cap_f, int32_t* __restrict__ status_word) {
-    const int lane = threadIdx.x & 63;
-    const int64_t t = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+__global__ void __launch_bounds__(256)
+kv_slot_kernel(int64_t n_rows, const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_len,
+               const int32_t* __restrict__ chunk_slot, const int32_t* __restrict__ n_chunks_p, int64_t cap_q,
+               int64_t cap_f, int32_t* __restrict__ slot, int32_t* __restrict__ status_word) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= n_rows) return;
-    const int passes = (sh.width + 511) / 512;
-    // the row's data first: its address does not depend on the look-up below
-    u32x4 v[kMaxPasses];
-    const uint16_t* rp = kv + t * ld;
-#pragma unroll
-    for (int p = 0; p < kMaxPasses; ++p) {
-        const int e0 = p * 512 + lane * 8;
-        v[p] = u32x4{0u, 0u, 0u, 0u};
-        if (p < passes && e0 < sh.width) v[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rp + e0));
-    }
     // chunk of the row: the last chunk whose start is <= t (starts ascend in the chunker's table)
     const int32_t n_chunks = *n_chunks_p;
     int32_t lo = 0, hi = n_chunks;
@@ -151,26 +142,50 @@ kv_quantise_kernel(const uint16_t* __restrict__ kv, int64_t ld, int64_t n_rows,
             } else if (idx < cap_f) {
                 my_slot = (int32_t)(-1 - idx);
             }
-            if (my_slot == INT32_MIN && lane == 0) atomicOr(status_word, (int32_t)CWL_STATUS_CAPACITY);
+            if (my_slot == INT32_MIN) atomicOr(status_word, (int32_t)CWL_STATUS_CAPACITY);
         }
     }
-    if (lane == 0) slot[t] = my_slot;
+    slot[t] = my_slot;
+}
+
+// A wavefront takes a segment of PASSES * 512 elements of one row (whole heads: a head has at most 512
+// elements), `segs` segments per row.  PASSES is a compile-time constant of at most four: the segment lives
+// in registers between its loads and its stores; with a run-time bound on these loops it went through
+// scratch memory, and eight passes at once took 231 registers (two wavefronts per SIMD).
+template <int PASSES>
+__global__ void __launch_bounds__(kRowsPerBlock * 64)
+kv_quantise_kernel(const uint16_t* __restrict__ kv, int64_t ld, int64_t n_rows, KvShape sh, int32_t segs,
+                   const int32_t* __restrict__ slot, int8_t* __restrict__ q_codes, float* __restrict__ q_scale,
+                   uint16_t* __restrict__ f_pool) {
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+    const int64_t t = w / segs;
+    if (t >= n_rows) return;
+    const int seg0 = (int)(w % segs) * PASSES * 512;
+    const int32_t my_slot = slot[t];
+    u32x4 v[PASSES];
+    const uint16_t* rp = kv + t * ld;
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+        const int e0 = seg0 + p * 512 + lane * 8;
+        v[p] = u32x4{0u, 0u, 0u, 0u};
+        if (e0 < sh.width) v[p] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rp + e0));
+    }
     if (my_slot == INT32_MIN) return;
     if (my_slot < 0) {
         uint16_t* dst = f_pool + (int64_t)(-1 - my_slot) * sh.width;
 #pragma unroll
-        for (int p = 0; p < kMaxPasses; ++p) {
-            const int e0 = p * 512 + lane * 8;
-            if (p < passes && e0 < sh.width) *reinterpret_cast<u32x4*>(dst + e0) = v[p];
+        for (int p = 0; p < PASSES; ++p) {
+            const int e0 = seg0 + p * 512 + lane * 8;
+            if (e0 < sh.width) *reinterpret_cast<u32x4*>(dst + e0) = v[p];
         }
         return;
     }
     int8_t* crow = q_codes + (int64_t)my_slot * sh.width;
     float* srow = q_scale + (int64_t)my_slot * sh.n_heads;
 #pragma unroll
-    for (int p = 0; p < kMaxPasses; ++p) {
-        if (p >= passes) break;
-        const int e0 = p * 512 + lane * 8;
+    for (int p = 0; p < PASSES; ++p) {
+        const int e0 = seg0 + p * 512 + lane * 8;
         float x[8];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -286,10 +301,21 @@ extern "C" cwl_status cwl_kv_quantise_chunks(const void* kv, int64_t ld, int64_t
                                                             sh.k_keep, chunk_slot, n_chunks_dev, counts, status_word);
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (n_rows > 0) {
-        const unsigned blocks = (unsigned)((n_rows + kRowsPerBlock - 1) / kRowsPerBlock);
-        kv_quantise_kernel<<<dim3(blocks), dim3(kRowsPerBlock * 64), 0, st>>>(
-            static_cast<const uint16_t*>(kv), ld, n_rows, chunk_start, chunk_len, chunk_slot, n_chunks_dev, sh, slot,
-            q_codes, q_scale, cap_q, static_cast<uint16_t*>(f_pool), cap_f, status_word);
+        kv_slot_kernel<<<dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st>>>(
+            n_rows, chunk_start, chunk_len, chunk_slot, n_chunks_dev, cap_q, cap_f, slot, status_word);
+        CWL_RETURN_IF_LAUNCH_FAILED();
+        const int passes = (sh.width + 511) / 512;
+        const int per_wave = passes >= 4 ? 4 : (passes >= 2 ? 2 : 1);
+        const int32_t segs = (passes + per_wave - 1) / per_wave;
+        const int64_t waves = n_rows * segs;
+        const unsigned blocks = (unsigned)((waves + kRowsPerBlock - 1) / kRowsPerBlock);
+#define CWL_KV_LAUNCH(P)                                                                                  \
+    kv_quantise_kernel<P><<<dim3(blocks), dim3(kRowsPerBlock * 64), 0, st>>>(                             \
+        static_cast<const uint16_t*>(kv), ld, n_rows, sh, segs, slot, q_codes, q_scale, static_cast<uint16_t*>(f_pool))
+        if (per_wave == 1) CWL_KV_LAUNCH(1);
+        else if (per_wave == 2) CWL_KV_LAUNCH(2);
+        else CWL_KV_LAUNCH(4);
+#undef CWL_KV_LAUNCH
     }
     cwl::prof_end(CWL_PROF_KV, st);
     CWL_RETURN_IF_LAUNCH_FAILED();
