@@ -10,8 +10,11 @@
  * Around them: cwl_compose_scores (the other difficulty signals of Sec. III-A mixed into the score),
  * cwl_select_ranks_budget / cwl_bucket_sequences / cwl_partition_chunks_aligned (the chunker's budget
  * and the batch controller of Sec. III-G and IV-F), cwl_stream_step[_aligned] +
- * cwl_gated_lora_linear_packed (the same rules one token per sequence at a time, for decoding), and
- * the set-up calls cwl_prepack_weights and cwl_build_ladder (the ladder of Sec. III-C by one SVD).
+ * cwl_gated_lora_linear_packed (the same rules one token per sequence at a time, for decoding),
+ * cwl_schedule_chunks + cwl_lora_shrink_packed + cwl_chunkwise_lora_linear_packed_shrunk (the same
+ * pipeline in five launches: the part of the layer that needs no chunk table rides in the chunker's
+ * launch), cwl_kv_quantise_chunks / cwl_kv_dequantise (the chunk-level KV-cache policy of Sec. III-E),
+ * and the set-up calls cwl_prepack_weights and cwl_build_ladder (the ladder of Sec. III-C by one SVD).
  *
  * General rules
  *   - Every pointer is a DEVICE pointer unless its comment says "host".
