@@ -377,3 +377,100 @@ def test_build_ladder_argument_errors(L):
     assert call(ws_bytes=1024) == B.ERR_CAPACITY
     assert L.cwl_ladder_workspace_bytes(64) >= 8 * 64 * 64 * 8
     assert L.cwl_ladder_workspace_bytes(0) == 0 and L.cwl_ladder_workspace_bytes(B.MAX_RANK + 1) == 0
+
+
+def test_two_phase_and_schedule_argument_errors(L):
+    """cwl_lora_shrink_packed, cwl_chunkwise_lora_linear_packed_shrunk and cwl_schedule_chunks reject bad
+    arguments before anything is launched."""
+    nbytes = L.cwl_lora_shrink_bytes
+    assert nbytes(make_desc().ref()) >= 4 * 128 * 64            # 128 rows x 64 padded directions, fp32
+    assert nbytes(make_desc(group_rows=1).ref()) == 0
+    assert nbytes(make_desc(n_rows=-1).ref()) == 0
+
+    def shrink(d, x=P(0x10000), packed=P(0x20000), u=P(0x30000), u_bytes=1 << 30):
+        return L.cwl_lora_shrink_packed(d.ref(), x, packed, u, u_bytes, None)
+
+    assert shrink(make_desc(n_rows=-1)) == B.ERR_INVALID_ARG
+    assert shrink(make_desc(group_rows=1)) == B.ERR_UNSUPPORTED
+    assert shrink(make_desc(n_rows=0)) == B.OK
+    assert shrink(make_desc(), x=None) == B.ERR_NULL
+    assert shrink(make_desc(), packed=None) == B.ERR_NULL
+    assert shrink(make_desc(), u=None) == B.ERR_NULL
+    assert shrink(make_desc(), u=P(0x30010)) == B.ERR_INVALID_ARG
+    assert shrink(make_desc(), u_bytes=16) == B.ERR_CAPACITY
+
+    def second(d, x=P(0x10000), packed=P(0x20000), u=P(0x30000), u_bytes=1 << 30, y=P(0x40000), ws=P(0x50000),
+               ws_bytes=1 << 30):
+        return L.cwl_chunkwise_lora_linear_packed_shrunk(d.ref(), x, packed, u, u_bytes, P(), 1, P(), P(), P(), P(), 8,
+                                                         y, ws, ws_bytes, None)
+
+    assert second(make_desc(n_rows=-1)) == B.ERR_INVALID_ARG
+    assert second(make_desc(group_rows=1)) == B.ERR_UNSUPPORTED
+    assert second(make_desc(n_rows=0)) == B.OK
+    assert second(make_desc(), y=None) == B.ERR_NULL
+    assert second(make_desc(), u=None) == B.ERR_NULL
+    assert second(make_desc(), u_bytes=16) == B.ERR_CAPACITY
+    assert second(make_desc(), ws_bytes=16) == B.ERR_CAPACITY
+    assert second(make_desc(), ws=P(0x50010)) == B.ERR_INVALID_ARG
+
+    th = (ctypes.c_float * 2)(1.0, 2.0)
+
+    def schedule(l_min=4, l_max=8, K=3, thresholds=th, rank_idx=P(0x60000), shrink_d=None, x=P(0x10000),
+                 packed=P(0x20000), u=P(0x30000), u_bytes=1 << 30, ws=P(0x70000), ws_bytes=1 << 20):
+        p = B.ChunkParams(l_min, l_max, math.inf, math.inf)
+        return L.cwl_schedule_chunks(P(0x1000), 64, P(0x2000), 1, ctypes.byref(p), thresholds, K, P(0x3000),
+                                     P(0x4000), P(0x5000), P(0x6000), rank_idx, 32, P(0x7000), ws, ws_bytes,
+                                     shrink_d.ref() if shrink_d is not None else None, x, packed, u, u_bytes, None)
+
+    assert schedule(K=0) == B.ERR_INVALID_ARG
+    assert schedule(K=B.MAX_LADDER + 1) == B.ERR_INVALID_ARG
+    assert schedule(thresholds=None) == B.ERR_NULL
+    assert schedule(thresholds=(ctypes.c_float * 2)(2.0, 1.0)) == B.ERR_INVALID_ARG      # descending
+    assert schedule(l_min=5, l_max=8) == B.ERR_INFEASIBLE
+    assert schedule(rank_idx=None) == B.ERR_NULL
+    assert schedule(ws_bytes=16) == B.ERR_CAPACITY
+    assert schedule(shrink_d=make_desc(group_rows=1)) == B.ERR_UNSUPPORTED
+    assert schedule(shrink_d=make_desc(), u=None) == B.ERR_NULL
+    assert schedule(shrink_d=make_desc(), u_bytes=16) == B.ERR_CAPACITY
+
+
+def test_kv_cache_argument_errors(L):
+    assert L.cwl_kv_workspace_bytes(-1) == 0
+    assert L.cwl_kv_workspace_bytes(100) >= 404
+
+    def quantise(n_heads=4, head_dim=64, k_keep=1, kv=P(0x10000), ld=256, n_rows=64, slot=P(0x20000),
+                 counts=P(0x30000), codes=P(0x40000), scale=P(0x50000), cap_q=64, pool=P(0x60000), cap_f=64,
+                 status=P(0x70000), ws=P(0x80000), ws_bytes=1 << 20):
+        p = B.KvParams(n_heads, head_dim, k_keep)
+        return L.cwl_kv_quantise_chunks(kv, ld, n_rows, P(0x1000), 1, P(0x2000), P(0x3000), P(0x4000), 32,
+                                        ctypes.byref(p), slot, counts, codes, scale, cap_q, pool, cap_f, status, ws,
+                                        ws_bytes, None)
+
+    assert quantise(n_heads=0) == B.ERR_INVALID_ARG
+    assert quantise(k_keep=-1) == B.ERR_INVALID_ARG
+    assert quantise(head_dim=16) == B.ERR_UNSUPPORTED          # fewer than four lanes per head
+    assert quantise(head_dim=96, ld=384) == B.ERR_UNSUPPORTED  # lanes per head not a power of two
+    assert quantise(n_heads=32, head_dim=512, ld=16384) == B.ERR_UNSUPPORTED   # rows beyond 8192 elements
+    assert quantise(ld=128) == B.ERR_INVALID_ARG               # shorter than a row
+    assert quantise(ld=260) == B.ERR_UNSUPPORTED
+    assert quantise(kv=None) == B.ERR_NULL
+    assert quantise(slot=None) == B.ERR_NULL
+    assert quantise(counts=None) == B.ERR_NULL
+    assert quantise(status=None) == B.ERR_NULL
+    assert quantise(codes=None) == B.ERR_NULL
+    assert quantise(pool=None) == B.ERR_NULL
+    assert quantise(ws=None) == B.ERR_NULL
+    assert quantise(ws=P(0x80010)) == B.ERR_INVALID_ARG
+    assert quantise(ws_bytes=16) == B.ERR_CAPACITY
+    assert quantise(kv=P(0x10008)) == B.ERR_UNSUPPORTED
+    assert quantise(n_rows=-1) == B.ERR_INVALID_ARG
+
+    def dequantise(n_heads=4, head_dim=64, slot=P(0x20000), out=P(0x90000), ld=256, n_rows=64):
+        p = B.KvParams(n_heads, head_dim, 0)
+        return L.cwl_kv_dequantise(slot, n_rows, P(0x40000), P(0x50000), P(0x60000), ctypes.byref(p), out, ld, None)
+
+    assert dequantise(head_dim=16) == B.ERR_UNSUPPORTED
+    assert dequantise(ld=128) == B.ERR_INVALID_ARG
+    assert dequantise(slot=None) == B.ERR_NULL
+    assert dequantise(out=None) == B.ERR_NULL
+    assert dequantise(n_rows=0) == B.OK
