@@ -110,3 +110,40 @@ def test_cfg3_skewed_mix_table_bit_exact():
     assert_tables_equal(gpu, ref)
     frac_top = gpu["chunk_len"][gpu["rank_idx"] == len(wl.ladder) - 1].sum() / wl.n_rows
     assert 0.55 < frac_top < 0.85       # low sigma = near-uniform = hard: about 70 % of tokens on the top rung
+
+
+def test_cfg1_two_phase_step_in_the_benchmarks_configuration():
+    """The benchmark's default step at full size (16384 x 32000 logits, 4096 -> 4096, packed weights): scores,
+    cwl_schedule_chunks with x A riding in the chunker's launch, then gate + main GEMM.  Table and rungs against
+    the oracle on the device's own scores (bit for bit), y against the oracle on a row sample, and against the
+    four calls one after the other (bit for bit)."""
+    from helpers import assert_tables_equal, gpu_table_to_host, oracle_table
+    wl = W.WORKLOADS["cfg1"]
+    K = len(wl.ladder)
+    so = W.seq_offsets(wl)
+    sod = torch.from_numpy(so).to(DEV)
+    logits = W.logits(wl, DEV)
+    x, Wm, A, Bm = W.linear_operands(wl, 0, DEV)
+    pw = B.prepack_weights(Wm, A, Bm)
+    h = B.score_tokens(logits)
+    del logits
+    u = B.lora_shrink(x, pw, wl.ladder, wl.scales, wl.blend_w)
+    u.zero_()
+    table, ri = B.schedule_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta(), wl.taus(), K,
+                                  shrink=(x, pw, wl.ladder, wl.scales, wl.blend_w, u))
+    y = B.chunkwise_lora_linear_shrunk(x, pw, u, wl.ladder, wl.scales, wl.blend_w, sod, table, ri)
+    t1 = B.partition_chunks(h, sod, wl.l_min, wl.l_max, wl.theta(), wl.delta())
+    r1 = B.select_ranks(t1, wl.taus(), K)
+    y1 = B.chunkwise_lora_linear(x, pw, None, None, wl.ladder, wl.scales, wl.blend_w, sod, t1, r1)
+    torch.cuda.synchronize()
+    gpu = gpu_table_to_host(table, ri)
+    ref = oracle_table(host(h), so, wl)
+    assert gpu["status"] == 0
+    assert_tables_equal(gpu, ref)
+    assert torch.equal(y, y1)
+    rows = sample_rows(wl.n_rows, ref["chunk_start"], ref["chunk_len"], wl.blend_w, 64, seed=5, first_chunks=12)
+    idx = torch.from_numpy(rows).to(DEV)
+    want = O.linear(host(x[idx]), host(Wm), host(A), host(Bm), wl.ladder, wl.scales, wl.blend_w, so,
+                    ref["chunk_offsets"], ref["chunk_start"], ref["chunk_len"], ref["rank_idx"], rows=rows,
+                    x_compact=True)
+    assert rel_err(host(y[idx]), want) <= TOL_BF16
