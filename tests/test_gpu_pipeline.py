@@ -100,6 +100,9 @@ def test_cfg1_full_size_scoring_and_table():
     (8, 2048, 512, 1024, 0),      # persistent 256 x 256 kernel
     (2, 200, 256, 320, 0),        # few-row path (partial products + fix-up)
     (8, 2048, 512, 1024, 1),      # rows grouped by rank
+    (8, 2048, 512, 1024, 2),      # two-phase form: x A in the chunker's launch, gate + persistent kernel
+    (3, 700, 256, 512, 2),        # two-phase form: split shrink behind the chunker
+    (2, 200, 256, 320, 2),        # two-phase form on the few-row path (empty first phase)
 ])
 def test_whole_step_replays_from_a_hip_graph(n_seqs, seq_len, d_in, d_out, group_rows):
     """The four calls only enqueue kernels on the caller's stream: a whole step captured once must give, on every
@@ -131,8 +134,16 @@ def test_whole_step_replays_from_a_hip_graph(n_seqs, seq_len, d_in, d_out, group
     table = B.partition_chunks(B.score_tokens(logits, out=h), sod, 8, 64, theta, delta)
     ri = B.select_ranks(table, taus, 3)
 
+    two_phase = group_rows == 2          # (third setting of the parameter: the step in its two-phase form)
+    u = B.lora_shrink(x, packed, ranks, scales, 3) if two_phase else None
+
     def step():
         B.score_tokens(logits, out=h)
+        if two_phase:
+            B.schedule_chunks(h, sod, 8, 64, theta, delta, taus, 3, out=table, rank_idx=ri,
+                              shrink=(x, packed, ranks, scales, 3, u))
+            B.chunkwise_lora_linear_shrunk(x, packed, u, ranks, scales, 3, sod, table, ri, out=y, workspace=ws)
+            return
         B.partition_chunks(h, sod, 8, 64, theta, delta, out=table)
         B.select_ranks(table, taus, 3, out=ri)
         B.chunkwise_lora_linear(x, packed, None, None, ranks, scales, 3, sod, table, ri, out=y, group_rows=group_rows,
