@@ -336,7 +336,7 @@ def main():
     # the other form of the step, same region length, and its kernels (the one-call linear is what the
     # whole-call roofline figure is stated on)
     ms_calls, calls_ms = None, None
-    if two_phase:
+    if two_phase and not args.no_variants:
         for _ in range(args.warmup):
             step_calls()
         torch.cuda.synchronize()
@@ -418,19 +418,19 @@ def main():
                                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                                         "traffic": traffic.get("score"), "avg_launch_ms": kern_ms["score"],
                                         "bytes_per_launch": bytes_score}
-    if two_phase:
+    if calls_ms is not None:
         out["calls_form"] = {"note": "the same step as the four calls of the boundary one after the other "
                                      "(7 launches), same run", "ms_per_step": ms_calls,
                              "value": N / (ms_calls * 1e-3), "kernel_ms": calls_ms}
     lin_src = calls_ms if two_phase else kern_ms
-    lin_ms = sum(lin_src[k] or 0.0 for k in ("meta", "shrink", "main"))
+    lin_ms = sum(lin_src[k] or 0.0 for k in ("meta", "shrink", "main")) if lin_src is not None else 0.0
     if lin_ms and "roofline" in out and bf16:
         # the benchmark spec's target is stated for the whole call: gate table + shrink + main GEMM, priced with
         # the whole layer's algorithmic flops
         out["roofline"]["whole_call"] = {"kernels": "token_meta + shrink + main", "ms": lin_ms,
                                          "flops": flops_alg, "achieved": flops_alg / (lin_ms * 1e-3) / 1e12,
                                          "frac": flops_alg / (lin_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
-        if two_phase and kern_ms["meta"] and kern_ms["main"]:
+        if two_phase and calls_ms is not None and kern_ms["meta"] and kern_ms["main"]:
             ms2 = kern_ms["meta"] + kern_ms["main"]
             sched_alone = sum(calls_ms[k] or 0.0 for k in ("partition", "select"))
             out["roofline"]["two_phase"] = {
