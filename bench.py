@@ -525,7 +525,10 @@ def main():
             if n_p:
                 us_p = t_p / n_p * 1e3
                 us_f = t_f / n_f * 1e3 if n_f else 0.0
-                few[str(rows)] = {"products_us": us_p, "fixup_us": us_f, "launches": 2 if n_f else 1,
+                few[str(rows)] = {"path": ("one row: x A (+ gate entry) in a first launch ('fixup_us'), then every output column "
+                                           "as one dot product over [x | uhat] ('products_us')") if rows == 1 and d_in <= 8192
+                                  else "partial products over slices of d_in ('products_us') + fix-up kernel ('fixup_us')",
+                                  "products_us": us_p, "fixup_us": us_f, "launches": 2 if n_f else 1,
                                   "weight_stream_GBps": w_bytes / ((us_p + us_f) * 1e-6) / 1e9,
                                   "frac_of_hbm_peak": w_bytes / ((us_p + us_f) * 1e-6) / 1e9 / PEAK_HBM_GBS}
         # one decode step of the scheduler for 64 sequences (one thread per sequence: launch latency)
@@ -594,7 +597,7 @@ def main():
                 "projection_frac_of_hbm_peak": w_bytes / (us_proj * 1e-6) / 1e9 / PEAK_HBM_GBS}
         except RuntimeError as err:           # graph capture unavailable: report, do not fail the bench
             few["decode_step_graph_64_sequences"] = {"error": str(err)[:200]}
-        out["few_rows"] = {"note": "rows <= 512: partial products + fix-up kernel; weight bytes = 2 d_in (d_out + R), "
+        out["few_rows"] = {"note": "rows <= 512: two launches per call (see 'path'); weight bytes = 2 d_in (d_out + R), "
                                    "rate over both event-timed kernels (a few microseconds of launch gap included)",
                            "weight_bytes": w_bytes, **few}
 

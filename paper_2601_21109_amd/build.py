@@ -6,7 +6,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(_HERE), "include")
 LIB_PATH = os.path.join(_HERE, "libcwl.so")
-SOURCES = ["score_tokens.hip", "compose.hip", "partition.hip", "align.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "linear.hip", "linear_small.hip", "stream.hip", "ladder.hip", "kv_cache.hip", "profile.hip"]
+SOURCES = ["score_tokens.hip", "compose.hip", "partition.hip", "align.hip", "gemm_f32.hip", "gemm_bf16.hip", "gemm_bf16_main.hip", "linear.hip", "linear_small.hip", "linear_gemv.hip", "stream.hip", "ladder.hip", "kv_cache.hip", "profile.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 code

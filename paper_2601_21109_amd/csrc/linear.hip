@@ -618,7 +618,11 @@ WsLayout ws_layout(const cwl_linear_desc* d, int32_t n_proj = 1) {
     L.perm = off; off = align_up(off + sizeof(int32_t) * (n + 1), 256);
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
     L.partial = off;
-    if (small_rows_path(d, packed_layout(d, n_proj))) off = align_up(off + small_rows_plan(d, n_proj).partial_bytes, 256);
+    if (small_rows_path(d, packed_layout(d, n_proj))) {
+        // (the path for a handful of rows keeps x A there: at most 8 rows x 256 directions of fp32)
+        const size_t pb = small_rows_plan(d, n_proj).partial_bytes;
+        off = align_up(off + (pb > 8192 ? pb : 8192), 256);
+    }
     else if (n_proj == 1 && shrink_split_plan(d).splits >= 2) off = align_up(off + shrink_split_plan(d).partial_bytes, 256);
     L.total = off;
     return L;
@@ -728,6 +732,10 @@ cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void
     const int32_t n_proj = grp.n_proj;
     const PackedLayout P = packed_layout(d, n_proj);
     const WsLayout L = ws_layout(d, n_proj);
+    if (n_proj == 1 && small_rows_path(d, P) && gemv_rows_serves(d))
+        return run_gemv_rows(d, x, packed + P.wt, packed + P.at, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
+                             chunk_start, chunk_len, rank_idx, chunk_cap, gate, y,
+                             reinterpret_cast<float*>(ws + L.partial), reinterpret_cast<TokMeta*>(ws + L.meta), st);
     if (small_rows_path(d, P))
         return run_small_rows(d, grp, x, packed + P.wt, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
                               chunk_start, chunk_len, rank_idx, chunk_cap, y,

@@ -131,12 +131,34 @@ def test_bf16_few_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
     assert torch.equal(y, y2)                         # slice sums in a fixed order
 
 
+@pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [2], 4096, 4096, [8, 16, 32, 64], 4),          # two rows of one sequence at the 7B shape
+    (2, [2, 1], 4096, 11008, [8, 16, 32, 64], 4),      # three rows, wide output (1376 workgroups)
+    (1, [3], 11008, 4096, [8, 16, 32, 64], 4),         # three rows of the long reduction: 66 KB of x in LDS
+    (1, [4], 11008, 136, [8, 64], 2),                  # four rows of it no longer fit: the split-reduction path
+    (2, [3, 2], 8192, 264, [0, 24, 100], 3),           # five rows pad to eight: 128 KB of x, split-reduction path
+    (3, [4, 1, 2], 2048, 1032, [4, 8, 200], 3),        # seven rows, padded rank 256, joins with a cross-fade inside
+    (1, [8], 4096, 4096, [8, 16, 32, 64], 4),          # eight rows of one sequence: two chunks, a join
+    (8, [1] * 8, 1344, 8, [16], 0),                    # reduction not a multiple of 512 elements, one column block
+])
+@pytest.mark.parametrize("packed", [True, False])
+def test_bf16_a_handful_of_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
+    """At most eight rows: matrix-vector products on the vector ALUs (x A first, then every output column as
+    one dot product over [x | uhat]) where x fits the kernel's LDS, else the split-reduction path."""
+    yh, ref, y = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 31, l_min=2, l_max=5,
+                          packed=packed)
+    assert rel_err(yh, ref) <= TOL_BF16
+    _, _, y2 = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 31, l_min=2, l_max=5,
+                        packed=packed)
+    assert torch.equal(y, y2)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_bf16_random_shapes_across_the_launch_plans(seed):
     """Random shapes around the switch points of the launch plan (512 rows, 64 / 128 tiles of 256 x 256,
     slice counts), random ladders and joins, against the oracle."""
     rng = np.random.RandomState(1000 + seed)
-    n = int(rng.choice([1, 2, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700, 1100]))
+    n = int(rng.choice([1, 2, 3, 5, 8, 9, 15, 16, 17, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513, 700, 1100]))
     d_in = 64 * int(rng.randint(1, 13))
     d_out = 8 * int(rng.randint(1, 90))
     K = int(rng.randint(1, 5))
