@@ -732,8 +732,8 @@ cwl_status run_packed(const cwl_linear_desc* d, const GroupCols& grp, const void
     const int32_t n_proj = grp.n_proj;
     const PackedLayout P = packed_layout(d, n_proj);
     const WsLayout L = ws_layout(d, n_proj);
-    if (n_proj == 1 && small_rows_path(d, P) && gemv_rows_serves(d))
-        return run_gemv_rows(d, x, packed + P.wt, packed + P.at, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
+    if (small_rows_path(d, P) && gemv_rows_serves(d))
+        return run_gemv_rows(d, grp, x, packed + P.wt, packed + P.at, packed + P.bt, seq_offsets, n_seqs, chunk_offsets,
                              chunk_start, chunk_len, rank_idx, chunk_cap, gate, y,
                              reinterpret_cast<float*>(ws + L.partial), reinterpret_cast<TokMeta*>(ws + L.meta), st);
     if (small_rows_path(d, P))

@@ -127,11 +127,11 @@ cwl_status run_small_rows(const cwl_linear_desc* d, const GroupCols& grp, const 
                           const int32_t* rank_idx, int32_t chunk_cap, void* y, float* partial, TokMeta* meta,
                           const TokMeta* gate, hipStream_t st);   // gate != NULL: use these entries, leave the chunk table alone
 
-// ---- a handful of rows (linear_gemv.hip): bf16, token order, one projection ----
+// ---- one row (linear_gemv.hip): bf16, token order, a projection or a group of them ----
 bool gemv_rows_serves(const cwl_linear_desc* d);
-// wt / at / bt: W^T, A^T, B^T of the packed weights; u: n_rows x padded-rank floats of scratch; meta: n_rows
-// entries of scratch, filled from the chunk table when gate is NULL
-cwl_status run_gemv_rows(const cwl_linear_desc* d, const void* x, const void* wt, const void* at, const void* bt,
+// wt / at / bt: W^T, A^T, B^T of the packed weights; u: (projections x padded rank) floats of scratch; meta: one
+// entry of scratch, filled from the chunk table when gate is NULL
+cwl_status run_gemv_rows(const cwl_linear_desc* d, const GroupCols& grp, const void* x, const void* wt, const void* at, const void* bt,
                          const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                          const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
                          int32_t chunk_cap, const TokMeta* gate, void* y, float* u, TokMeta* meta, hipStream_t st);

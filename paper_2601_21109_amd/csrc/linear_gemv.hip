@@ -31,8 +31,10 @@ struct GemvArgs {
     const uint16_t* Wt;     // [N, K]: row n holds output column n, K-contiguous
     int64_t K, N;
     // second launch only (ADAPTER):
-    const float* u;         // [R] x A, fp32
+    const float* u;         // [n_proj R] x A of every adapter, fp32
     int32_t R;
+    int32_t n_proj;         // projections side by side: columns [col0[p], col0[p + 1]) use directions [p R, p R + R)
+    int64_t col0[kMaxGroup];
     const uint16_t* Bt;     // [N, R]
     const TokMeta* gate;    // the row's gate entry
     uint16_t* y;            // [N] bf16
@@ -98,8 +100,13 @@ __global__ void __launch_bounds__(kThreads) gemv_row_kernel(GemvArgs a) {
 #pragma unroll
         for (int c = 0; c < kColsPerWave; ++c) bv[c] = u32x4{0u, 0u, 0u, 0u};
         if (lora_lane) {
-            ua = *reinterpret_cast<const f32x4*>(a.u + i0);
-            ub = *reinterpret_cast<const f32x4*>(a.u + i0 + 4);
+            // the workgroup's eight columns belong to one projection (column counts are multiples of eight)
+            int proj = 0;
+            for (int q = 1; q < a.n_proj; ++q)
+                if (j0 >= a.col0[q]) proj = q;
+            const float* up = a.u + (int64_t)proj * a.R + i0;
+            ua = *reinterpret_cast<const f32x4*>(up);
+            ub = *reinterpret_cast<const f32x4*>(up + 4);
 #pragma unroll
             for (int c = 0; c < kColsPerWave; ++c) {
                 int64_t j = j0 + c;
@@ -226,9 +233,10 @@ bool gemv_rows_serves(const cwl_linear_desc* d) {
     return d->d_in % 8 == 0 && d->d_out % 8 == 0 && d->d_in <= 8192;
 }
 
-// wt / at / bt: W^T [d_out, d_in], A^T [R, d_in], B^T [d_out, R] of the packed weights; u: R floats of scratch;
+// wt / at / bt: W^T [d_out, d_in], A^T [n_proj R, d_in], B^T [d_out, R] of the packed weights (d_out: the columns
+// of all projections of the group); u: n_proj R floats of scratch;
 // meta: one gate entry of scratch (used when `gate` is NULL: then the chunk table is looked up)
-cwl_status run_gemv_rows(const cwl_linear_desc* d, const void* x, const void* wt, const void* at, const void* bt,
+cwl_status run_gemv_rows(const cwl_linear_desc* d, const GroupCols& grp, const void* x, const void* wt, const void* at, const void* bt,
                          const int32_t* seq_offsets, int32_t n_seqs, const int32_t* chunk_offsets,
                          const int32_t* chunk_start, const int32_t* chunk_len, const int32_t* rank_idx,
                          int32_t chunk_cap, const TokMeta* gate, void* y, float* u, TokMeta* meta, hipStream_t st) {
@@ -237,7 +245,7 @@ cwl_status run_gemv_rows(const cwl_linear_desc* d, const void* x, const void* wt
     a1.x = static_cast<const uint16_t*>(x);
     a1.Wt = static_cast<const uint16_t*>(at);
     a1.K = d->d_in;
-    a1.N = R;
+    a1.N = (int64_t)grp.n_proj * R;
     a1.R = R;
     a1.out32 = u;
     if (!gate) {
@@ -268,6 +276,8 @@ cwl_status run_gemv_rows(const cwl_linear_desc* d, const void* x, const void* wt
     a2.N = d->d_out;
     a2.u = u;
     a2.R = R;
+    a2.n_proj = grp.n_proj;
+    for (int32_t q = 0; q < grp.n_proj; ++q) a2.col0[q] = grp.col0[q];
     a2.Bt = static_cast<const uint16_t*>(bt);
     a2.gate = gate ? gate : meta;
     a2.y = static_cast<uint16_t*>(y);

@@ -153,11 +153,12 @@ def test_decode_steps_end_to_end():
     assert ost.chunks.sum() > 0
 
 
-def test_decode_step_replays_from_a_hip_graph():
+@pytest.mark.parametrize("n_seqs", [8, 1])        # one sequence: the projections run as matrix-vector products
+def test_decode_step_replays_from_a_hip_graph(n_seqs):
     """The calls only enqueue kernels on the caller's stream, so a decode step (scores, scheduler step,
     two projections) can be captured once and replayed.  Every replay, with eager work and
     synchronisations in between, must equal the eager result for the same inputs and state."""
-    n_seqs, vocab, d_in, d_out, r_max = 8, 1500, 256, 320, 16
+    vocab, d_in, d_out, r_max = 1500, 256, 320, 16
     ranks, scales = [4, 8, 16], [4.0, 2.0, 1.0]
     lnv = math.log(vocab)
     args = (2, 4, 0.9 * lnv, 0.3 * lnv, [0.45 * lnv, 0.9 * lnv], ranks, scales, 2)
