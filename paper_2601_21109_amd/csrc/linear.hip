@@ -619,9 +619,10 @@ WsLayout ws_layout(const cwl_linear_desc* d, int32_t n_proj = 1) {
     L.uhat = off; off = align_up(off + es * (n + 1) * R, 256);
     L.partial = off;
     if (small_rows_path(d, packed_layout(d, n_proj))) {
-        // (the path for a handful of rows keeps x A there: at most 8 rows x 256 directions of fp32)
+        // (the one-row path keeps x A there, fp32, every adapter's padded directions: at most 8 KiB)
         const size_t pb = small_rows_plan(d, n_proj).partial_bytes;
-        off = align_up(off + (pb > 8192 ? pb : 8192), 256);
+        const size_t ub = sizeof(float) * (size_t)n_proj * (size_t)padded_rank(d->r_max);
+        off = align_up(off + (pb > ub ? pb : ub), 256);
     }
     else if (n_proj == 1 && shrink_split_plan(d).splits >= 2) off = align_up(off + shrink_split_plan(d).partial_bytes, 256);
     L.total = off;

@@ -223,9 +223,12 @@ cwl_status launch_gemv_row(const GemvArgs& a, hipStream_t st) {
 
 }  // namespace
 
-// bf16, token order, one projection, ONE row.  More rows lose to the matrix cores: from a HIP graph on
-// 4096 -> 4096 a form of this kernel with x staged in LDS took 15.1 / 18.5 / 26.6 us for 2 / 4 / 8 rows against
-// 14.9 us for the split-reduction path (v_dot2_f32_bf16 issues at about a quarter of the vector rate).
+// bf16, token order, ONE row.  More rows stay with the split-reduction path (14.2 to 15.8 us for 2 to 16 rows of
+// 4096 -> 4096 from a HIP graph): a form of this kernel with x staged in LDS took 15.1 / 18.5 / 26.6 us for 2 / 4 /
+// 8 rows (v_dot2_f32_bf16 issues at about a quarter of the vector rate), and the same walk on the matrix cores
+// (v_mfma_f32_4x4x4_16b_bf16, block b of a 128-element k-step on elements [8 b, 8 b + 8), so that a column's
+// lanes read 256 contiguous bytes) 15.9 / 16.9 / 21.4 / 39.6 us for 2 / 4 / 8 / 16 rows: every further row of x
+// costs about half a microsecond of loads there.
 // A reduction of more than 8192 elements stays with the split path too: a wavefront walks its rows of W^T
 // (and, in the first launch, of A^T) from end to end, 11008 -> 4096 took 24.4 us here against 22.7 us there.
 bool gemv_rows_serves(const cwl_linear_desc* d) {

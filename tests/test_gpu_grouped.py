@@ -41,6 +41,8 @@ def check_against_oracle(y, pg, x, Ws, As, Bs, ranks, scales, blend_w, table, ro
     ([300, 100], 256, [256, 512], [4, 8, 16, 32, 64, 128], 4, torch.bfloat16, TOL_BF16),   # few-row path, rank 128 x 2
     ([1], 1024, [1024, 1024, 1024], [8, 16, 32, 64], 4, torch.bfloat16, TOL_BF16),         # one decode row
     ([1], 4096, [264, 8, 4096, 72], [0, 24, 100], 0, torch.bfloat16, TOL_BF16),            # one row, four projections, padded rank 128
+    ([3, 2], 1024, [264, 8, 72], [0, 24, 100], 2, torch.bfloat16, TOL_BF16),               # five rows, three projections whose columns are not multiples of 16
+    ([7, 6], 11008, [136, 520], [8, 16, 32, 64], 4, torch.bfloat16, TOL_BF16),             # thirteen rows, long reduction
     ([700, 500], 256, [520, 264], [0, 24, 100], 3, torch.bfloat16, TOL_BF16),              # mid-size tiles, padded rank 128
     ([2100, 900], 192, [1032, 512, 2056], [8, 16, 32, 64], 4, torch.bfloat16, TOL_BF16),   # persistent kernel per projection
     ([900, 400], 128, [256, 264, 8, 64, 72], [200], 2, torch.bfloat16, TOL_BF16),          # five adapters of 256 padded directions: five shrink passes

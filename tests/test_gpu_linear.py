@@ -132,19 +132,19 @@ def test_bf16_few_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
 
 
 @pytest.mark.parametrize("n_seqs,seq_lens,d_in,d_out,ranks,w", [
+    (1, [1], 4096, 11008, [8, 16, 32, 64], 4),         # one row, wide output (1376 workgroups)
+    (1, [1], 8192, 264, [0, 24, 100], 3),              # one row, the longest reduction of the one-row path, padded rank 128
+    (1, [1], 11008, 4096, [8, 16, 32, 64], 4),         # one row of a longer reduction: the split-reduction path
+    (1, [1], 1344, 8, [200], 0),                       # reduction not a multiple of 512 elements, one column block, padded rank 256
     (1, [2], 4096, 4096, [8, 16, 32, 64], 4),          # two rows of one sequence at the 7B shape
-    (2, [2, 1], 4096, 11008, [8, 16, 32, 64], 4),      # three rows, wide output (1376 workgroups)
-    (1, [3], 11008, 4096, [8, 16, 32, 64], 4),         # three rows of the long reduction: 66 KB of x in LDS
-    (1, [4], 11008, 136, [8, 64], 2),                  # four rows of it no longer fit: the split-reduction path
-    (2, [3, 2], 8192, 264, [0, 24, 100], 3),           # five rows pad to eight: 128 KB of x, split-reduction path
+    (2, [2, 1], 4096, 11008, [8, 16, 32, 64], 4),      # three rows, wide output
     (3, [4, 1, 2], 2048, 1032, [4, 8, 200], 3),        # seven rows, padded rank 256, joins with a cross-fade inside
     (1, [8], 4096, 4096, [8, 16, 32, 64], 4),          # eight rows of one sequence: two chunks, a join
-    (8, [1] * 8, 1344, 8, [16], 0),                    # reduction not a multiple of 512 elements, one column block
 ])
 @pytest.mark.parametrize("packed", [True, False])
 def test_bf16_a_handful_of_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
-    """At most eight rows: matrix-vector products on the vector ALUs (x A first, then every output column as
-    one dot product over [x | uhat]) where x fits the kernel's LDS, else the split-reduction path."""
+    """A handful of rows around the one-row path (x A first, then every output column as one dot product over
+    [x | uhat] on the vector ALUs; from two rows up, and for reductions beyond 8192 elements, the split-reduction path)."""
     yh, ref, y = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 31, l_min=2, l_max=5,
                           packed=packed)
     assert rel_err(yh, ref) <= TOL_BF16
