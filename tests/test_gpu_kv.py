@@ -154,3 +154,28 @@ def test_argument_errors():
     with pytest.raises(B.CwlError) as e:
         B.kv_quantise_chunks(kv, 1, 128, -1, tab, rid)
     assert e.value.status == B.ERR_INVALID_ARG
+
+
+def test_degenerate_tables():
+    """No rows; no chunks (every row absent); a table whose capacity cuts the chunk list short."""
+    H, D = 2, 64
+    kv0 = torch.empty((0, H * D), dtype=torch.bfloat16, device=DEV)
+    sod, tab, rid = B.table_from_host(np.array([0, 0], np.int32), np.array([0, 0], np.int32), np.zeros(0, np.int32),
+                                      np.zeros(0, np.int32), np.zeros(0, np.int32), DEV)
+    c0 = B.kv_quantise_chunks(kv0, H, D, 1, tab, rid)
+    torch.cuda.synchronize()
+    assert c0["counts"].cpu().tolist() == [0, 0] and int(c0["status_word"].item()) == 0
+    kv = make_kv(50, H * D, 1)
+    c1 = B.kv_quantise_chunks(kv, H, D, 1, tab, rid)
+    back = B.kv_dequantise(c1, 50)
+    torch.cuda.synchronize()
+    assert np.all(c1["slot"].cpu().numpy()[:50] == B.KV_SLOT_ABSENT) and float(back.float().abs().max()) == 0.0
+    # five chunks listed, the table holds three: rows of the last two are not cached
+    so, co = np.array([0, 50], np.int32), np.array([0, 5], np.int32)
+    cs, cl, ri = np.arange(0, 50, 10, dtype=np.int32), np.full(5, 10, np.int32), np.array([0, 1, 0, 1, 0], np.int32)
+    sod, tab, rid = B.table_from_host(so, co, cs[:3], cl[:3], ri[:3], DEV)
+    c2 = B.kv_quantise_chunks(kv, H, D, 1, tab, rid)
+    torch.cuda.synchronize()
+    ref = O.kv_quantise(host(kv), H, D, cs[:3], cl[:3], ri[:3], 1)
+    assert c2["slot"].cpu().numpy()[:50].tolist() == ref["slot"].tolist()
+    assert c2["counts"].cpu().tolist() == [20, 10]

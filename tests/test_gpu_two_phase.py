@@ -236,3 +236,31 @@ def test_schedule_with_shrink_repeats():
         torch.cuda.synchronize()
         _tables_equal(t1, r1, tab, ri)
         assert same_bits(host(y1), host(y2))
+
+
+def test_schedule_degenerate_batches():
+    """No sequences, empty sequences, and a first phase on other rows than the scheduler's: the calls return the
+    same tables as the separate calls and leave the product alone where there is none to make."""
+    wl = W.WORKLOADS["cfg1"]
+    h0 = torch.empty(0, dtype=torch.float32, device=DEV)
+    so0 = torch.zeros(1, dtype=torch.int32, device=DEV)
+    t, r = B.schedule_chunks(h0, so0, 4, 8, wl.theta(), wl.delta(), wl.taus(), 4)
+    torch.cuda.synchronize()
+    assert t["chunk_offsets"].cpu().tolist() == [0] and int(t["status_word"].item()) == 0
+    # three sequences, the middle one empty; the product belongs to a batch of another size (20000 rows)
+    seq_lens = [700, 0, 300]
+    g = torch.Generator(device=DEV).manual_seed(5)
+    h = (torch.rand(1000, generator=g, device=DEV) * math.log(wl.vocab)).float()
+    so = torch.tensor([0, 700, 700, 1000], dtype=torch.int32, device=DEV)
+    x, Wm, A, Bm = operands(20000, 128, 64, 64, torch.bfloat16, 7)
+    pw = B.prepack_weights(Wm, A, Bm)
+    ranks, scales = [8, 16, 32, 64], [2.0, 1.0, 0.5, 0.25]
+    u1 = B.lora_shrink(x, pw, ranks, scales, 2)
+    u2 = torch.zeros_like(u1)
+    t2, r2 = B.schedule_chunks(h, so, 4, 40, wl.theta(), wl.delta(), wl.taus(), 4, shrink=(x, pw, ranks, scales, 2, u2))
+    t1 = B.partition_chunks(h, so, 4, 40, wl.theta(), wl.delta())
+    r1 = B.select_ranks(t1, wl.taus(), 4)
+    torch.cuda.synchronize()
+    _tables_equal(t1, r1, t2, r2)
+    assert torch.equal(u1, u2)
+    assert t2["chunk_offsets"].cpu().tolist()[1] == t2["chunk_offsets"].cpu().tolist()[2]      # the empty sequence has no chunk
