@@ -228,7 +228,12 @@ cwl_status launch_gemv_row(const GemvArgs& a, hipStream_t st) {
 // 8 rows (v_dot2_f32_bf16 issues at about a quarter of the vector rate), and the same walk on the matrix cores
 // (v_mfma_f32_4x4x4_16b_bf16, block b of a 128-element k-step on elements [8 b, 8 b + 8), so that a column's
 // lanes read 256 contiguous bytes) 15.9 / 16.9 / 21.4 / 39.6 us for 2 / 4 / 8 / 16 rows: every further row of x
-// costs about half a microsecond of loads there.
+// costs about half a microsecond of loads there.  A third form took 16 rows per instruction
+// (v_mfma_f32_16x16x32_bf16, a workgroup per 16 output columns, its four wavefronts a quarter of d_in each, both
+// fragments straight from memory in the instruction's layout with every load issued before the first product):
+// 16.1 / 16.7 / 17.9 / 20.3 us for 2 / 4 / 8 / 16 rows (kernels: x A 7.2 to 10.0 us on its four workgroups next
+// to the gate look-ups, the layer 8.4 to 10.7 us against 6.4 us for one row here): a fragment load touches 16 rows
+// of W^T with 64 bytes each where this kernel's loads are 1 KiB of one row, and every wavefront re-reads x.
 // A reduction of more than 8192 elements stays with the split path too: a wavefront walks its rows of W^T
 // (and, in the first launch, of A^T) from end to end, 11008 -> 4096 took 24.4 us here against 22.7 us there.
 bool gemv_rows_serves(const cwl_linear_desc* d) {
