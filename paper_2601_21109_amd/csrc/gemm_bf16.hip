@@ -51,7 +51,7 @@ __device__ __forceinline__ void gemm_bf16_tn_body(const GemmArgs& a, const int v
     constexpr int N_DS = MI + NI, N_MFMA = MI * NI;
     static_assert(ROWS % (RPI * NW) == 0 && BM % RPI == 0, "tile rows must split evenly over the waves");
     static_assert(BM % 16 == 0 && BN % 16 == 0 && TM % 32 == 0 && TN % 32 == 0, "tile shape");
-    static_assert(BM % kRankBlock == 0, "row tile must cover whole rank blocks");
+    static_assert(EPI == EPI_PARTIAL || BM % kRankBlock == 0, "row tile must cover whole rank blocks");
     static_assert(NST >= 2 && (NST - 1) * LOADS < 64, "ring depth");
 
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -506,11 +506,12 @@ cwl_status launch_seq_shrink_raw_bf16(const part::SeqJob& job, const GemmArgs& a
     return CWL_ERR_UNSUPPORTED;
 }
 
-// fp32 partial products over slices of the reduction dimension, for a few hundred rows: tiles of 64
-// columns, rings shallow enough for two workgroups per compute unit (the launch is bound by how
-// many bytes of the weight matrix are in flight).
+// fp32 partial products over slices of the reduction dimension, for a few hundred rows at most: the
+// tile shape comes with the plan (small_rows_plan), the rings are shallow enough for two or three
+// workgroups per compute unit.
 cwl_status launch_partial_bf16(const GemmArgs& a, const MetaJob& job, hipStream_t st) {
     if (a.M_tile == 256) return launch_partial_cfg<256, 128, 2, 2, 3>(a, job, st);
+    if (a.M_tile == 32) return launch_partial_cfg<32, 128, 1, 4, 3>(a, job, st);
     if (a.M <= 64 && a.three_per_cu) return launch_partial_cfg<64, 64, 2, 2, 3>(a, job, st);
     if (a.M <= 64) return launch_partial_cfg<64, 64, 2, 2, 4>(a, job, st);
     if (a.N_tile == 64 && a.three_per_cu) return launch_partial_cfg<128, 64, 2, 2, 2>(a, job, st);

@@ -4,8 +4,8 @@
 // output tiles alone is far too small to have enough bytes in flight.  Two launches:
 //   1. Partial products and gate table.  W^T and A^T lie back to back in the packed weights, so
 //      P = x . [W | A] is one product with d_out + R output columns.  It is cut into tiles of 64
-//      columns and into slices of the reduction dimension, one workgroup each (several hundred
-//      in all), every one leaving an fp32 tile in the workspace (the matrix-core kernel of
+//      or 128 columns and into slices of the reduction dimension, one workgroup each (several
+//      hundred in all, small_rows_plan), every one leaving an fp32 tile in the workspace (the matrix-core kernel of
 //      gemm_bf16.hip with the EPI_PARTIAL epilogue).  One or two more workgroups of the same
 //      launch look up the rows' gate entries (token_meta.h): a chain of dependent loads that
 //      takes as long as the products.
@@ -180,6 +180,24 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d, int32_t n_proj) {
     }
     p.m_tile = (int32_t)bm;
     const int64_t stages = d->d_in / 64;
+    if (d->n_rows <= 16 && (n_cols + 127) / 128 <= 64 && stages >= 8 && stages <= 64) {
+        // Up to 16 rows, up to 8192 columns, d_in up to 4096: tiles of 32 rows x 128 columns in 8 slices.  Every column tile re-reads
+        // its slice of x, and what bounds the launch is the bytes that go into LDS: with 128 columns per tile x is
+        // a fifth of them instead of half.  Whole calls from a HIP graph, 4096 -> 4096: 12.0 / 13.0 / 14.5 us for
+        // 2 / 8 / 16 rows against 13.7 / 14.4 / 15.4 us with 64 x 64 tiles in 4 slices (4 slices of the wide tiles:
+        // 15.2 / 17.8 / 18.7 us, 15 slices: 13.8 / 15.4 / 17.7 us); 4096 -> 6144: 16.4 / 18.8 against 17.5 / 19.0 us
+        // for 2 / 16 rows; at 32 rows the two are level.  Longer reductions stay with the 64 x 64 tiles: 8192 -> 4096
+        // is level (19.1 / 21.8 against 18.7 / 21.2 us; 12 slices 17.2 / 21.2), 11008 -> 4096 slower with 8, 12 or 15
+        // slices (25.7, 24.7, 23.0 us against 22.5 us for 2 rows; 28.4, 28.5, 27.0 against 25.1 us for 16).
+        p.n_tile = 128;
+        p.m_tile = 32;
+        p.ks_per_split = (int32_t)((stages + 7) / 8);
+        p.splits = (int32_t)((stages + p.ks_per_split - 1) / p.ks_per_split);
+        p.ldp = n_cols;
+        p.partial_stride = d->n_rows * n_cols;
+        p.partial_bytes = sizeof(float) * (size_t)p.splits * (size_t)p.partial_stride;
+        return p;
+    }
     int64_t s = (p.n_tile == 64 ? 512 : 256) / tiles;   // what fits at once: two (one) workgroups per compute unit
     if (p.n_tile == 64 && s < 3) {
         // wide outputs leave room for one or two slices only (173 tiles of 4096 -> 11008: 346 workgroups on 256

@@ -140,11 +140,15 @@ def test_bf16_few_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
     (2, [2, 1], 4096, 11008, [8, 16, 32, 64], 4),      # three rows, wide output
     (3, [4, 1, 2], 2048, 1032, [4, 8, 200], 3),        # seven rows, padded rank 256, joins with a cross-fade inside
     (1, [8], 4096, 4096, [8, 16, 32, 64], 4),          # eight rows of one sequence: two chunks, a join
+    (2, [9, 7], 4096, 4096, [8, 16, 32, 64], 4),       # 16 rows: the last count on 32 x 128 partial-product tiles
+    (2, [9, 8], 4096, 4096, [8, 16, 32, 64], 4),       # 17 rows: back on 64 x 64 tiles
+    (1, [16], 4096, 8320, [8, 16, 32, 64], 4),         # 16 rows, 66 column tiles of 128: 64 x 64 tiles
 ])
 @pytest.mark.parametrize("packed", [True, False])
 def test_bf16_a_handful_of_rows(n_seqs, seq_lens, d_in, d_out, ranks, w, packed):
     """A handful of rows around the one-row path (x A first, then every output column as one dot product over
-    [x | uhat] on the vector ALUs; from two rows up, and for reductions beyond 8192 elements, the split-reduction path)."""
+    [x | uhat] on the vector ALUs; from two rows up, and for reductions beyond 8192 elements, the split-reduction path,
+    with tiles of 32 rows x 128 columns up to 16 rows, 8192 columns and a reduction of 4096 elements)."""
     yh, ref, y = run_case(n_seqs, seq_lens, d_in, d_out, ranks, w, torch.bfloat16, 31, l_min=2, l_max=5,
                           packed=packed)
     assert rel_err(yh, ref) <= TOL_BF16
