@@ -189,6 +189,8 @@ SmallPlan small_rows_plan(const cwl_linear_desc* d, int32_t n_proj) {
         // for 2 / 16 rows; at 32 rows the two are level.  Longer reductions stay with the 64 x 64 tiles: 8192 -> 4096
         // is level (19.1 / 21.8 against 18.7 / 21.2 us; 12 slices 17.2 / 21.2), 11008 -> 4096 slower with 8, 12 or 15
         // slices (25.7, 24.7, 23.0 us against 22.5 us for 2 rows; 28.4, 28.5, 27.0 against 25.1 us for 16).
+        // For 17 to 64 rows tiles of 64 rows x 128 columns gave nothing (6 slices: 15.2 / 15.8 / 17.0 us for 17 / 32 /
+        // 64 rows against 15.3 / 16.1 / 17.6 us; 8 slices and 4096 -> 6144 slower).
         p.n_tile = 128;
         p.m_tile = 32;
         p.ks_per_split = (int32_t)((stages + 7) / 8);
