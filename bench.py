@@ -528,7 +528,7 @@ def main():
             torch.cuda.synchronize()
             return e0.elapsed_time(e1) / (args.steps * reps) * 1e3
 
-        for rows in (1, 64, 512):
+        for rows in (1, 8, 64, 512):
             tb = W.random_chunk_table(1, [rows], min(wl.l_min, rows), max(min(wl.l_max, rows), 1), K, 11)
             sod_f, tab_f, rid_f = B.table_from_host(*tb, dev)
             ws_f = B.linear_workspace((rows, d_in), wl.dtype, d_out, wl.r_max, wl.ladder, wl.scales,
