@@ -175,6 +175,24 @@ def other_workload(name, steps, warmup):
             "main_ms": main_ms, "main_frac_of_bf16_peak": fl_main / (main_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         fl_all += fl_call
         ms_all += call_ms
+    # the first projection at fixed r_max (one rung, every chunk on it) next to its chunk-wise call, in
+    # interleaved blocks so that clock drift hits both alike
+    pr0 = projs[0]
+    zero_idx = torch.zeros(max(n_chunks, 1), dtype=torch.int32, device=dev)
+
+    def linear_fixed():
+        B.chunkwise_lora_linear(pr0[3], pr0[4], None, None, [wl.r_max], [wl.alpha / wl.r_max], wl.blend_w, sod, table,
+                                zero_idx, out=pr0[5], workspace=pr0[6])
+    linear_fixed()
+    torch.cuda.synchronize()
+    t_cw = t_fx = 0.0
+    n_blk = max(steps // 2, 2)
+    for _ in range(3):
+        t_cw += timed(lambda: linear(pr0), n_blk)
+        t_fx += timed(linear_fixed, n_blk)
+    fixed = {"projection": pr0[0], "chunkwise_ms": t_cw / 3, "fixed_r_max_ms": t_fx / 3,
+             "speedup_vs_fixed_r_max": t_fx / t_cw,
+             "adapter_stage_share_of_main": ((wl.r_max + 63) // 64 * 64) / (pr0[1] + (wl.r_max + 63) // 64 * 64)}
     # the projections that read the same activations (q/k/v; gate/up) as grouped calls: one gate table and one
     # shrink pass over x per group, every projection still on its own rungs
     grouped = None
@@ -225,7 +243,8 @@ def other_workload(name, steps, warmup):
            "score": {"ms_per_launch": score_ms, "launches_per_step": n_tiles, "GBps": score_gbs,
                      "frac_of_hbm_peak": score_gbs / PEAK_HBM_GBS},
            "linear_calls": calls,
-           "all_calls_frac_of_bf16_peak": fl_all / (ms_all * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+           "all_calls_frac_of_bf16_peak": fl_all / (ms_all * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "first_projection_vs_fixed_r_max": fixed}
     if grouped:
         out["with_grouped_calls"] = grouped
     del projs, logits
