@@ -693,6 +693,11 @@ def main():
         bk = B.bucket_sequences(h, sod, n_b, 2)
         tab_a = B.partition_chunks_aligned(h, sod, bk["bucket"], n_b, wl.l_min, wl.l_max, wl.theta(), wl.delta())
         ri_b, asked = B.select_ranks_budget(table, wl.taus(), K, K - 1, 4)
+        # composite score: entropy + 3-gram novelty in a window of 256 tokens + positional prior over 512 positions
+        gt = torch.Generator(device=dev)
+        gt.manual_seed(5)
+        tok = torch.randint(0, 8, (N,), generator=gt, device=dev, dtype=torch.int32)    # small alphabet: n-grams do repeat
+        sc_c, nov_c = B.compose_scores(h, tok, sod, 3, 256, 1.0, 0.5, 0.25, 512.0)
         torch.cuda.synchronize()
         reps = max(args.steps, 10)
         us = lambda fn: timed(fn, reps, 3)[0] * 1e3
@@ -707,6 +712,9 @@ def main():
             "select_ranks_us": us(lambda: B.select_ranks(table, wl.taus(), K, out=ri)),
             "select_ranks_budget_us": us(lambda: B.select_ranks_budget(table, wl.taus(), K, K - 1, 4, out=ri_b,
                                                                        n_asked=asked)),
+            "compose_scores_us": us(lambda: B.compose_scores(h, tok, sod, 3, 256, 1.0, 0.5, 0.25, 512.0, out=sc_c,
+                                                             novelty=nov_c)),
+            "compose_scores_new_ngrams": float(nov_c.float().mean().item()),
             "stream_step_aligned_us_64_sequences": None,
             "chunks_plain": int(table["chunk_offsets"][-1].item()),
             "chunks_aligned": int(tab_a["chunk_offsets"][-1].item()),
