@@ -3,6 +3,8 @@
 // INT8 with one fp32 scale per row and head, rows of the other chunks at full fidelity, in two pools.
 // Streaming work, bound by reading the cache rows once from HBM.
 //
+//   kv_plan_slot_kernel  tables of up to 4096 chunks: the two kernels below in one launch (every workgroup
+//                        scans the chunk list itself and keeps it in LDS)
 //   kv_plan_kernel       one workgroup: per chunk its policy and its first row in its pool (two
 //                        exclusive scans over the chunk lengths, in table order), the pool totals
 //   kv_slot_kernel       one thread per row: the row's chunk (binary search in the ascending chunk
@@ -38,8 +40,8 @@ struct KvShape {
 __global__ void __launch_bounds__(kPlanThreads)
 kv_plan_kernel(const int32_t* __restrict__ chunk_offsets, int32_t n_seqs, const int32_t* __restrict__ chunk_len,
                const int32_t* __restrict__ rank_idx, int32_t chunk_cap, int32_t k_keep,
-               int32_t* __restrict__ chunk_slot, int32_t* __restrict__ n_chunks_out, int32_t* __restrict__ counts,
-               int32_t* __restrict__ status_word) {
+               int64_t cap_q, int64_t cap_f, int32_t* __restrict__ chunk_slot, int32_t* __restrict__ n_chunks_out,
+               int32_t* __restrict__ counts, int32_t* __restrict__ status_word) {
     __shared__ int64_t wave_q[kPlanThreads / 64], wave_f[kPlanThreads / 64];
     __shared__ int64_t carry_q_sh, carry_f_sh;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -50,7 +52,6 @@ kv_plan_kernel(const int32_t* __restrict__ chunk_offsets, int32_t n_seqs, const 
         carry_q_sh = 0;
         carry_f_sh = 0;
         *n_chunks_out = n_chunks;
-        *status_word = 0;          // the row kernel ORs its bits in
     }
     __syncthreads();
     for (int32_t c0 = 0; c0 < n_chunks; c0 += kPlanThreads) {
@@ -103,6 +104,8 @@ kv_plan_kernel(const int32_t* __restrict__ chunk_offsets, int32_t n_seqs, const 
         const int64_t q = carry_q_sh, f = carry_f_sh;
         counts[0] = q > 0x7fffffffll ? 0x7fffffff : (int32_t)q;
         counts[1] = f > 0x7fffffffll ? 0x7fffffff : (int32_t)f;
+        // a pool is too small exactly when its chunks list more rows than it holds
+        *status_word = (q > cap_q || f > cap_f) ? (int32_t)CWL_STATUS_CAPACITY : 0;
     }
 }
 
@@ -120,7 +123,7 @@ __device__ __forceinline__ int32_t code_of(float x, float inv) {
 __global__ void __launch_bounds__(256)
 kv_slot_kernel(int64_t n_rows, const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_len,
                const int32_t* __restrict__ chunk_slot, const int32_t* __restrict__ n_chunks_p, int64_t cap_q,
-               int64_t cap_f, int32_t* __restrict__ slot, int32_t* __restrict__ status_word) {
+               int64_t cap_f, int32_t* __restrict__ slot) {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= n_rows) return;
     // chunk of the row: the last chunk whose start is <= t (starts ascend in the chunker's table)
@@ -142,7 +145,96 @@ kv_slot_kernel(int64_t n_rows, const int32_t* __restrict__ chunk_start, const in
             } else if (idx < cap_f) {
                 my_slot = (int32_t)(-1 - idx);
             }
-            if (my_slot == INT32_MIN) atomicOr(status_word, (int32_t)CWL_STATUS_CAPACITY);
+        }
+    }
+    slot[t] = my_slot;
+}
+
+// Plan and slots in one launch, for tables of up to kFusedChunks chunks: every workgroup of 256 rows scans the
+// whole chunk list itself (a few hundred entries; starts, lengths and first pool rows stay in LDS) and then
+// searches its rows' chunks there, so a row waits for two round trips to memory instead of a launch boundary
+// and eight.  Workgroup 0 also writes the pool totals and the status word.
+constexpr int kFusedChunks = 4096;
+
+__global__ void __launch_bounds__(256)
+kv_plan_slot_kernel(int64_t n_rows, const int32_t* __restrict__ chunk_offsets, int32_t n_seqs,
+                    const int32_t* __restrict__ chunk_start, const int32_t* __restrict__ chunk_len,
+                    const int32_t* __restrict__ rank_idx, int32_t chunk_cap, int32_t k_keep, int64_t cap_q,
+                    int64_t cap_f, int32_t* __restrict__ slot, int32_t* __restrict__ counts,
+                    int32_t* __restrict__ status_word) {
+    __shared__ int32_t s_start[kFusedChunks], s_len[kFusedChunks], s_slot[kFusedChunks];
+    __shared__ int64_t wave_q[4], wave_f[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int32_t n_chunks = chunk_offsets[n_seqs];
+    if (n_chunks > chunk_cap) n_chunks = chunk_cap;
+    if (n_chunks < 0) n_chunks = 0;
+    int64_t carry_q = 0, carry_f = 0;              // the same in every thread
+    for (int32_t c0 = 0; c0 < n_chunks; c0 += 256) {
+        const int32_t c = c0 + tid;
+        int64_t lq = 0, lf = 0;
+        bool easy = false;
+        if (c < n_chunks) {
+            const int32_t k = rank_idx[c];
+            const int32_t len_raw = chunk_len[c];
+            s_start[c] = chunk_start[c];
+            s_len[c] = len_raw;
+            easy = k >= 0 && k < k_keep;
+            (easy ? lq : lf) = len_raw < 0 ? 0 : len_raw;
+        }
+        int64_t iq = lq, ifl = lf;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int64_t vq = cwl::shfl_up_i64(iq, off), vf = cwl::shfl_up_i64(ifl, off);
+            if (lane >= off) {
+                iq += vq;
+                ifl += vf;
+            }
+        }
+        if (lane == 63) {
+            wave_q[wave] = iq;
+            wave_f[wave] = ifl;
+        }
+        __syncthreads();
+        int64_t base_q = carry_q, base_f = carry_f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            if (w < wave) {
+                base_q += wave_q[w];
+                base_f += wave_f[w];
+            }
+            carry_q += wave_q[w];
+            carry_f += wave_f[w];
+        }
+        if (c < n_chunks) {
+            const int64_t first = easy ? base_q + iq - lq : base_f + ifl - lf;
+            s_slot[c] = easy ? (int32_t)first : (int32_t)(-1 - first);
+        }
+        __syncthreads();                           // the wavefront totals are rewritten by the next round
+    }
+    if (blockIdx.x == 0 && tid == 0) {
+        counts[0] = carry_q > 0x7fffffffll ? 0x7fffffff : (int32_t)carry_q;
+        counts[1] = carry_f > 0x7fffffffll ? 0x7fffffff : (int32_t)carry_f;
+        *status_word = (carry_q > cap_q || carry_f > cap_f) ? (int32_t)CWL_STATUS_CAPACITY : 0;
+    }
+    const int64_t t = (int64_t)blockIdx.x * 256 + tid;
+    if (t >= n_rows) return;
+    int32_t lo = 0, hi = n_chunks;
+    while (lo < hi) {
+        const int32_t mid = lo + (hi - lo) / 2;
+        if ((int64_t)s_start[mid] <= t) lo = mid + 1; else hi = mid;
+    }
+    const int32_t c = lo - 1;
+    int32_t my_slot = INT32_MIN;
+    if (c >= 0) {
+        const int64_t j = t - s_start[c];
+        if (j < s_len[c]) {
+            const int32_t cs = s_slot[c];
+            const int64_t idx = (cs >= 0 ? (int64_t)cs : -1 - (int64_t)cs) + j;
+            if (cs >= 0) {
+                if (idx < cap_q) my_slot = (int32_t)idx;
+            } else if (idx < cap_f) {
+                my_slot = (int32_t)(-1 - idx);
+            }
         }
     }
     slot[t] = my_slot;
@@ -297,13 +389,22 @@ extern "C" cwl_status cwl_kv_quantise_chunks(const void* kv, int64_t ld, int64_t
     int32_t* n_chunks_dev = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) +
                                                        cwl::align_up(sizeof(int32_t) * ((size_t)chunk_cap + 1), 256));
     cwl::prof_begin(CWL_PROF_KV, st);
-    kv_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, st>>>(chunk_offsets, n_seqs, chunk_len, rank_idx, chunk_cap,
-                                                            sh.k_keep, chunk_slot, n_chunks_dev, counts, status_word);
+    const unsigned row_blocks = (unsigned)((n_rows + 255) / 256);
+    if (chunk_cap <= kFusedChunks) {
+        kv_plan_slot_kernel<<<dim3(row_blocks > 0 ? row_blocks : 1), dim3(256), 0, st>>>(
+            n_rows, chunk_offsets, n_seqs, chunk_start, chunk_len, rank_idx, chunk_cap, sh.k_keep, cap_q, cap_f, slot,
+            counts, status_word);
+    } else {
+        kv_plan_kernel<<<dim3(1), dim3(kPlanThreads), 0, st>>>(chunk_offsets, n_seqs, chunk_len, rank_idx, chunk_cap,
+                                                                sh.k_keep, cap_q, cap_f, chunk_slot, n_chunks_dev,
+                                                                counts, status_word);
+        CWL_RETURN_IF_LAUNCH_FAILED();
+        if (n_rows > 0)
+            kv_slot_kernel<<<dim3(row_blocks), dim3(256), 0, st>>>(n_rows, chunk_start, chunk_len, chunk_slot,
+                                                                   n_chunks_dev, cap_q, cap_f, slot);
+    }
     CWL_RETURN_IF_LAUNCH_FAILED();
     if (n_rows > 0) {
-        kv_slot_kernel<<<dim3((unsigned)((n_rows + 255) / 256)), dim3(256), 0, st>>>(
-            n_rows, chunk_start, chunk_len, chunk_slot, n_chunks_dev, cap_q, cap_f, slot, status_word);
-        CWL_RETURN_IF_LAUNCH_FAILED();
         const int passes = (sh.width + 511) / 512;
         const int per_wave = passes >= 4 ? 4 : (passes >= 2 ? 2 : 1);
         const int32_t segs = (passes + per_wave - 1) / per_wave;

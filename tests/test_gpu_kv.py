@@ -144,6 +144,22 @@ def test_workload_size_on_the_chunkers_table():
     assert_cache_equal(cache, back, ref, nq, nf, kv, H, D)
 
 
+def test_table_of_more_than_4096_chunks():
+    """Above 4096 chunks the plan and the slots are two launches instead of one; same results, and the status
+    word says when a pool is too small on this path too."""
+    n, H, D = 12000, 2, 64
+    kv = make_kv(n, H * D, 33)
+    so, co, cs, cl, ri = W.random_chunk_table(3, [5000, 1, 6999], 1, 2, 4, 29)
+    assert len(cs) > 4096
+    cache, back, ref, nq, nf = compare(kv, H, D, 2, so, co, cs, cl, ri)
+    assert_cache_equal(cache, back, ref, nq, nf, kv, H, D)
+    sod, tab, rid = B.table_from_host(so, co, cs, cl, ri, DEV)
+    small = B.kv_quantise_chunks(kv, H, D, 2, tab, rid, cap_q=nq - 1, cap_f=nf)
+    torch.cuda.synchronize()
+    assert int(small["status_word"].item()) == B.STATUS_CAPACITY
+    assert small["counts"].cpu().tolist() == [nq, nf]
+
+
 def test_argument_errors():
     kv = make_kv(64, 128, 1)
     so, co, cs, cl, ri = W.random_chunk_table(1, [64], 4, 40, 3, 1)
