@@ -85,6 +85,15 @@ def test_bf16_shapes(n_seqs, seq_lens, d_in, d_out, ranks, w):
     assert same_bits(y1, y2)
 
 
+@pytest.mark.parametrize("n_seqs,seq_lens", [(1, [6000]), (1500, [4] * 1500), (2, [1, 2047])])
+def test_bf16_long_tables(n_seqs, seq_lens):
+    """Tables with thousands of chunks of one or two rows, and with more than a thousand sequences: the gate
+    kernel's look-ups at their deepest (every row a chunk start or a join)."""
+    y1, y2, y2s, ref = both_forms(n_seqs, seq_lens, 128, 72, [8, 16, 32, 64], 2, torch.bfloat16, 41, l_min=1, l_max=2)
+    assert rel_err(y2s, ref) <= TOL_BF16
+    assert same_bits(y1, y2)
+
+
 @pytest.mark.parametrize("d_in,ranks,side", [(512, [8, 16, 32, 64], False), (256, [0, 24, 100], True),
                                               (128, [40, 200], False)])
 def test_bf16_one_pass_shrink(d_in, ranks, side):
