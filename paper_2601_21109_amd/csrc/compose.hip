@@ -31,10 +31,11 @@ compose_scores_kernel(const float* __restrict__ entropy, const int32_t* __restri
     int64_t last = t0 + kCompTokens;
     if (last > n_rows) last = n_rows;
     for (int64_t i = origin + threadIdx.x; i < last; i += kCompThreads) ids_lds[i - origin] = ids[i];
-    __syncthreads();
     const int part = threadIdx.x % kCompParts;
     const int64_t t = t0 + threadIdx.x / kCompParts;
     const bool live = t < n_rows;                            // (every lane stays for the exchanges below)
+    // (the entropy and the sequence search are asked for while the ids are on their way into LDS)
+    const float h = (live && part == 0) ? entropy[t] : 0.0f;
     // sequence: last b with seq_offsets[b] <= t
     int32_t b = -1;
     if (live) {
@@ -46,6 +47,7 @@ compose_scores_kernel(const float* __restrict__ entropy, const int32_t* __restri
         b = lo - 1;
         if (b >= 0 && t >= (int64_t)seq_offsets[b + 1]) b = -1;
     }
+    __syncthreads();
     int64_t j = 0;
     int32_t found = 0;
     if (b >= 0) {
@@ -56,21 +58,27 @@ compose_scores_kernel(const float* __restrict__ entropy, const int32_t* __restri
             if (jlo < n - 1) jlo = n - 1;
             const int32_t* cur = ids_lds + (t - origin);     // cur[-i] = id at position j - i
             const int32_t* seq0 = ids_lds + (base - origin); // seq0[jp] = id at position jp
-            const int32_t cur0 = cur[0];
+            // the n-gram's last three ids (fewer for shorter n-grams) are compared without a branch, the rest
+            // only where those match: with a small alphabet a test of the last id alone sent some lane of every
+            // wavefront into the slow path at nearly every position
+            const int32_t n_fast = n < 3 ? n : 3;
+            const int32_t cur0 = cur[0], cur1 = n_fast > 1 ? cur[-1] : 0, cur2 = n_fast > 2 ? cur[-2] : 0;
             for (int64_t jp0 = jlo + part; jp0 < j && !found; jp0 += kCompParts * kCompRound) {
-                int32_t last_id[kCompRound];
+                int32_t id0[kCompRound], id1[kCompRound], id2[kCompRound];
 #pragma unroll
                 for (int u = 0; u < kCompRound; ++u) {
                     int64_t jp = jp0 + (int64_t)u * kCompParts;
                     if (jp > j - 1) jp = j - 1;               // in bounds; its answer is dropped below
-                    last_id[u] = seq0[jp];
+                    id0[u] = seq0[jp];
+                    id1[u] = n_fast > 1 ? seq0[jp - 1] : 0;
+                    id2[u] = n_fast > 2 ? seq0[jp - 2] : 0;
                 }
 #pragma unroll
                 for (int u = 0; u < kCompRound; ++u) {
                     const int64_t jp = jp0 + (int64_t)u * kCompParts;
-                    if (jp < j && last_id[u] == cur0) {
+                    if (jp < j && id0[u] == cur0 && id1[u] == cur1 && id2[u] == cur2) {
                         bool same = true;
-                        for (int32_t i = 1; i < n; ++i)
+                        for (int32_t i = 3; i < n; ++i)
                             if (seq0[jp - i] != cur[-i]) { same = false; break; }
                         if (same) found = 1;
                     }
@@ -81,7 +89,7 @@ compose_scores_kernel(const float* __restrict__ entropy, const int32_t* __restri
     found |= __shfl_xor(found, 1);
     found |= __shfl_xor(found, 2);
     if (!live || part != 0) return;
-    float s = w_entropy * entropy[t];
+    float s = w_entropy * h;
     int32_t is_new = 0;
     if (b >= 0) {
         is_new = found ? 0 : 1;
